@@ -1,0 +1,228 @@
+"""CPU oracle for the verify -> select -> draft path of Vegas.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this file; the
+product path (the HIP library and its binding) never does, and this file imports nothing
+from the product.  It is a plain float64 NumPy implementation of the *definitions*:
+
+  * attention                         -- Eq. 1 (Sec. 2.1), softmax(q K^T / sqrt(d)) V
+  * verification of gamma+1 tokens in one full-attention pass over the whole cache
+                                      -- Sec. 2.3; causal masking as in Sec. 4 ("after causal
+                                         or local masking")
+  * criticality of prefix entries     -- Eq. 2 (all gamma+1 rows, all query heads) and Eq. 3
+                                         (first draft row + bonus row), Sec. 3.2-3.3, with the
+                                         attention *weights* as the metric (App. B) and the
+                                         row/head averaging of Sec. 3.3's last paragraph
+  * top-k selection                   -- the argmax of Eq. 2 / Eq. 3, here over unions of
+                                         16-token KV pages; "remaining tokens are kept"
+                                         (Sec. 3.2, last sentence) becomes the forced tail pages
+  * sparse drafting                   -- Sec. 2.2 (attention over the selected entries only),
+                                         realised as paged attention over the selected page
+                                         list (Sec. 4, App. D)
+
+No tiling, no online softmax, no reordering: gather the sequence's keys and values through
+the page table, form the logit matrix with one matmul, mask, softmax, one more matmul.
+
+Readings taken where the paper is silent (each is also listed in the design notes):
+  * the gamma+1 verify tokens' own K/V are the last gamma+1 entries of the cache, seq_lens
+    counts them, and row t (0-based) sees keys 0 .. n-G+t (bottom-right aligned causal mask);
+  * a page's score is the SUM of its member tokens' weights (this makes top-k of page scores
+    the exact argmax of Eq. 2 restricted to unions of pages), then the MEAN over the collected
+    rows and over all query heads (so the scores of one sequence add up to 1);
+  * the pages that overlap the last gamma+1 token positions are always selected and count
+    towards the budget; k = min(ceil(budget/16), number of pages), raised to the number of
+    forced pages if smaller; ties go to the lower logical page index;
+  * a row with no visible key (only possible when seq_len < gamma+1) outputs 0 and
+    contributes no weight.
+
+Pins (tests/test_oracle_*.py): closed forms for uniform weights, one-hot dominance, the
+library routines torch.nn.functional.scaled_dot_product_attention and scipy.special
+(softmax, logsumexp) on special cases, exhaustive subset search for the argmax of Eq. 2 on
+tiny inputs, sum-to-one invariants, page-permutation invariance, budget >= context.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+PAGE = 16
+
+COLLECT_NONE = 0
+COLLECT_ALL_ROWS = 1      # Eq. 2
+COLLECT_FIRST_LAST = 2    # Eq. 3
+
+
+def decode_bf16(bits: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> float64, exactly."""
+    b = np.asarray(bits)
+    if b.dtype != np.uint16:
+        raise TypeError("bf16 tensors are passed as uint16 bit patterns")
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def gather_sequence(cache_bits: np.ndarray, pages: np.ndarray, n_tokens: int, kv_head: int) -> np.ndarray:
+    """Tokens 0..n_tokens-1 of one sequence for one KV head as float64 [n_tokens, D].
+
+    Token i lives in physical page pages[i // 16], slot i % 16 of the NHD cache
+    [num_pages, 16, H_kv, D] (App. D)."""
+    nblk = (n_tokens + PAGE - 1) // PAGE
+    phys = np.asarray(pages[:nblk], dtype=np.int64)
+    x = cache_bits[phys, :, kv_head, :]                    # [nblk, 16, D]
+    x = x.reshape(nblk * PAGE, -1)[:n_tokens]
+    return decode_bf16(x)
+
+
+def collected_rows(num_queries: int, collect_rows: int) -> Tuple[int, ...]:
+    """Row set R of Eq. 2 (all rows) or Eq. 3 (first draft row and bonus row)."""
+    if collect_rows == COLLECT_ALL_ROWS:
+        return tuple(range(num_queries))
+    if collect_rows == COLLECT_FIRST_LAST:
+        return tuple(sorted({0, num_queries - 1}))
+    return ()
+
+
+def attention_weights(q_rows: np.ndarray, keys: np.ndarray, scale: float,
+                      visible: np.ndarray) -> np.ndarray:
+    """softmax(scale * q K^T) restricted to visible keys (Eq. 1's weights).
+
+    q_rows [R, D], keys [n, D], visible bool [R, n].  Rows with no visible key are all 0."""
+    s = (q_rows @ keys.T) * scale
+    s = np.where(visible, s, -np.inf)
+    m = np.max(s, axis=1, keepdims=True)
+    m = np.where(np.isfinite(m), m, 0.0)
+    e = np.where(visible, np.exp(s - m), 0.0)
+    z = np.sum(e, axis=1, keepdims=True)
+    return np.divide(e, z, out=np.zeros_like(e), where=z > 0)
+
+
+def verify_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
+                     block_table: np.ndarray, seq_lens: np.ndarray, scale: float,
+                     collect_rows: int = COLLECT_ALL_ROWS):
+    """Full attention of the G = gamma+1 verify rows over the paged cache + page criticality.
+
+    q uint16 [B, G, H_q, D]; caches uint16 [P, 16, H_kv, D]; block_table int32 [B, max_blocks];
+    seq_lens int32 [B].  Returns (out float64 [B, G, H_q, D], block_scores float64 [B, max_blocks]).
+    block_scores[b, j] = 1/(|R| H_q) * sum_{t in R} sum_h sum_{i in page j} w[t, h, i]; entries
+    j >= ceil(n_b/16) are 0.  With COLLECT_NONE the scores are all 0."""
+    B, G, Hq, D = q.shape
+    Hkv = k_cache.shape[2]
+    g = Hq // Hkv
+    max_blocks = block_table.shape[1]
+    qf = decode_bf16(q)
+    out = np.zeros((B, G, Hq, D), dtype=np.float64)
+    scores = np.zeros((B, max_blocks), dtype=np.float64)
+    R = collected_rows(G, collect_rows)
+    for b in range(B):
+        n = int(seq_lens[b])
+        if n <= 0:
+            continue
+        nblk = (n + PAGE - 1) // PAGE
+        pos = np.arange(n)
+        # row t of the G verify tokens sees keys 0 .. n-G+t
+        last_visible = n - G + np.arange(G)
+        vis_t = pos[None, :] <= last_visible[:, None]                     # [G, n]
+        for hk in range(Hkv):
+            K = gather_sequence(k_cache, block_table[b], n, hk)
+            V = gather_sequence(v_cache, block_table[b], n, hk)
+            for j in range(g):
+                h = hk * g + j
+                w = attention_weights(qf[b, :, h, :], K, scale, vis_t)     # [G, n]
+                out[b, :, h, :] = w @ V
+                if R:
+                    wr = w[list(R)].sum(axis=0)                            # [n]
+                    padded = np.zeros(nblk * PAGE, dtype=np.float64)
+                    padded[:n] = wr
+                    scores[b, :nblk] += padded.reshape(nblk, PAGE).sum(axis=1)
+        if R:
+            scores[b] /= (len(R) * Hq)
+    return out, scores
+
+
+def forced_pages(n: int, num_queries: int) -> np.ndarray:
+    """Logical pages that overlap the last num_queries token positions [n-G, n)."""
+    if n <= 0:
+        return np.zeros(0, dtype=np.int64)
+    first = max(n - num_queries, 0) // PAGE
+    last = (n - 1) // PAGE
+    return np.arange(first, last + 1, dtype=np.int64)
+
+
+def select_logical(scores_row: np.ndarray, n: int, num_queries: int, budget_tokens: int) -> np.ndarray:
+    """Selected logical page ids (ascending) of one sequence.
+
+    k = min(ceil(budget/16), nblk), raised to the number of forced pages; forced pages first,
+    then the best remaining pages by (score descending, logical index ascending)."""
+    if n <= 0:
+        return np.zeros(0, dtype=np.int64)
+    nblk = (n + PAGE - 1) // PAGE
+    F = forced_pages(n, num_queries)
+    k = min((max(int(budget_tokens), 0) + PAGE - 1) // PAGE, nblk)
+    k = max(k, F.size)
+    rest = np.setdiff1d(np.arange(nblk, dtype=np.int64), F)
+    s = np.asarray(scores_row[:nblk])[rest]
+    order = np.argsort(-s, kind="stable")          # descending score; equal scores keep ascending index
+    chosen = rest[order[:k - F.size]]
+    return np.sort(np.concatenate([F, chosen]))
+
+
+def select_blocks(block_scores: np.ndarray, block_table: np.ndarray, seq_lens: np.ndarray,
+                  num_queries: int, budget_tokens: int, max_sel_blocks: int,
+                  budgets: Optional[Sequence[int]] = None):
+    """Top-k pages per sequence -> (sel_table int32 [B, max_sel_blocks] of PHYSICAL page ids in
+    ascending logical order, -1 padded; sel_seq_lens int32 [B] = tokens covered by the selection;
+    list of the logical ids per sequence)."""
+    B = block_table.shape[0]
+    sel_table = np.full((B, max_sel_blocks), -1, dtype=np.int32)
+    sel_seq_lens = np.zeros(B, dtype=np.int32)
+    logical = []
+    for b in range(B):
+        n = int(seq_lens[b])
+        bud = int(budgets[b]) if budgets is not None else int(budget_tokens)
+        ids = select_logical(block_scores[b], n, num_queries, bud)
+        if ids.size > max_sel_blocks:
+            raise ValueError("max_sel_blocks too small")
+        logical.append(ids)
+        if ids.size == 0:
+            continue
+        sel_table[b, :ids.size] = block_table[b, ids]
+        nblk = (n + PAGE - 1) // PAGE
+        tail = n - PAGE * (nblk - 1)               # tokens in the last logical page (always selected)
+        sel_seq_lens[b] = PAGE * (ids.size - 1) + tail
+    return sel_table, sel_seq_lens, logical
+
+
+def draft_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
+                    sel_table: np.ndarray, sel_seq_lens: np.ndarray, scale: float) -> np.ndarray:
+    """One draft query per sequence attends over exactly the tokens of the selected pages.
+
+    q uint16 [B, H_q, D]; sel_table int32 [B, max_sel_blocks] physical page ids; sel_seq_lens[b]
+    tokens are valid (only the last listed page may be partial).  No causal mask: the draft token
+    is newer than everything cached.  Returns float64 [B, H_q, D]."""
+    B, Hq, D = q.shape
+    Hkv = k_cache.shape[2]
+    g = Hq // Hkv
+    qf = decode_bf16(q)
+    out = np.zeros((B, Hq, D), dtype=np.float64)
+    for b in range(B):
+        n = int(sel_seq_lens[b])
+        if n <= 0:
+            continue
+        vis = np.ones((g, n), dtype=bool)
+        for hk in range(Hkv):
+            K = gather_sequence(k_cache, sel_table[b], n, hk)
+            V = gather_sequence(v_cache, sel_table[b], n, hk)
+            w = attention_weights(qf[b, hk * g:(hk + 1) * g, :], K, scale, vis)
+            out[b, hk * g:(hk + 1) * g, :] = w @ V
+    return out
+
+
+def decoding_iteration(q_verify, q_draft, k_cache, v_cache, block_table, seq_lens, scale,
+                       budget_tokens, max_sel_blocks, collect_rows=COLLECT_ALL_ROWS, budgets=None):
+    """verify -> select -> one draft call per draft query slab (Sec. 2.3, Sec. 3.1)."""
+    G = q_verify.shape[1]
+    out_v, scores = verify_attention(q_verify, k_cache, v_cache, block_table, seq_lens, scale, collect_rows)
+    sel_table, sel_seq_lens, logical = select_blocks(scores, block_table, seq_lens, G, budget_tokens,
+                                                     max_sel_blocks, budgets)
+    outs_d = [draft_attention(q_draft[s], k_cache, v_cache, sel_table, sel_seq_lens, scale)
+              for s in range(q_draft.shape[0])]
+    return out_v, scores, sel_table, sel_seq_lens, logical, outs_d

@@ -1,0 +1,389 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, independent of the oracle's code.
+
+Each test is chosen so that one plausible class of mistake in oracle/vegas_oracle.py fails it:
+scale or transposition (library attention), mask alignment (closed form + square-causal library
+run), page/slot/head index arithmetic (hand-placed caches, page permutation), normalisation of the
+scores (sum to one, closed form), the argmax of Eq. 2 (exhaustive subset search), tail and tie
+rules (hand-worked golden cases).
+"""
+import itertools
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import vegas_oracle as O
+from paper_2602_07223_amd import synth
+
+PAGE = 16
+
+
+def bf16_round(x):
+    return synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))).astype(np.float64)
+
+
+def place_cache(dense, table, num_pages, Hkv, D, fill=np.nan):
+    """Write dense [n, Hkv, D] (float) into an NHD paged cache by the layout's definition (App. D):
+    token i -> page table[i // 16], slot i % 16.  Unused slots hold `fill`."""
+    cache = np.full((num_pages, PAGE, Hkv, D), fill, dtype=np.float32)
+    for i in range(dense.shape[0]):
+        cache[table[i // PAGE], i % PAGE] = dense[i]
+    return synth.f32_to_bf16_bits(cache)
+
+
+def small_case(seed, n, G, Hq, Hkv, D=32, shuffle=True, scale_q=1.0):
+    rng = np.random.default_rng(seed)
+    nblk = (n + PAGE - 1) // PAGE
+    num_pages = nblk + 2
+    table = rng.permutation(num_pages)[:nblk].astype(np.int32) if shuffle else np.arange(nblk, dtype=np.int32)
+    Kd = bf16_round(rng.standard_normal((n, Hkv, D)))
+    Vd = bf16_round(rng.standard_normal((n, Hkv, D)))
+    Q = bf16_round(rng.standard_normal((1, G, Hq, D)) * scale_q)
+    k_cache = place_cache(Kd, table, num_pages, Hkv, D)
+    v_cache = place_cache(Vd, table, num_pages, Hkv, D)
+    return dict(Q=Q, Kd=Kd, Vd=Vd, q=synth.f32_to_bf16_bits(Q), k_cache=k_cache, v_cache=v_cache,
+                block_table=table[None, :].copy(), seq_lens=np.array([n], dtype=np.int32),
+                scale=1.0 / math.sqrt(D), nblk=nblk)
+
+
+# ----------------------------------------------------------------------------------------------
+# Eq. 1 against library attention
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,Hq,Hkv", [(37, 4, 2), (64, 2, 2), (5, 6, 2)])
+def test_single_query_matches_library_attention(n, Hq, Hkv):
+    """G = 1: the verify row sees every key, so the result is textbook attention (Eq. 1); the GQA
+    head mapping is the library's (enable_gqa)."""
+    c = small_case(11, n, 1, Hq, Hkv)
+    out, _ = O.verify_attention(c["q"], c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"], c["scale"])
+    q = torch.from_numpy(c["Q"][0]).permute(1, 0, 2)[None]            # [1, Hq, 1, D]
+    k = torch.from_numpy(c["Kd"]).permute(1, 0, 2)[None]              # [1, Hkv, n, D]
+    v = torch.from_numpy(c["Vd"]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, enable_gqa=True)   # scale 1/sqrt(D)
+    ref = ref[0].permute(1, 0, 2).numpy()                             # [1, Hq, D]
+    np.testing.assert_allclose(out[0], ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("n,G", [(48, 5), (33, 7), (16, 16)])
+def test_verify_rows_are_the_last_rows_of_square_causal_attention(n, G):
+    """The G verify tokens are the last G tokens of the sequence: their rows must equal the last G
+    rows of ordinary causal self-attention over all n tokens (the library's square is_causal mask
+    fixes the alignment, nothing is retyped here)."""
+    Hq = Hkv = 2
+    c = small_case(5, n, G, Hq, Hkv)
+    rng = np.random.default_rng(99)
+    q_all = rng.standard_normal((n, Hq, c["Q"].shape[-1]))
+    q_all[n - G:] = c["Q"][0]
+    q = torch.from_numpy(q_all).permute(1, 0, 2)[None]
+    k = torch.from_numpy(c["Kd"]).permute(1, 0, 2)[None]
+    v = torch.from_numpy(c["Vd"]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0]  # [H, n, D]
+    ref = ref.permute(1, 0, 2).numpy()[n - G:]
+    out, _ = O.verify_attention(c["q"], c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"], c["scale"])
+    np.testing.assert_allclose(out[0], ref, rtol=0, atol=1e-12)
+
+
+def test_weights_match_scipy_softmax_and_logsumexp():
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((3, 16))
+    K = rng.standard_normal((40, 16))
+    vis = np.ones((3, 40), dtype=bool)
+    w = O.attention_weights(q, K, 0.25, vis)
+    s = 0.25 * np.einsum("rd,nd->rn", q, K)
+    np.testing.assert_allclose(w, scipy.special.softmax(s, axis=1), atol=1e-14)
+    np.testing.assert_allclose(np.log(w), s - scipy.special.logsumexp(s, axis=1, keepdims=True), atol=1e-12)
+    np.testing.assert_allclose(w.sum(axis=1), 1.0, atol=1e-13)
+
+
+def test_softmax_is_monotone_per_head():
+    """App. B: within one query head, ranking by weights equals ranking by logits."""
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((1, 16))
+    K = rng.standard_normal((50, 16))
+    w = O.attention_weights(q, K, 0.25, np.ones((1, 50), dtype=bool))[0]
+    logits = K @ q[0]
+    assert np.array_equal(np.argsort(-w, kind="stable"), np.argsort(-logits, kind="stable"))
+
+
+# ----------------------------------------------------------------------------------------------
+# closed forms
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,G,collect", [(53, 5, 1), (53, 5, 2), (32, 7, 1), (20, 3, 2), (6, 6, 1)])
+def test_uniform_weights_closed_form(n, G, collect):
+    """q = 0 makes every visible key equally weighted: row t outputs the mean of the first n-G+t+1
+    values and page j's score is mean_t |page j intersect [0, n-G+t]| / (n-G+t+1)."""
+    Hq, Hkv, D = 4, 2, 32
+    c = small_case(21, n, G, Hq, Hkv, D)
+    q0 = np.zeros_like(c["q"])
+    out, scores = O.verify_attention(q0, c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"],
+                                     c["scale"], collect)
+    g = Hq // Hkv
+    for t in range(G):
+        vis = n - G + t + 1
+        for h in range(Hq):
+            np.testing.assert_allclose(out[0, t, h], c["Vd"][:vis, h // g].mean(axis=0), atol=1e-13)
+    rows = range(G) if collect == 1 else sorted({0, G - 1})
+    nblk = c["nblk"]
+    expect = []
+    for j in range(nblk):
+        acc = Fraction(0)
+        for t in rows:
+            vis = n - G + t + 1
+            inside = max(0, min(vis, PAGE * (j + 1)) - PAGE * j)
+            acc += Fraction(inside, vis)
+        expect.append(float(acc / len(list(rows))))
+    np.testing.assert_allclose(scores[0, :nblk], expect, atol=1e-14)
+
+
+def test_one_hot_key_takes_all_the_weight():
+    n, G, Hq, Hkv, D = 61, 4, 4, 2, 32
+    c = small_case(8, n, G, Hq, Hkv, D)
+    star = 23
+    u = np.zeros(D); u[3] = 1.0
+    Kd = c["Kd"] * 0.01
+    Kd[star] = 64.0 * u                      # logit 64 * 8 / sqrt(32) ~ 90 for q = 8u
+    Q = np.zeros((1, G, Hq, D)); Q[..., 3] = 8.0
+    k_cache = place_cache(Kd, c["block_table"][0], c["k_cache"].shape[0], Hkv, D)
+    out, scores = O.verify_attention(synth.f32_to_bf16_bits(Q), k_cache, c["v_cache"], c["block_table"],
+                                     c["seq_lens"], c["scale"])
+    g = Hq // Hkv
+    for h in range(Hq):
+        np.testing.assert_allclose(out[0, :, h], np.broadcast_to(c["Vd"][star, h // g], (G, D)), atol=1e-9)
+    assert abs(scores[0, star // PAGE] - 1.0) < 1e-9
+    assert abs(scores[0].sum() - 1.0) < 1e-12
+
+
+# ----------------------------------------------------------------------------------------------
+# invariants
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("collect", [1, 2])
+def test_scores_sum_to_one_and_are_nonnegative(collect):
+    L = synth.make_random_case(5, batch=3, num_q_heads=8, num_kv_heads=2, num_queries=5,
+                               seq_lens=[100, 17, 64], head_dim=32, outliers=2)
+    _, scores = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                                   L.softmax_scale, collect)
+    assert np.all(np.isfinite(scores)) and np.all(scores >= 0)
+    np.testing.assert_allclose(scores.sum(axis=1), 1.0, atol=1e-12)
+    for b, n in enumerate(L.seq_lens):
+        assert np.all(scores[b, (n + PAGE - 1) // PAGE:] == 0)
+
+
+def test_eq3_equals_eq2_when_gamma_is_one():
+    L = synth.make_random_case(6, batch=2, num_q_heads=4, num_kv_heads=2, num_queries=2,
+                               seq_lens=[70, 33], head_dim=32)
+    a = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 1)[1]
+    b = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 2)[1]
+    assert np.array_equal(a, b)
+
+
+def test_eq3_uses_first_and_last_row_only():
+    """Changing a middle verify query must not move Eq. 3's scores, changing the first or last must."""
+    L = synth.make_random_case(7, batch=1, num_q_heads=4, num_kv_heads=2, num_queries=5,
+                               seq_lens=[90], head_dim=32)
+    base = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 2)[1]
+    for t, moves in [(0, True), (2, False), (4, True)]:
+        q = L.q_verify.copy()
+        q[0, t] = L.q_verify[0, (t + 1) % 5]
+        s = O.verify_attention(q, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 2)[1]
+        assert (not np.array_equal(s, base)) == moves
+
+
+def test_physical_page_permutation_changes_nothing():
+    L = synth.make_random_case(9, batch=2, num_q_heads=4, num_kv_heads=2, num_queries=3,
+                               seq_lens=[75, 40], head_dim=32, shuffle=False, spare_pages=0, poison=False)
+    rng = np.random.default_rng(1)
+    P = L.k_cache.shape[0]
+    perm = rng.permutation(P)                    # new physical id of old page p is perm[p]
+    k2 = np.empty_like(L.k_cache); v2 = np.empty_like(L.v_cache)
+    k2[perm] = L.k_cache; v2[perm] = L.v_cache
+    bt2 = np.where(L.block_table >= 0, perm[np.clip(L.block_table, 0, None)], -1).astype(np.int32)
+    r1 = O.decoding_iteration(L.q_verify, L.q_draft, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                              L.softmax_scale, 32, 8)
+    r2 = O.decoding_iteration(L.q_verify, L.q_draft, k2, v2, bt2, L.seq_lens, L.softmax_scale, 32, 8)
+    assert np.array_equal(r1[0], r2[0]) and np.array_equal(r1[1], r2[1])
+    assert np.array_equal(r1[3], r2[3])
+    for a, b in zip(r1[4], r2[4]):
+        assert np.array_equal(a, b)
+    for a, b in zip(r1[5], r2[5]):
+        assert np.array_equal(a, b)
+    assert np.array_equal(np.where(r1[2] >= 0, perm[np.clip(r1[2], 0, None)], -1), r2[2])
+
+
+def test_poison_never_reaches_an_output():
+    L = synth.make_random_case(10, batch=2, num_q_heads=4, num_kv_heads=2, num_queries=4,
+                               seq_lens=[45, 19], head_dim=32, poison=True, spare_pages=4)
+    r = O.decoding_iteration(L.q_verify, L.q_draft, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                             L.softmax_scale, 32, 8)
+    assert np.all(np.isfinite(r[0])) and np.all(np.isfinite(r[1]))
+    for o in r[5]:
+        assert np.all(np.isfinite(o))
+
+
+# ----------------------------------------------------------------------------------------------
+# brute force on tiny inputs: weights by scalar loops, Eq. 2's argmax by subset enumeration
+# ----------------------------------------------------------------------------------------------
+
+def loop_weights(Q, Kd, scale, n, G, t, h, g):
+    """Scalar-loop softmax weights of verify row t, head h over keys 0..n-G+t."""
+    vis = n - G + t + 1
+    s = [scale * sum(float(Q[0, t, h, d]) * float(Kd[i, h // g, d]) for d in range(Kd.shape[-1]))
+         for i in range(vis)]
+    m = max(s)
+    e = [math.exp(x - m) for x in s]
+    z = math.fsum(e)
+    return [x / z for x in e] + [0.0] * (n - vis)
+
+
+@pytest.mark.parametrize("n,G,budget,collect", [(64, 3, 32, 1), (57, 2, 32, 1), (50, 4, 48, 2), (23, 5, 16, 1)])
+def test_selection_is_the_exhaustive_argmax_of_eq2(n, G, budget, collect):
+    Hq, Hkv, D = 2, 1, 8
+    c = small_case(31 + n, n, G, Hq, Hkv, D, scale_q=3.0)
+    out, scores = O.verify_attention(c["q"], c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"],
+                                     c["scale"], collect)
+    rows = list(range(G)) if collect == 1 else sorted({0, G - 1})
+    W = {(t, h): loop_weights(c["Q"], c["Kd"], c["scale"], n, G, t, h, Hq // Hkv) for t in rows for h in range(Hq)}
+    nblk = c["nblk"]
+    page_mass = [math.fsum(W[(t, h)][i] for t in rows for h in range(Hq)
+                           for i in range(PAGE * j, min(n, PAGE * (j + 1)))) for j in range(nblk)]
+    np.testing.assert_allclose(scores[0, :nblk], np.array(page_mass) / (len(rows) * Hq), atol=1e-13)
+    # outputs by loops too
+    for t in rows:
+        for h in range(Hq):
+            o = [math.fsum(W[(t, h)][i] * float(c["Vd"][i, 0, d]) for i in range(n)) for d in range(D)]
+            np.testing.assert_allclose(out[0, t, h], o, atol=1e-12)
+    # exhaustive search over all page subsets of size k that contain the forced tail pages
+    forced = set(range(max(n - G, 0) // PAGE, (n - 1) // PAGE + 1))
+    k = max(min(-(-budget // PAGE), nblk), len(forced))
+    best, best_set = -1.0, None
+    for T in itertools.combinations(range(nblk), k):
+        if not forced.issubset(T):
+            continue
+        val = math.fsum(page_mass[j] for j in T)
+        if val > best + 1e-15:
+            best, best_set = val, T
+    ids = O.select_logical(scores[0], n, G, budget)
+    assert tuple(ids) == tuple(best_set)
+
+
+# ----------------------------------------------------------------------------------------------
+# selection rules
+# ----------------------------------------------------------------------------------------------
+
+def test_golden_selection_cases(golden_dir):
+    with open(os.path.join(golden_dir, "select_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    assert len(cases) >= 8
+    for c in cases:
+        scores = np.array([c["scores"]], dtype=np.float64)
+        nblk = len(c["scores"])
+        table = (np.arange(nblk, dtype=np.int32)[::-1] * 3 + 7)[None, :].copy()     # distinct physical ids
+        sel, ssl, logical = O.select_blocks(scores, table, np.array([c["seq_len"]], dtype=np.int32),
+                                            c["num_queries"], c["budget"], max_sel_blocks=nblk + 2)
+        assert list(logical[0]) == c["logical"], c["name"]
+        assert int(ssl[0]) == c["sel_seq_len"], c["name"]
+        k = len(c["logical"])
+        assert list(sel[0, :k]) == [int(table[0, j]) for j in c["logical"]], c["name"]
+        assert np.all(sel[0, k:] == -1), c["name"]
+
+
+def test_selection_matches_numpy_partition_on_distinct_scores():
+    rng = np.random.default_rng(12)
+    for trial in range(20):
+        nblk = int(rng.integers(3, 400))
+        n = PAGE * nblk - int(rng.integers(0, PAGE))
+        G = int(rng.integers(1, 8))
+        scores = rng.random(nblk).astype(np.float32)
+        assert np.unique(scores).size == nblk
+        budget = int(rng.integers(1, PAGE * nblk + 40))
+        ids = O.select_logical(scores, n, G, budget)
+        forced = O.forced_pages(n, G)
+        k = max(min(-(-budget // PAGE), nblk), forced.size)
+        assert ids.size == k and np.all(np.diff(ids) > 0)
+        assert np.isin(forced, ids).all()
+        free = np.setdiff1d(ids, forced)
+        others = np.setdiff1d(np.arange(nblk), forced)
+        if free.size:
+            kth = np.sort(scores[others])[::-1][free.size - 1]
+            assert np.all(scores[free] >= kth)
+            assert np.all(scores[np.setdiff1d(others, free)] < kth)
+
+
+def test_planted_dominant_key_is_always_selected():
+    L = synth.make_layer(synth.scaled(synth.CONFIGS["ctx4k"], seq_len=1024, hitters=4, budget_tokens=128))
+    r = O.decoding_iteration(L.q_verify, L.q_draft, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                             L.softmax_scale, 128, 8)
+    logical = r[4][0]
+    assert np.isin(np.unique(L.hitters[0] // PAGE), logical).all()
+    assert np.isin(np.unique(L.sinks[0] // PAGE), logical).all()
+    assert logical.size == 8 and logical[-1] == 63
+
+
+# ----------------------------------------------------------------------------------------------
+# draft
+# ----------------------------------------------------------------------------------------------
+
+def test_full_budget_draft_equals_full_attention_and_last_verify_row():
+    L = synth.make_random_case(14, batch=2, num_q_heads=4, num_kv_heads=2, num_queries=4,
+                               seq_lens=[77, 48], head_dim=32)
+    out_v, scores = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale)
+    sel, ssl, logical = O.select_blocks(scores, L.block_table, L.seq_lens, 4, 10 ** 6, L.block_table.shape[1])
+    assert list(ssl) == list(L.seq_lens)
+    for b in range(2):
+        nb = (L.seq_lens[b] + PAGE - 1) // PAGE
+        assert np.array_equal(sel[b, :nb], L.block_table[b, :nb])
+    q_last = np.ascontiguousarray(L.q_verify[:, -1])           # the bonus row sees all n keys
+    out_d = O.draft_attention(q_last, L.k_cache, L.v_cache, sel, ssl, L.softmax_scale)
+    np.testing.assert_allclose(out_d, out_v[:, -1], atol=1e-13)
+
+
+def test_draft_over_hand_built_selection_matches_library_attention():
+    n, Hq, Hkv, D = 80, 4, 2, 32
+    c = small_case(17, n, 1, Hq, Hkv, D)
+    logical = [0, 2, 4]                                          # first page, a middle page, the tail
+    sel = np.full((1, 6), -1, dtype=np.int32)
+    sel[0, :3] = c["block_table"][0, logical]
+    ssl = np.array([48], dtype=np.int32)
+    out = O.draft_attention(c["q"][:, 0], c["k_cache"], c["v_cache"], sel, ssl, c["scale"])
+    tok = np.concatenate([np.arange(PAGE * j, PAGE * (j + 1)) for j in logical])
+    q = torch.from_numpy(c["Q"][0]).permute(1, 0, 2)[None]
+    k = torch.from_numpy(c["Kd"][tok]).permute(1, 0, 2)[None]
+    v = torch.from_numpy(c["Vd"][tok]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, enable_gqa=True)[0, :, 0].numpy()
+    np.testing.assert_allclose(out[0], ref, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------------
+# layout
+# ----------------------------------------------------------------------------------------------
+
+def test_layout_byte_arithmetic(golden_dir):
+    with open(os.path.join(golden_dir, "layout_arithmetic.json")) as f:
+        gold = json.load(f)
+    L = synth.make_layer(synth.scaled(synth.CONFIGS["ctx4k"], seq_len=64, hitters=0))
+    per_token = (L.k_cache[0, 0].nbytes + L.v_cache[0, 0].nbytes)
+    assert per_token == gold["kv_bytes_per_token_qwen3_8b"]["value"]
+    assert 2 * 8 * 64 * 2 == gold["kv_bytes_per_token_gpt_oss_20b"]["value"]
+    t = gold["kv_cache_total_gib"]
+    assert t["batch"] * t["context"] * t["layers"] * per_token == t["value"] * 2 ** 30
+    # NHD: one token's K for all heads is contiguous, consecutive slots of a page are adjacent
+    assert L.k_cache.strides == (16 * 8 * 128 * 2, 8 * 128 * 2, 128 * 2, 2)
+
+
+def test_degenerate_lengths():
+    """seq_len 0 -> zeros and an empty selection; seq_len < G -> rows without a visible key output 0."""
+    L = synth.make_random_case(15, batch=2, num_q_heads=2, num_kv_heads=1, num_queries=4,
+                               seq_lens=[0, 2], head_dim=32, spare_pages=1)
+    out, scores = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale)
+    assert np.all(out[0] == 0) and np.all(scores[0] == 0)
+    assert np.all(out[1, :2] == 0) and np.all(np.isfinite(out[1]))      # rows 0,1 see keys <= -2, -1
+    assert np.any(out[1, 2] != 0) and np.any(out[1, 3] != 0)
+    sel, ssl, logical = O.select_blocks(scores, L.block_table, L.seq_lens, 4, 64, 4)
+    assert ssl[0] == 0 and np.all(sel[0] == -1) and logical[0].size == 0
+    assert ssl[1] == 2 and sel[1, 0] == L.block_table[1, 0]
