@@ -1,0 +1,143 @@
+/*
+ * vegas.h -- C ABI of the MI355X (gfx950) verify -> select -> draft attention path of Vegas,
+ * self-speculative decoding with verification-guided sparse attention.
+ *
+ * One decoding iteration of the method (Sec. 2.3, Sec. 3.1, Fig. 1b) spends its attention time in
+ * three operations, which are the three calls below:
+ *   1. vegas_verify_attention  full attention of the gamma+1 verification tokens over the whole
+ *                              paged KV cache (Eq. 1), which as a by-product yields the criticality
+ *                              of every KV page (Eq. 2 / Eq. 3, weights as the metric, App. B);
+ *   2. vegas_select_blocks     top-k of those criticalities (the argmax of Eq. 2 / Eq. 3);
+ *   3. vegas_draft_attention   attention of one draft token over the selected pages only, done as
+ *                              paged attention whose page list is the selection (Sec. 4, App. D).
+ *
+ * Conventions shared by every call
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *     frees or synchronises: a call validates its arguments on the host, enqueues kernels on
+ *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and returns.
+ *   - bf16 tensors are raw 16-bit patterns.  All tensor pointers must be 16-byte aligned.
+ *   - KV cache layout is "NHD" (App. D): [num_pages, page_size, num_kv_heads, head_dim] with the
+ *     strides given in the descriptor (in elements; the head_dim stride is 1).  K and V are two
+ *     caches with the same strides.
+ *   - Query head h uses KV head h / (num_q_heads / num_kv_heads).
+ *   - Return value: VEGAS_OK (0) or a negative vegas_status.  Errors that the host can detect are
+ *     reported before anything is launched and leave every output untouched.  Page ids are clamped
+ *     into [0, num_pages) and lengths into [0, max_blocks*page_size] on the device, so a corrupt
+ *     table cannot fault; results are then unspecified.
+ *   - `workspace` is caller-owned device scratch of at least vegas_workspace_bytes(desc) bytes,
+ *     256-byte aligned.  Its contents are meaningless between calls; calls that share a workspace
+ *     must be ordered on one stream.
+ */
+#ifndef VEGAS_H
+#define VEGAS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vegas_status {
+  VEGAS_OK = 0,
+  VEGAS_ERR_NULL = -1,        /* a required pointer is NULL */
+  VEGAS_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent */
+  VEGAS_ERR_UNSUPPORTED = -3, /* a valid shape this build has no kernel for */
+  VEGAS_ERR_ALIGN = -4,       /* pointer or stride alignment */
+  VEGAS_ERR_WORKSPACE = -5,   /* workspace missing or too small */
+  VEGAS_ERR_LAUNCH = -6       /* the HIP runtime refused a launch */
+} vegas_status;
+
+/* Which verification rows contribute to the page criticality. */
+enum {
+  VEGAS_COLLECT_NONE = 0,       /* no scores; block_scores may be NULL */
+  VEGAS_COLLECT_ALL_ROWS = 1,   /* Eq. 2: all gamma+1 rows */
+  VEGAS_COLLECT_FIRST_LAST = 2  /* Eq. 3: first draft row and bonus row */
+};
+
+typedef struct vegas_desc {
+  int32_t batch;           /* B: sequences */
+  int32_t num_q_heads;     /* H_q */
+  int32_t num_kv_heads;    /* H_kv, divides H_q */
+  int32_t head_dim;        /* 128 */
+  int32_t page_size;       /* 16 tokens */
+  int32_t num_queries;     /* verify: G = gamma+1 rows per sequence; ignored by draft (1 row) */
+  int32_t max_blocks;      /* row stride of block_table and block_scores */
+  int32_t max_sel_blocks;  /* row stride of sel_table */
+  int32_t max_seq_len;     /* upper bound on every seq_lens[b] (and sel_seq_lens[b]); sizes the
+                              launch grid and the workspace; <= max_blocks*page_size */
+  int32_t collect_rows;    /* VEGAS_COLLECT_* */
+  int32_t kv_chunk_tokens; /* tokens of one sequence handled by one workgroup; 0 = choose */
+  float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
+  int64_t num_pages;       /* pages in each cache (device-side clamp of page ids) */
+  int64_t kv_page_stride;  /* elements between pages */
+  int64_t kv_token_stride; /* elements between slots of a page */
+  int64_t kv_head_stride;  /* elements between KV heads of a slot */
+  void*   ev_kernel_begin; /* optional hipEvent_t recorded on the stream right before ... */
+  void*   ev_kernel_end;   /* ... and right after the call's KV-streaming kernel (timing hook) */
+} vegas_desc;
+
+/* Bytes of device scratch that any of the three calls may need for this descriptor.
+ * Pure host function; returns 0 if the descriptor is invalid. */
+size_t vegas_workspace_bytes(const vegas_desc* desc);
+
+/*
+ * Verification pass (Sec. 2.3; Eq. 1; Eq. 2 / Eq. 3 with weights, App. B).
+ *   q            bf16 [B, G, H_q, D]       the gamma+1 verification tokens' queries
+ *   k_cache/v_cache bf16 NHD caches; the G tokens' own K/V are already the last G entries of each
+ *                sequence, and seq_lens counts them
+ *   block_table  int32 [B, max_blocks]     physical page of each logical page; entries at or
+ *                                          beyond ceil(seq_lens[b]/16) are never read
+ *   seq_lens     int32 [B]
+ *   out          bf16 [B, G, H_q, D]       row t attends to keys 0 .. seq_lens[b]-G+t (causal);
+ *                                          a row with no visible key gets 0
+ *   block_scores fp32 [B, max_blocks]      score[b][j] = 1/(|R| H_q) sum_{t in R} sum_h
+ *                                          sum_{i in page j} w[t,h,i]; R per desc->collect_rows;
+ *                                          entries j >= ceil(seq_lens[b]/16) are written as 0.
+ *                                          The KV cache is read exactly once.
+ */
+int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* block_table, const int32_t* seq_lens,
+                           void* out, float* block_scores,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Top-k page selection (Eq. 2's argmax over unions of pages; last sentence of Sec. 3.2 for the
+ * tail; Sec. 3.3's last paragraph for "highest scores").
+ *   k_b = min(ceil(budget_b/16), pages_b), raised to the number of forced pages; forced pages are
+ *   those overlapping token positions [seq_lens[b]-G, seq_lens[b]); the rest are the highest
+ *   scores, ties to the lower logical index.  budget_b = budgets[b] if budgets != NULL (per-sequence
+ *   budgets, App. C) else budget_tokens.
+ *   sel_table    int32 [B, max_sel_blocks]  PHYSICAL page ids in ascending logical order, then -1
+ *   sel_seq_lens int32 [B]                  tokens covered: 16*(k_b-1) + tokens in the last page
+ * Integer work: for identical fp32 scores the result is defined bit for bit.
+ * Returns VEGAS_ERR_SHAPE if max_sel_blocks < min(ceil(max budget/16), ceil(max_seq_len/16)) + 2
+ * cannot be guaranteed to hold k_b (the host checks budget_tokens only when budgets == NULL; with
+ * per-sequence budgets, k_b is clamped to max_sel_blocks on the device).
+ */
+int vegas_select_blocks(const vegas_desc* desc, const float* block_scores,
+                        const int32_t* block_table, const int32_t* seq_lens,
+                        int32_t budget_tokens, const int32_t* budgets,
+                        int32_t* sel_table, int32_t* sel_seq_lens,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Sparse draft attention (Sec. 2.2 last paragraph; Sec. 4: the selection is the page list).
+ *   q            bf16 [B, H_q, D]           one draft token per sequence
+ *   sel_table    int32 [B, max_sel_blocks]  as written by vegas_select_blocks
+ *   sel_seq_lens int32 [B]
+ *   out          bf16 [B, H_q, D]           softmax attention over exactly the first sel_seq_lens[b]
+ *                                          token slots of the listed pages; no causal mask; 0 if
+ *                                          sel_seq_lens[b] == 0
+ */
+int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* sel_table, const int32_t* sel_seq_lens,
+                          void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static, human-readable text for a vegas_status. */
+const char* vegas_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VEGAS_H */

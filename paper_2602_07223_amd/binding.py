@@ -1,0 +1,226 @@
+"""ctypes binding of libvegas.so: the three calls of include/vegas.h under the same names.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels.  Tensors may be
+torch tensors on the GPU (their ``data_ptr()`` is passed) or raw integer device addresses.  The
+library is loaded on first use and a missing build is an error, never a fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvegas.so")
+
+VEGAS_OK = 0
+VEGAS_ERR_NULL = -1
+VEGAS_ERR_SHAPE = -2
+VEGAS_ERR_UNSUPPORTED = -3
+VEGAS_ERR_ALIGN = -4
+VEGAS_ERR_WORKSPACE = -5
+VEGAS_ERR_LAUNCH = -6
+
+COLLECT_NONE = 0
+COLLECT_ALL_ROWS = 1
+COLLECT_FIRST_LAST = 2
+
+EXPORTS = ("vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
+           "vegas_draft_attention", "vegas_strerror")
+
+
+class VegasDesc(ctypes.Structure):
+    """Mirror of ``vegas_desc`` (include/vegas.h)."""
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("page_size", ctypes.c_int32),
+        ("num_queries", ctypes.c_int32),
+        ("max_blocks", ctypes.c_int32),
+        ("max_sel_blocks", ctypes.c_int32),
+        ("max_seq_len", ctypes.c_int32),
+        ("collect_rows", ctypes.c_int32),
+        ("kv_chunk_tokens", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float),
+        ("num_pages", ctypes.c_int64),
+        ("kv_page_stride", ctypes.c_int64),
+        ("kv_token_stride", ctypes.c_int64),
+        ("kv_head_stride", ctypes.c_int64),
+        ("ev_kernel_begin", ctypes.c_void_p),
+        ("ev_kernel_end", ctypes.c_void_p),
+    ]
+
+
+class VegasError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None):
+    """Load libvegas.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or os.environ.get("VEGAS_LIB", LIB_PATH)
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it first (python -m paper_2602_07223_amd.build, "
+                           "or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(path)
+    P = ctypes.c_void_p
+    D = ctypes.POINTER(VegasDesc)
+    lib.vegas_workspace_bytes.restype = ctypes.c_size_t
+    lib.vegas_workspace_bytes.argtypes = [D]
+    lib.vegas_verify_attention.restype = ctypes.c_int
+    lib.vegas_verify_attention.argtypes = [D, P, P, P, P, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_select_blocks.restype = ctypes.c_int
+    lib.vegas_select_blocks.argtypes = [D, P, P, P, ctypes.c_int32, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_draft_attention.restype = ctypes.c_int
+    lib.vegas_draft_attention.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_strerror.restype = ctypes.c_char_p
+    lib.vegas_strerror.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _nbytes(x) -> int:
+    return int(x.numel() * x.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def strerror(status: int) -> str:
+    return load_library().vegas_strerror(int(status)).decode()
+
+
+def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: int, max_blocks: int,
+              max_sel_blocks: int, max_seq_len: int, num_pages: int, softmax_scale: float,
+              collect_rows: int = COLLECT_ALL_ROWS, head_dim: int = 128, page_size: int = 16,
+              kv_chunk_tokens: int = 0, kv_page_stride: int = 0, kv_token_stride: int = 0,
+              kv_head_stride: int = 0) -> VegasDesc:
+    """Descriptor for a contiguous NHD cache unless strides are given (elements)."""
+    d = VegasDesc()
+    d.batch, d.num_q_heads, d.num_kv_heads = batch, num_q_heads, num_kv_heads
+    d.head_dim, d.page_size, d.num_queries = head_dim, page_size, num_queries
+    d.max_blocks, d.max_sel_blocks, d.max_seq_len = max_blocks, max_sel_blocks, max_seq_len
+    d.collect_rows, d.kv_chunk_tokens, d.softmax_scale = collect_rows, kv_chunk_tokens, softmax_scale
+    d.num_pages = num_pages
+    d.kv_head_stride = kv_head_stride or head_dim
+    d.kv_token_stride = kv_token_stride or num_kv_heads * head_dim
+    d.kv_page_stride = kv_page_stride or page_size * num_kv_heads * head_dim
+    d.ev_kernel_begin = None
+    d.ev_kernel_end = None
+    return d
+
+
+def vegas_workspace_bytes(desc: VegasDesc) -> int:
+    return int(load_library().vegas_workspace_bytes(ctypes.byref(desc)))
+
+
+def vegas_verify_attention(desc: VegasDesc, q, k_cache, v_cache, block_table, seq_lens, out, block_scores,
+                           workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    rc = load_library().vegas_verify_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                               _ptr(block_table), _ptr(seq_lens), _ptr(out), _ptr(block_scores),
+                                               _ptr(workspace), wb, _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_verify_attention")
+
+
+def vegas_select_blocks(desc: VegasDesc, block_scores, block_table, seq_lens, budget_tokens: int, sel_table,
+                        sel_seq_lens, budgets=None, workspace=None, stream=None) -> None:
+    wb = _nbytes(workspace) if workspace is not None and not isinstance(workspace, int) else 0
+    rc = load_library().vegas_select_blocks(ctypes.byref(desc), _ptr(block_scores), _ptr(block_table),
+                                            _ptr(seq_lens), int(budget_tokens), _ptr(budgets), _ptr(sel_table),
+                                            _ptr(sel_seq_lens), _ptr(workspace), wb, _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_select_blocks")
+
+
+def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace,
+                          stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    rc = load_library().vegas_draft_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                              _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out), _ptr(workspace),
+                                              wb, _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_draft_attention")
+
+
+# ---------------------------------------------------------------------------------------------
+# HIP events on a raw stream (timing plumbing for the benchmark's per-kernel hook)
+# ---------------------------------------------------------------------------------------------
+
+_hip = None
+
+
+def _hip_runtime():
+    global _hip
+    if _hip is None:
+        for name in ("libamdhip64.so", "libamdhip64.so.7", "libamdhip64.so.6", "/opt/rocm/lib/libamdhip64.so"):
+            try:
+                _hip = ctypes.CDLL(name)
+                break
+            except OSError:
+                continue
+        if _hip is None:
+            raise RuntimeError("libamdhip64.so not found")
+        _hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        _hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        _hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        _hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    return _hip
+
+
+class HipEvent:
+    """A hipEvent_t usable as ``desc.ev_kernel_begin`` / ``desc.ev_kernel_end``."""
+
+    def __init__(self):
+        self.handle = ctypes.c_void_p()
+        rc = _hip_runtime().hipEventCreate(ctypes.byref(self.handle))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+
+    def record(self, stream=None) -> None:
+        rc = _hip_runtime().hipEventRecord(self.handle, _stream(stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed ({rc})")
+
+    def synchronize(self) -> None:
+        rc = _hip_runtime().hipEventSynchronize(self.handle)
+        if rc != 0:
+            raise RuntimeError(f"hipEventSynchronize failed ({rc})")
+
+    def elapsed_ms(self, end: "HipEvent") -> float:
+        ms = ctypes.c_float()
+        rc = _hip_runtime().hipEventElapsedTime(ctypes.byref(ms), self.handle, end.handle)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            if self.handle:
+                _hip_runtime().hipEventDestroy(self.handle)
+        except Exception:
+            pass

@@ -1,0 +1,146 @@
+// Top-k page selection: workgroup-wide radix select over fp32 score bit patterns, then an
+// order-preserving compaction that gathers physical page ids.
+//
+// The argmax of Eq. 2 / Eq. 3 over unions of pages is the k pages with the largest scores.  The
+// pages overlapping the last G token positions are always kept (last sentence of Sec. 3.2) and
+// are a suffix of the logical page range, so the search runs over the prefix [0, f0) only.
+// Everything is integer work on the score bits: the result is defined bit for bit, ties go to the
+// lower logical page index.
+#pragma once
+#include "vegas_common.hpp"
+
+namespace vegas {
+
+constexpr int kSelectThreads = 1024;
+
+// Order-preserving key of a score (larger float <=> larger unsigned); -0 is folded onto +0.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  const uint32_t u = __float_as_uint(s + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const SelectParams p) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sh_prefix, sh_need;
+  __shared__ uint32_t wave_take[kSelectThreads / 64], wave_eq[kSelectThreads / 64];
+
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  int32_t* sel = p.sel_table + static_cast<int64_t>(b) * p.max_sel_blocks;
+  const int32_t* table = p.block_table + static_cast<int64_t>(b) * p.max_blocks;
+  const float* scores = p.block_scores + static_cast<int64_t>(b) * p.max_blocks;
+
+  int n = p.seq_lens[b];
+  n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+  const int nblk = (n + kPage - 1) / kPage;
+  if (nblk == 0) {
+    for (int i = tid; i < p.max_sel_blocks; i += kSelectThreads) sel[i] = -1;
+    if (tid == 0) p.sel_seq_lens[b] = 0;
+    return;
+  }
+  int budget = p.budgets ? p.budgets[b] : p.budget_tokens;
+  budget = budget < 0 ? 0 : budget;
+  const int f0 = max(n - p.G, 0) / kPage;            // first forced page
+  int nF = nblk - f0;                                // forced pages (1 or 2 for G <= 17)
+  int k = min((budget + kPage - 1) / kPage, nblk);
+  k = max(k, nF);
+  k = min(k, p.max_sel_blocks);                      // device-side clamp; the host rejects this case
+  nF = min(nF, k);
+  const int kc = k - nF;                             // pages to take from the prefix [0, f0)
+
+  // ---- radix select: key of the kc-th largest prefix score, and how many of its ties to take
+  uint32_t T = 0u, need_eq = 0u;
+  bool take_all = false;
+  if (kc >= f0) {
+    take_all = true;
+  } else if (kc > 0) {
+    uint32_t prefix = 0u, mask = 0u, need = static_cast<uint32_t>(kc);
+#pragma unroll 1
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) hist[tid] = 0u;
+      __syncthreads();
+      for (int j = tid; j < f0; j += kSelectThreads) {
+        const uint32_t key = score_key(scores[j]);
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        // lane l owns bins 4l .. 4l+3; count from the top bin downwards
+        uint32_t c[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = hist[4 * lane + i];
+        const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+        uint32_t incl = mine;                          // sum over lanes >= lane
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const uint32_t o = __shfl_down(incl, off, 64);
+          if (lane + off < 64) incl += o;
+        }
+        uint32_t above = incl - mine;                  // elements in bins above this lane's bins
+#pragma unroll
+        for (int i = 3; i >= 0; --i) {
+          if (above < need && need <= above + c[i]) {
+            sh_prefix = prefix | (static_cast<uint32_t>(4 * lane + i) << shift);
+            sh_need = need - above;
+          }
+          above += c[i];
+        }
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      need = sh_need;
+      mask |= 255u << shift;
+    }
+    T = prefix;
+    need_eq = need;
+  }
+
+  // ---- ordered compaction of the prefix
+  uint32_t out_base = 0u, eq_seen = 0u;
+  if (kc > 0) {
+#pragma unroll 1
+    for (int start = 0; start < f0; start += kSelectThreads) {
+      const int j = start + tid;
+      uint32_t key = 0u;
+      const bool in = j < f0;
+      if (in) key = score_key(scores[j]);
+      const bool eq = in && !take_all && key == T;
+      const bool gt = in && (take_all || key > T);
+      const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
+      const uint64_t lt = (1ull << lane) - 1ull;
+      if (lane == 0) wave_eq[wave] = __popcll(beq);
+      __syncthreads();
+      uint32_t eq_before = eq_seen, eq_total = 0u;
+      for (int w = 0; w < kSelectThreads / 64; ++w) {
+        const uint32_t c = wave_eq[w];
+        if (w < wave) eq_before += c;
+        eq_total += c;
+      }
+      const uint32_t eq_rank = eq_before + __popcll(beq & lt);
+      const bool take = gt || (eq && eq_rank < need_eq);
+      const uint64_t btk = __builtin_amdgcn_ballot_w64(take);
+      if (lane == 0) wave_take[wave] = __popcll(btk);
+      __syncthreads();
+      uint32_t tk_before = out_base, tk_total = 0u;
+      for (int w = 0; w < kSelectThreads / 64; ++w) {
+        const uint32_t c = wave_take[w];
+        if (w < wave) tk_before += c;
+        tk_total += c;
+      }
+      if (take) {
+        const uint32_t pos = tk_before + __popcll(btk & lt);
+        if (pos < static_cast<uint32_t>(p.max_sel_blocks)) sel[pos] = table[j];
+      }
+      out_base += tk_total;
+      eq_seen += eq_total;
+    }
+  }
+
+  // ---- forced tail pages, padding, covered length
+  for (int i = tid; i < nF; i += kSelectThreads) sel[kc + i] = table[nblk - nF + i];
+  for (int i = k + tid; i < p.max_sel_blocks; i += kSelectThreads) sel[i] = -1;
+  if (tid == 0) p.sel_seq_lens[b] = kPage * (k - 1) + (n - kPage * (nblk - 1));
+}
+
+}  // namespace vegas

@@ -1,0 +1,274 @@
+// Host side of the C ABI declared in include/vegas.h: argument validation, launch planning,
+// workspace carving and kernel launches.  Nothing here allocates or synchronises.
+#include "../../include/vegas.h"
+
+#include <hip/hip_runtime.h>
+
+#include "attn_finalize.hpp"
+#include "attn_split.hpp"
+#include "select_blocks.hpp"
+#include "vegas_common.hpp"
+
+namespace {
+
+using namespace vegas;
+
+constexpr int kNumCU = 256;           // MI355X compute units
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct SplitPlan {
+  int R = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;
+  size_t off_part_o = 0, off_part_ml = 0, off_row_lse = 0, off_page_lse = 0, total = 0;
+};
+
+int check_common(const vegas_desc* d) {
+  if (!d) return VEGAS_ERR_NULL;
+  if (d->batch <= 0 || d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->max_blocks <= 0 ||
+      d->max_seq_len <= 0 || d->num_pages <= 0)
+    return VEGAS_ERR_SHAPE;
+  if (d->num_q_heads % d->num_kv_heads != 0) return VEGAS_ERR_SHAPE;
+  if (static_cast<int64_t>(d->max_seq_len) > static_cast<int64_t>(d->max_blocks) * kPage) return VEGAS_ERR_SHAPE;
+  if (d->head_dim != kHeadDim || d->page_size != kPage) return VEGAS_ERR_UNSUPPORTED;
+  if (d->kv_head_stride < kHeadDim || d->kv_token_stride < kHeadDim || d->kv_page_stride < kPage * kHeadDim)
+    return VEGAS_ERR_SHAPE;
+  if ((d->kv_head_stride % 8) || (d->kv_token_stride % 8) || (d->kv_page_stride % 8)) return VEGAS_ERR_ALIGN;
+  if (d->kv_chunk_tokens < 0 || (d->kv_chunk_tokens % kTile) != 0) return VEGAS_ERR_SHAPE;
+  if (!(d->softmax_scale > 0.f)) return VEGAS_ERR_SHAPE;
+  return VEGAS_OK;
+}
+
+// Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
+int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, SplitPlan* pl) {
+  pl->R = rows_per_head;
+  if (rows_per_head <= 32) { pl->NB = 1; pl->NW = 8; }
+  else if (rows_per_head <= 64) { pl->NB = 2; pl->NW = 4; }
+  else return VEGAS_ERR_UNSUPPORTED;
+  const int unit = kTile * pl->NW;
+  int chunk = d->kv_chunk_tokens;
+  if (chunk == 0) {
+    const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
+    const int64_t slots = kNumCU * (pl->NW == 8 ? 1 : 2);
+    int64_t splits = slots / heads;
+    if (splits < 1) splits = 1;
+    int64_t c = (max_len + splits - 1) / splits;
+    c = (c + unit - 1) / unit * unit;
+    if (c > 4096) c = 4096;
+    chunk = static_cast<int>(c);
+  }
+  pl->chunk = chunk;
+  pl->nsplit = (max_len + chunk - 1) / chunk;
+  pl->lse_pages = with_lse ? (max_len + kPage - 1) / kPage : 0;
+  const size_t heads = static_cast<size_t>(d->batch) * d->num_kv_heads;
+  size_t off = 0;
+  pl->off_part_o = off;  off += align_up(heads * pl->nsplit * pl->R * kHeadDim * sizeof(float));
+  pl->off_part_ml = off; off += align_up(heads * pl->nsplit * pl->R * sizeof(float2));
+  pl->off_row_lse = off; off += align_up(heads * pl->R * sizeof(float));
+  pl->off_page_lse = off; off += align_up(heads * static_cast<size_t>(pl->lse_pages) * pl->R * sizeof(float));
+  pl->total = off;
+  return VEGAS_OK;
+}
+
+int plan_verify(const vegas_desc* d, SplitPlan* pl) {
+  if (d->num_queries <= 0) return VEGAS_ERR_SHAPE;
+  if (d->collect_rows < 0 || d->collect_rows > 2) return VEGAS_ERR_SHAPE;
+  const int g = d->num_q_heads / d->num_kv_heads;
+  return plan_split(d, d->num_queries * g, d->max_seq_len, d->collect_rows != 0, pl);
+}
+
+int plan_draft(const vegas_desc* d, SplitPlan* pl) {
+  const int g = d->num_q_heads / d->num_kv_heads;
+  return plan_split(d, g, d->max_seq_len, false, pl);
+}
+
+template <bool CAUSAL, bool COLLECT>
+int launch_split(const SplitPlan& pl, const SplitParams& sp, int batch, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
+  if (pl.NB == 1)
+    hipLaunchKernelGGL((attn_split_kernel<1, 8, CAUSAL, COLLECT>), grid, dim3(512), 0, st, sp);
+  else
+    hipLaunchKernelGGL((attn_split_kernel<2, 4, CAUSAL, COLLECT>), grid, dim3(256), 0, st, sp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const void* q, const void* k,
+                       const void* v, const int32_t* table, int table_stride, const int32_t* lens,
+                       unsigned char* ws, SplitParams* sp) {
+  sp->q = static_cast<const uint16_t*>(q);
+  sp->k = static_cast<const uint16_t*>(k);
+  sp->v = static_cast<const uint16_t*>(v);
+  sp->table = table;
+  sp->lens = lens;
+  sp->part_o = reinterpret_cast<float*>(ws + pl.off_part_o);
+  sp->part_ml = reinterpret_cast<float2*>(ws + pl.off_part_ml);
+  sp->page_lse = reinterpret_cast<float*>(ws + pl.off_page_lse);
+  sp->table_stride = table_stride;
+  sp->G = G;
+  sp->g = d->num_q_heads / d->num_kv_heads;
+  sp->R = pl.R;
+  sp->Hq = d->num_q_heads;
+  sp->Hkv = d->num_kv_heads;
+  sp->chunk_tokens = pl.chunk;
+  sp->nsplit = pl.nsplit;
+  sp->lse_pages = pl.lse_pages;
+  sp->max_tokens = d->max_seq_len;
+  sp->page_stride = d->kv_page_stride;
+  sp->token_stride = d->kv_token_stride;
+  sp->head_stride = d->kv_head_stride;
+  sp->num_pages = d->num_pages;
+  sp->scale_log2e = d->softmax_scale * 1.4426950408889634f;
+}
+
+int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& sp, void* out, float* row_lse,
+                   hipStream_t st) {
+  CombineParams cp;
+  cp.part_o = sp.part_o;
+  cp.part_ml = sp.part_ml;
+  cp.lens = sp.lens;
+  cp.out = static_cast<uint16_t*>(out);
+  cp.row_lse = row_lse;
+  cp.G = sp.G; cp.g = sp.g; cp.R = sp.R; cp.Hq = sp.Hq; cp.Hkv = sp.Hkv;
+  cp.chunk_tokens = pl.chunk; cp.nsplit = pl.nsplit; cp.max_tokens = d->max_seq_len;
+  hipLaunchKernelGGL(attn_combine_kernel, dim3(pl.R, sp.Hkv, d->batch), dim3(128), 0, st, cp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t vegas_workspace_bytes(const vegas_desc* desc) {
+  if (check_common(desc) != VEGAS_OK) return 0;
+  SplitPlan pv, pd;
+  size_t need = kAlign;
+  if (desc->num_queries > 0 && plan_verify(desc, &pv) == VEGAS_OK) need = pv.total > need ? pv.total : need;
+  if (plan_draft(desc, &pd) == VEGAS_OK) need = pd.total > need ? pd.total : need;
+  return need;
+}
+
+int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* block_table, const int32_t* seq_lens, void* out, float* block_scores,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out) return VEGAS_ERR_NULL;
+  SplitPlan pl;
+  rc = plan_verify(desc, &pl);
+  if (rc != VEGAS_OK) return rc;
+  const bool collect = desc->collect_rows != VEGAS_COLLECT_NONE;
+  if (collect && !block_scores) return VEGAS_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(block_table) ||
+      (block_scores && !aligned16(block_scores)))
+    return VEGAS_ERR_ALIGN;
+  if (!workspace || workspace_bytes < pl.total) return VEGAS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return VEGAS_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+
+  SplitParams sp;
+  fill_split_params(desc, pl, desc->num_queries, q, k_cache, v_cache, block_table, desc->max_blocks, seq_lens, ws, &sp);
+  if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
+  rc = collect ? launch_split<true, true>(pl, sp, desc->batch, st) : launch_split<true, false>(pl, sp, desc->batch, st);
+  if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
+  if (rc != VEGAS_OK) return rc;
+  float* row_lse = reinterpret_cast<float*>(ws + pl.off_row_lse);
+  rc = launch_combine(desc, pl, sp, out, collect ? row_lse : nullptr, st);
+  if (rc != VEGAS_OK) return rc;
+  if (collect) {
+    ScoreParams sc;
+    sc.page_lse = sp.page_lse;
+    sc.row_lse = row_lse;
+    sc.lens = seq_lens;
+    sc.block_scores = block_scores;
+    sc.G = desc->num_queries; sc.g = sp.g; sc.R = pl.R; sc.Hkv = sp.Hkv;
+    sc.max_blocks = desc->max_blocks; sc.lse_pages = pl.lse_pages; sc.max_tokens = desc->max_seq_len;
+    sc.collect_rows = desc->collect_rows;
+    const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
+                                                                     : (desc->num_queries > 1 ? 2 : 1);
+    sc.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
+    const size_t shm = static_cast<size_t>(sp.Hkv) * pl.R * sizeof(float);
+    hipLaunchKernelGGL(block_score_kernel, dim3((desc->max_blocks + 255) / 256, desc->batch), dim3(256), shm, st, sc);
+    if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
+  }
+  return VEGAS_OK;
+}
+
+int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const int32_t* block_table,
+                        const int32_t* seq_lens, int32_t budget_tokens, const int32_t* budgets,
+                        int32_t* sel_table, int32_t* sel_seq_lens, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int rc = check_common(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (!block_scores || !block_table || !seq_lens || !sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
+  if (desc->num_queries <= 0 || desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
+  if (!budgets) {
+    if (budget_tokens <= 0) return VEGAS_ERR_SHAPE;
+    const int64_t max_pages = (static_cast<int64_t>(desc->max_seq_len) + kPage - 1) / kPage;
+    int64_t kmax = (static_cast<int64_t>(budget_tokens) + kPage - 1) / kPage;
+    const int64_t forced = (desc->num_queries + kPage - 2) / kPage + 1;   // pages G positions can touch
+    if (kmax < forced) kmax = forced;
+    if (kmax > max_pages) kmax = max_pages;
+    if (desc->max_sel_blocks < kmax) return VEGAS_ERR_SHAPE;
+  }
+  SelectParams sp;
+  sp.block_scores = block_scores;
+  sp.block_table = block_table;
+  sp.seq_lens = seq_lens;
+  sp.budgets = budgets;
+  sp.sel_table = sel_table;
+  sp.sel_seq_lens = sel_seq_lens;
+  sp.budget_tokens = budget_tokens;
+  sp.G = desc->num_queries;
+  sp.max_blocks = desc->max_blocks;
+  sp.max_sel_blocks = desc->max_sel_blocks;
+  sp.max_tokens = desc->max_seq_len;
+  hipLaunchKernelGGL(select_blocks_kernel, dim3(desc->batch), dim3(kSelectThreads), 0,
+                     static_cast<hipStream_t>(hip_stream), sp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* sel_table, const int32_t* sel_seq_lens, void* out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (!q || !k_cache || !v_cache || !sel_table || !sel_seq_lens || !out) return VEGAS_ERR_NULL;
+  if (desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
+  if (static_cast<int64_t>(desc->max_seq_len) > static_cast<int64_t>(desc->max_sel_blocks) * kPage)
+    return VEGAS_ERR_SHAPE;
+  SplitPlan pl;
+  rc = plan_draft(desc, &pl);
+  if (rc != VEGAS_OK) return rc;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(sel_table))
+    return VEGAS_ERR_ALIGN;
+  if (!workspace || workspace_bytes < pl.total) return VEGAS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return VEGAS_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  SplitParams sp;
+  fill_split_params(desc, pl, 1, q, k_cache, v_cache, sel_table, desc->max_sel_blocks, sel_seq_lens, ws, &sp);
+  if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
+  rc = launch_split<false, false>(pl, sp, desc->batch, st);
+  if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
+  if (rc != VEGAS_OK) return rc;
+  return launch_combine(desc, pl, sp, out, nullptr, st);
+}
+
+const char* vegas_strerror(int status) {
+  switch (status) {
+    case VEGAS_OK: return "ok";
+    case VEGAS_ERR_NULL: return "a required pointer is NULL";
+    case VEGAS_ERR_SHAPE: return "a size is non-positive or inconsistent";
+    case VEGAS_ERR_UNSUPPORTED: return "shape not supported by this build (head_dim 128, page_size 16, <= 64 rows per KV head)";
+    case VEGAS_ERR_ALIGN: return "pointer or stride alignment";
+    case VEGAS_ERR_WORKSPACE: return "workspace missing or too small";
+    case VEGAS_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+// Shared device-side types and helpers for the gfx950 kernels (wave64, MFMA, LDS).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vegas {
+
+constexpr int kPage = 16;       // tokens per KV page
+constexpr int kHeadDim = 128;   // head dimension the kernels are written for
+constexpr int kTile = 32;       // tokens per MFMA tile (two pages)
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Value of the lane 32 positions away (the other half of the wave).
+__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32, 64); }
+
+// Orders LDS traffic between the lanes of ONE wave (a wave's LDS instructions execute in order,
+// so only the compiler has to be kept from moving accesses across this point).
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// float -> bf16 bits, round to nearest even (finite values and infinities).
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+// Arguments of the KV-streaming attention kernel (verification and draft share it).
+struct SplitParams {
+  const uint16_t* q;        // verify [B, G, Hq, D]; draft [B, Hq, D] (G = 1)
+  const uint16_t* k;
+  const uint16_t* v;
+  const int32_t* table;     // [B, table_stride] physical page of each logical page
+  const int32_t* lens;      // [B] valid tokens
+  float* part_o;            // [B, Hkv, nsplit, R, D] un-normalised partial outputs
+  float2* part_ml;          // [B, Hkv, nsplit, R]    (running max in log2 units, partial sum)
+  float* page_lse;          // [B, Hkv, lse_pages, R] log2-sum-exp2 of each page's scaled logits
+  int32_t table_stride;
+  int32_t G, g, R, Hq, Hkv;
+  int32_t chunk_tokens, nsplit, lse_pages, max_tokens;
+  int64_t page_stride, token_stride, head_stride, num_pages;
+  float scale_log2e;
+};
+
+struct CombineParams {
+  const float* part_o;
+  const float2* part_ml;
+  const int32_t* lens;
+  uint16_t* out;            // bf16 [B, G, Hq, D]
+  float* row_lse;           // [B, Hkv, R] or nullptr
+  int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
+};
+
+struct ScoreParams {
+  const float* page_lse;
+  const float* row_lse;
+  const int32_t* lens;
+  float* block_scores;      // [B, max_blocks]
+  int32_t G, g, R, Hkv, max_blocks, lse_pages, max_tokens, collect_rows;
+  float inv_norm;
+};
+
+struct SelectParams {
+  const float* block_scores;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  const int32_t* budgets;   // or nullptr
+  int32_t* sel_table;
+  int32_t* sel_seq_lens;
+  int32_t budget_tokens, G, max_blocks, max_sel_blocks, max_tokens;
+};
+
+}  // namespace vegas

@@ -1,0 +1,110 @@
+"""Device-memory plumbing around the binding: upload a synthetic layer, allocate outputs and
+workspace with torch, and issue verify -> select -> draft through the C ABI.  No arithmetic of the
+method lives here; torch is used for allocation, copies and streams only."""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as vb
+from .synth import LayerInputs
+
+PAGE = 16
+
+
+def bf16_to_device(bits: np.ndarray, device) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on ``device`` (bit-exact)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.to(device).view(torch.bfloat16)
+
+
+def bf16_to_host_f64(t: torch.Tensor) -> np.ndarray:
+    """torch.bfloat16 tensor -> float64 NumPy array (exact)."""
+    bits = t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+@dataclasses.dataclass
+class DeviceLayer:
+    q_verify: torch.Tensor      # bf16 [B, G, Hq, D]
+    q_draft: torch.Tensor       # bf16 [G, B, Hq, D]
+    k_cache: torch.Tensor       # bf16 [P, 16, Hkv, D]
+    v_cache: torch.Tensor
+    block_table: torch.Tensor   # int32 [B, max_blocks]
+    seq_lens: torch.Tensor      # int32 [B]
+
+    @staticmethod
+    def upload(L: LayerInputs, device="cuda:0") -> "DeviceLayer":
+        return DeviceLayer(
+            q_verify=bf16_to_device(L.q_verify, device), q_draft=bf16_to_device(L.q_draft, device),
+            k_cache=bf16_to_device(L.k_cache, device), v_cache=bf16_to_device(L.v_cache, device),
+            block_table=torch.from_numpy(L.block_table).to(device), seq_lens=torch.from_numpy(L.seq_lens).to(device))
+
+
+class VegasPath:
+    """One layer's verify -> select -> draft calls with preallocated outputs and workspace."""
+
+    def __init__(self, *, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: int, max_blocks: int,
+                 max_seq_len: int, num_pages: int, budget_tokens: int, softmax_scale: float,
+                 collect_rows: int = vb.COLLECT_ALL_ROWS, head_dim: int = 128, device="cuda:0",
+                 verify_chunk: int = 0, draft_chunk: int = 0, max_sel_blocks: int = 0):
+        self.device = torch.device(device)
+        self.B, self.Hq, self.Hkv, self.G, self.D = batch, num_q_heads, num_kv_heads, num_queries, head_dim
+        self.budget_tokens = budget_tokens
+        max_pages = (max_seq_len + PAGE - 1) // PAGE
+        want = max(min((budget_tokens + PAGE - 1) // PAGE, max_pages), (num_queries + PAGE - 2) // PAGE + 1)
+        self.max_sel_blocks = max_sel_blocks or (want + 2)
+        common = dict(batch=batch, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, num_queries=num_queries,
+                      max_blocks=max_blocks, max_sel_blocks=self.max_sel_blocks, num_pages=num_pages,
+                      softmax_scale=softmax_scale, head_dim=head_dim)
+        self.desc_verify = vb.make_desc(max_seq_len=max_seq_len, collect_rows=collect_rows,
+                                        kv_chunk_tokens=verify_chunk, **common)
+        draft_len = min(self.max_sel_blocks * PAGE, max_blocks * PAGE)
+        self.desc_draft = vb.make_desc(max_seq_len=draft_len, collect_rows=vb.COLLECT_NONE,
+                                       kv_chunk_tokens=draft_chunk, **common)
+        nbytes = max(vb.vegas_workspace_bytes(self.desc_verify), vb.vegas_workspace_bytes(self.desc_draft))
+        if nbytes == 0:
+            raise ValueError("descriptor rejected by vegas_workspace_bytes")
+        dev = self.device
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.out_verify = torch.empty((batch, num_queries, num_q_heads, head_dim), dtype=torch.bfloat16, device=dev)
+        self.block_scores = torch.empty((batch, max_blocks), dtype=torch.float32, device=dev)
+        self.sel_table = torch.empty((batch, self.max_sel_blocks), dtype=torch.int32, device=dev)
+        self.sel_seq_lens = torch.empty((batch,), dtype=torch.int32, device=dev)
+        self.out_draft = torch.empty((num_queries, batch, num_q_heads, head_dim), dtype=torch.bfloat16, device=dev)
+
+    @classmethod
+    def for_layer(cls, L: LayerInputs, budget_tokens: Optional[int] = None, **kw) -> "VegasPath":
+        s = L.spec
+        return cls(batch=s.batch, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads,
+                   num_queries=s.num_queries, max_blocks=L.max_blocks,
+                   max_seq_len=max(int(L.seq_lens.max()), 1), num_pages=L.num_pages,
+                   budget_tokens=budget_tokens if budget_tokens is not None else s.budget_tokens,
+                   softmax_scale=L.softmax_scale, head_dim=s.head_dim, **kw)
+
+    def stream(self) -> int:
+        return int(torch.cuda.current_stream(self.device).cuda_stream)
+
+    def verify(self, dl: DeviceLayer) -> None:
+        vb.vegas_verify_attention(self.desc_verify, dl.q_verify, dl.k_cache, dl.v_cache, dl.block_table,
+                                  dl.seq_lens, self.out_verify, self.block_scores, self.workspace,
+                                  stream=self.stream())
+
+    def select(self, dl: DeviceLayer, block_scores: Optional[torch.Tensor] = None, budgets=None) -> None:
+        vb.vegas_select_blocks(self.desc_verify, self.block_scores if block_scores is None else block_scores,
+                               dl.block_table, dl.seq_lens, self.budget_tokens, self.sel_table,
+                               self.sel_seq_lens, budgets=budgets, stream=self.stream())
+
+    def draft(self, dl: DeviceLayer, step: int) -> None:
+        vb.vegas_draft_attention(self.desc_draft, dl.q_draft[step], dl.k_cache, dl.v_cache, self.sel_table,
+                                 self.sel_seq_lens, self.out_draft[step], self.workspace, stream=self.stream())
+
+    def iteration(self, dl: DeviceLayer) -> None:
+        """One decoding iteration's attention work for one layer: verify, select, G draft steps."""
+        self.verify(dl)
+        self.select(dl)
+        for s in range(self.G):
+            self.draft(dl, s)

@@ -1,0 +1,130 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_07223_amd import binding as vb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good_desc(**over):
+    kw = dict(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, max_blocks=2048, max_sel_blocks=130,
+              max_seq_len=32768, num_pages=2048, softmax_scale=128 ** -0.5)
+    kw.update(over)
+    return vb.make_desc(**kw)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = vb.load_library()
+    with open(os.path.join(ROOT, "include", "vegas.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"\b(vegas_[a-z_]+)\s*\(", header))
+    assert declared == set(vb.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_desc_layout_matches_header():
+    with open(os.path.join(ROOT, "include", "vegas.h")) as f:
+        header = f.read()
+    body = header[header.index("typedef struct vegas_desc {"):header.index("} vegas_desc;")]
+    fields = re.findall(r"^\s*(?:int32_t|int64_t|float|void\*)\s+(\w+);", body, flags=re.M)
+    assert fields == [f[0] for f in vb.VegasDesc._fields_]
+    assert ctypes.sizeof(vb.VegasDesc) == 12 * 4 + 4 * 8 + 2 * 8
+
+
+def test_workspace_bytes_is_a_pure_host_function():
+    n = vb.vegas_workspace_bytes(good_desc())
+    assert n > 0 and n % 256 == 0
+    assert vb.vegas_workspace_bytes(good_desc(max_seq_len=65536, max_blocks=4096)) > n
+    assert vb.vegas_workspace_bytes(good_desc(head_dim=64)) == 0
+    assert vb.vegas_workspace_bytes(good_desc(num_q_heads=30)) == 0
+
+
+def test_strerror_is_defined_for_every_status():
+    for s in range(0, -7, -1):
+        assert vb.strerror(s) and vb.strerror(s) != "unknown status"
+    assert vb.strerror(-99) == "unknown status"
+
+
+A = 4096  # a 16-byte aligned fake device address: never dereferenced because validation fails first
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(batch=0), vb.VEGAS_ERR_SHAPE),
+    (dict(num_q_heads=30), vb.VEGAS_ERR_SHAPE),
+    (dict(head_dim=64), vb.VEGAS_ERR_UNSUPPORTED),
+    (dict(page_size=32), vb.VEGAS_ERR_UNSUPPORTED),
+    (dict(max_seq_len=32769), vb.VEGAS_ERR_SHAPE),
+    (dict(num_queries=0), vb.VEGAS_ERR_SHAPE),
+    (dict(num_queries=17), vb.VEGAS_ERR_UNSUPPORTED),          # 68 rows per KV head
+    (dict(collect_rows=3), vb.VEGAS_ERR_SHAPE),
+    (dict(kv_chunk_tokens=100), vb.VEGAS_ERR_SHAPE),
+    (dict(kv_token_stride=1028), vb.VEGAS_ERR_ALIGN),
+    (dict(softmax_scale=0.0), vb.VEGAS_ERR_SHAPE),
+])
+def test_verify_rejects_bad_descriptors(over, status):
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(good_desc(**over), A, A, A, A, A, A, A, A, workspace_bytes=1 << 30)
+    assert e.value.status == status
+
+
+def test_verify_rejects_null_misaligned_and_small_workspace():
+    d = good_desc()
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(d, None, A, A, A, A, A, A, A, workspace_bytes=1 << 30)
+    assert e.value.status == vb.VEGAS_ERR_NULL
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(d, A, A, A, A, A, A, None, A, workspace_bytes=1 << 30)
+    assert e.value.status == vb.VEGAS_ERR_NULL                  # scores required when collecting
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(d, A + 2, A, A, A, A, A, A, A, workspace_bytes=1 << 30)
+    assert e.value.status == vb.VEGAS_ERR_ALIGN
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(d, A, A, A, A, A, A, A, A, workspace_bytes=1024)
+    assert e.value.status == vb.VEGAS_ERR_WORKSPACE
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(d, A, A, A, A, A, A, A, A + 16, workspace_bytes=1 << 30)
+    assert e.value.status == vb.VEGAS_ERR_ALIGN
+
+
+def test_select_and_draft_reject_bad_arguments():
+    d = good_desc()
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_select_blocks(d, A, A, A, 0, A, A)
+    assert e.value.status == vb.VEGAS_ERR_SHAPE                 # budget must be positive
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_select_blocks(d, A, A, A, 4096, A, A)
+    assert e.value.status == vb.VEGAS_ERR_SHAPE                 # 256 pages do not fit max_sel_blocks=130
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_select_blocks(d, None, A, A, 2048, A, A)
+    assert e.value.status == vb.VEGAS_ERR_NULL
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_draft_attention(d, A, A, A, A, A, A, A, workspace_bytes=1 << 30)
+    assert e.value.status == vb.VEGAS_ERR_SHAPE                 # max_seq_len exceeds max_sel_blocks pages
+    dd = good_desc(max_seq_len=130 * 16)
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_draft_attention(dd, A, A, A, A, None, A, A, workspace_bytes=1 << 30)
+    assert e.value.status == vb.VEGAS_ERR_NULL
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_draft_attention(dd, A, A, A, A, A, A, None, workspace_bytes=0)
+    assert e.value.status == vb.VEGAS_ERR_WORKSPACE
+
+
+def test_product_path_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2602_07223_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                with open(os.path.join(dirpath, fn)) as f:
+                    text = f.read()
+                assert not re.search(r"^\s*(from|import)\s+\S*oracle", text, flags=re.M), fn
+                assert "vegas_oracle" not in text, fn
+    for fn in os.listdir(os.path.join(ROOT, "oracle")):
+        if fn.endswith(".py"):
+            with open(os.path.join(ROOT, "oracle", fn)) as f:
+                assert not re.search(r"^\s*(from|import)\s+paper_2602_07223_amd", f.read(), flags=re.M), fn

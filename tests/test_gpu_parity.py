@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the
+same seeded inputs.  Sizes span several tiles, several chunks and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import vegas_oracle as O
+from paper_2602_07223_amd import binding as vb
+from paper_2602_07223_amd import harness, synth
+from tests import parity_util as U
+
+pytestmark = pytest.mark.gpu
+PAGE = 16
+
+
+def run_chain(L, budget, collect=vb.COLLECT_ALL_ROWS, verify_chunk=0, draft_chunk=0, name="case", vscale=None):
+    """verify -> select -> G draft steps on the GPU, each stage compared with the oracle."""
+    print(f"[case] {name} B={L.spec.batch} Hq={L.spec.num_q_heads} G={L.spec.num_queries} "
+          f"lens={list(map(int, L.seq_lens[:8]))} budget={budget} collect={collect}", flush=True)
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=budget, collect_rows=collect,
+                                       verify_chunk=verify_chunk, draft_chunk=draft_chunk)
+    G = L.spec.num_queries
+    vs = U.vmax_visible(L) if vscale is None else vscale
+    # stage 1: verify
+    path.block_scores.fill_(float("nan"))
+    path.verify(dl)
+    torch.cuda.synchronize()
+    ref_out, ref_scores = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                                             L.softmax_scale, collect)
+    U.check_out(name + ".verify.out", path.out_verify, ref_out, vs)
+    U.check_scores(name + ".scores", path.block_scores, ref_scores)
+    # stage 2: select (GPU scores -> GPU selection) vs oracle scores -> oracle selection
+    path.select(dl)
+    torch.cuda.synchronize()
+    sel = path.sel_table.cpu().numpy()
+    ssl = path.sel_seq_lens.cpu().numpy()
+    _, ref_ssl, ref_logical = O.select_blocks(ref_scores, L.block_table, L.seq_lens, G, budget, path.max_sel_blocks)
+    U.check_selection(name + ".select", sel, ssl, L, ref_scores, ref_logical, G, budget)
+    # select on identical fp32 scores must agree bit for bit
+    s32 = ref_scores.astype(np.float32)
+    path.select(dl, block_scores=torch.from_numpy(s32).to(path.device))
+    torch.cuda.synchronize()
+    sel2, ssl2, _ = O.select_blocks(s32, L.block_table, L.seq_lens, G, budget, path.max_sel_blocks)
+    assert np.array_equal(path.sel_table.cpu().numpy(), sel2), name + ": select not bit-exact"
+    assert np.array_equal(path.sel_seq_lens.cpu().numpy(), ssl2), name + ": sel_seq_lens not bit-exact"
+    # stage 3: draft over the GPU's own selection (restored), oracle fed the same page list
+    path.select(dl)
+    for s in range(G):
+        path.draft(dl, s)
+    torch.cuda.synchronize()
+    for s in range(G):
+        ref_d = O.draft_attention(L.q_draft[s], L.k_cache, L.v_cache, sel, ssl, L.softmax_scale)
+        U.check_out(f"{name}.draft{s}", path.out_draft[s], ref_d, vs)
+    return path, ref_out, ref_scores
+
+
+SMALL = [
+    # name, B, Hq, Hkv, G, lens, kwargs
+    ("one_tile", 1, 32, 8, 5, [32], {}),
+    ("ragged_tail", 1, 32, 8, 5, [1000], {}),
+    ("tiny", 2, 32, 8, 5, [5, 17], {}),
+    ("multi_chunk", 1, 32, 8, 5, [5000], dict(verify_chunk=512)),
+    ("batch_ragged", 3, 32, 8, 5, [700, 2049, 31], dict(verify_chunk=256)),
+    ("gamma6", 1, 32, 8, 7, [3000], {}),
+    ("group8", 2, 64, 8, 5, [1500, 640], {}),
+    ("group8_chunks", 1, 64, 8, 5, [4100], dict(verify_chunk=1024)),
+    ("single_query", 1, 32, 8, 1, [777], {}),
+    ("gamma11_g4", 1, 32, 8, 12, [2000], {}),
+    ("mha_like", 1, 8, 8, 3, [900], {}),
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,kw", SMALL, ids=[c[0] for c in SMALL])
+@pytest.mark.parametrize("sharp", [False, True], ids=["flat", "sharp"])
+def test_small_cases(name, B, Hq, Hkv, G, lens, kw, sharp):
+    L = synth.make_random_case(seed=100 + len(name) + 7 * G, batch=B, num_q_heads=Hq, num_kv_heads=Hkv,
+                               num_queries=G, seq_lens=lens,
+                               logit_std=2.0 if sharp else 0.3, value_std=1.0,
+                               outliers=3 if sharp else 0, outlier_logit=30.0)
+    budget = max(32, (max(lens) // 10) // PAGE * PAGE)
+    run_chain(L, budget, name=name + ("_sharp" if sharp else "_flat"), **kw)
+
+
+@pytest.mark.parametrize("collect", [vb.COLLECT_FIRST_LAST, vb.COLLECT_ALL_ROWS])
+def test_collect_modes(collect):
+    L = synth.make_random_case(seed=77, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=6,
+                               seq_lens=[1234, 4000], logit_std=1.0, outliers=2)
+    run_chain(L, 256, collect=collect, name=f"collect{collect}")
+
+
+def test_collect_none_leaves_scores_untouched_and_out_correct():
+    L = synth.make_random_case(seed=78, batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, seq_lens=[2500])
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=256, collect_rows=vb.COLLECT_NONE)
+    path.block_scores.fill_(-7.0)
+    path.verify(dl)
+    torch.cuda.synchronize()
+    ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 0)
+    U.check_out("collect_none", path.out_verify, ref_out, U.vmax_visible(L))
+    assert bool((path.block_scores == -7.0).all())
+
+
+def test_baseline_config1_full():
+    L = synth.make_layer(synth.CONFIGS["ctx4k"])
+    run_chain(L, L.spec.budget_tokens, name="ctx4k")
+
+
+def test_baseline_config2_full():
+    L = synth.make_layer(synth.CONFIGS["ctx32k"])
+    path, _, ref_scores = run_chain(L, L.spec.budget_tokens, name="ctx32k")
+    sel = path.sel_table.cpu().numpy()[0]
+    inv = {int(p): j for j, p in enumerate(L.block_table[0])}
+    ids = {inv[int(p)] for p in sel if p >= 0}
+    assert set(np.unique(L.hitters[0] // PAGE)).issubset(ids)        # planted hitters are selected
+    assert set(np.unique(L.sinks[0] // PAGE)).issubset(ids)
+
+
+def test_empty_and_short_sequences():
+    L = synth.make_random_case(seed=79, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[0, 3, 40], spare_pages=2)
+    run_chain(L, 32, name="degenerate")
+
+
+def test_budget_covers_context_draft_equals_last_verify_row():
+    """Cross-kernel identity: with every page selected, a draft query equal to the bonus row's query
+    reproduces that verify row."""
+    L = synth.make_random_case(seed=80, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=4,
+                               seq_lens=[1500, 333], logit_std=1.0)
+    L.q_draft[0] = L.q_verify[:, -1]
+    path, ref_out, _ = run_chain(L, 10 ** 6, name="full_budget")
+    a = harness.bf16_to_host_f64(path.out_draft[0])
+    b = harness.bf16_to_host_f64(path.out_verify[:, -1])
+    assert np.abs(a - b).max() <= 2 * max(U.OUT_ATOL, U.vmax_visible(L) / 256.0)
+    assert np.array_equal(path.sel_seq_lens.cpu().numpy(), L.seq_lens)
+
+
+def test_results_do_not_depend_on_physical_page_ids():
+    L = synth.make_random_case(seed=81, batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[3000], shuffle=False, spare_pages=0, poison=False)
+    rng = np.random.default_rng(2)
+    P = L.k_cache.shape[0]
+    perm = rng.permutation(P)
+    import copy
+    L2 = copy.copy(L)
+    L2.k_cache = np.empty_like(L.k_cache); L2.v_cache = np.empty_like(L.v_cache)
+    L2.k_cache[perm] = L.k_cache; L2.v_cache[perm] = L.v_cache
+    L2.block_table = np.where(L.block_table >= 0, perm[np.clip(L.block_table, 0, None)], -1).astype(np.int32)
+    outs = []
+    for X in (L, L2):
+        dl = harness.DeviceLayer.upload(X)
+        path = harness.VegasPath.for_layer(X, budget_tokens=320)
+        path.iteration(dl)
+        torch.cuda.synchronize()
+        outs.append((path.out_verify.view(torch.int16).cpu().numpy().copy(), path.block_scores.cpu().numpy().copy(),
+                     path.sel_table.cpu().numpy().copy(), path.out_draft.view(torch.int16).cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    assert np.array_equal(outs[0][3], outs[1][3])
+    assert np.array_equal(np.where(outs[0][2] >= 0, perm[np.clip(outs[0][2], 0, None)], -1), outs[1][2])
+
+
+def test_run_to_run_bit_reproducible():
+    L = synth.make_layer(synth.scaled(synth.CONFIGS["ctx4k"], seq_len=2048 + 9))
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L)
+    snaps = []
+    for _ in range(3):
+        path.iteration(dl)
+        torch.cuda.synchronize()
+        snaps.append((path.out_verify.view(torch.int16).cpu().numpy().copy(), path.block_scores.cpu().numpy().copy(),
+                      path.sel_table.cpu().numpy().copy(), path.out_draft.view(torch.int16).cpu().numpy().copy()))
+    for s in snaps[1:]:
+        for a, b in zip(snaps[0], s):
+            assert np.array_equal(a, b)
+
+
+def test_select_bit_exact_with_ties_and_budgets():
+    """Integer work: many exact ties, per-sequence budgets, budgets below the forced pages and above the context."""
+    rng = np.random.default_rng(5)
+    B, mb = 6, 700
+    lens = np.array([11200, 5000, 16, 777, 0, 9000], dtype=np.int32)
+    nblk = (lens + PAGE - 1) // PAGE
+    scores = np.zeros((B, mb), dtype=np.float32)
+    for b in range(B):
+        scores[b, :nblk[b]] = rng.integers(0, 6, size=nblk[b]).astype(np.float32) / 8.0    # heavy ties
+    table = np.stack([rng.permutation(4000)[:mb] for _ in range(B)]).astype(np.int32)
+    budgets = np.array([2048, 1, 64, 100000, 32, 4800], dtype=np.int32)
+    G = 5
+    desc = vb.make_desc(batch=B, num_q_heads=32, num_kv_heads=8, num_queries=G, max_blocks=mb, max_sel_blocks=mb,
+                        max_seq_len=mb * PAGE, num_pages=4000, softmax_scale=0.1)
+    dev = torch.device("cuda:0")
+    sel = torch.empty((B, mb), dtype=torch.int32, device=dev)
+    ssl = torch.empty((B,), dtype=torch.int32, device=dev)
+    for use_per_seq in (True, False):
+        vb.vegas_select_blocks(desc, torch.from_numpy(scores).to(dev), torch.from_numpy(table).to(dev),
+                               torch.from_numpy(lens).to(dev), 640, sel, ssl,
+                               budgets=torch.from_numpy(budgets).to(dev) if use_per_seq else None)
+        torch.cuda.synchronize()
+        ref_sel, ref_ssl, _ = O.select_blocks(scores, table, lens, G, 640, mb, budgets if use_per_seq else None)
+        assert np.array_equal(sel.cpu().numpy(), ref_sel)
+        assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
