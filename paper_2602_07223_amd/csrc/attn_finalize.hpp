@@ -33,33 +33,36 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
 
 // Page criticality (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the last
 // paragraph of Sec. 3.3): score[b][j] = inv_norm * sum_h sum_{rows in R} 2^(page_lse - row_lse).
-// One thread per page; pages at or beyond the sequence's page count are written as 0.
+// One wave per page: the Hkv*R values of a page are contiguous, lanes stride over them and a
+// wave reduction adds them up.  Pages at or beyond the sequence's page count are written as 0.
 __global__ __launch_bounds__(256) void block_score_kernel(const ScoreParams p) {
-  extern __shared__ float sm_row[];           // [Hkv * R] global row lse of this sequence
+  extern __shared__ float sm_row[];           // [Hkv * R] global row lse; -inf for rows not collected
   const int b = blockIdx.y;
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   const int nblk = (n + kPage - 1) / kPage;
   const int HR = p.Hkv * p.R;
-  for (int i = threadIdx.x; i < HR; i += blockDim.x)
-    sm_row[i] = p.row_lse[static_cast<int64_t>(b) * HR + i];
+  for (int i = threadIdx.x; i < HR; i += blockDim.x) {
+    const int t = (i % p.R) / p.g;
+    const bool use = (p.collect_rows == 1) || (t == 0) || (t == p.G - 1);
+    sm_row[i] = use ? p.row_lse[static_cast<int64_t>(b) * HR + i] : -INFINITY;
+  }
   __syncthreads();
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (j >= p.max_blocks) return;
   float s = 0.f;
   if (j < nblk) {
-    for (int h = 0; h < p.Hkv; ++h) {
-      const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
-      for (int r = 0; r < p.R; ++r) {
-        const int t = r / p.g;
-        const bool use = (p.collect_rows == 1) || (t == 0) || (t == p.G - 1);
-        const float rl = sm_row[h * p.R + r];
-        if (use && rl != -INFINITY) s += fast_exp2(pl[r] - rl);
-      }
+    const float* pl = p.page_lse + (static_cast<int64_t>(b) * p.lse_pages + j) * HR;
+    for (int i = lane; i < HR; i += 64) {
+      const float rl = sm_row[i];
+      if (rl != -INFINITY) s += fast_exp2(pl[i] - rl);
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
     s *= p.inv_norm;
   }
-  p.block_scores[static_cast<int64_t>(b) * p.max_blocks + j] = s;
+  if (lane == 0) p.block_scores[static_cast<int64_t>(b) * p.max_blocks + j] = s;
 }
 
 }  // namespace vegas

@@ -18,34 +18,64 @@
 //     and both pages of the tile sit in separate registers, so page sums need no shuffles beyond
 //     one half-wave exchange.
 //   * K is loaded fully coalesced (four 256-byte token rows per 1 KB instruction), staged through
-//     a wave-private, XOR-swizzled 8 KB LDS tile and re-read in MFMA operand layout.
+//     a wave-private LDS tile (rows padded to 272 bytes against bank conflicts) and re-read in
+//     MFMA operand layout.
 //   * V needs no staging: tokens are the contraction index of the second MFMA, so a lane reads
 //     8 bytes (4 head dims) of one token per instruction -- 32 lanes cover one 256-byte row --
 //     and two byte-permutes per register pair build the operand.
 //   * All query rows of the GQA group (x G verification rows) are stacked in the N dimension, so
-//     every K/V byte is loaded once per workgroup and never re-read.
-//   * Loads for tile i+1 are in flight (in registers) while tile i is computed.
+//     every K/V byte is loaded once per workgroup and never re-read.  The queries sit in LDS
+//     (padded like K) and are shared by the workgroup's waves.
+//   * Loads run one tile ahead: K(next) is issued as soon as K(current) has been handed to LDS
+//     (same registers), V(next) after the first MFMA batch into a second register set.
 //   * At the end the NW waves merge their (max, sum, O) through LDS and the workgroup writes one
 //     partial result.
 #pragma once
+#include <type_traits>
+
 #include "vegas_common.hpp"
 
 namespace vegas {
 
-struct TileRegs {
-  u32x4 k[8];    // K: load i covers tokens 4i .. 4i+3 of the tile (16 lanes x 16 B per token)
-  u32x2 v[16];   // V: [s*8 + jj] = 4 head dims of token 16s + 8(jj/4) + 4*half + jj%4
-};
+// Both halves of the wave get op(x, x from the other half) with one VALU lane swap.
+__device__ __forceinline__ float half_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Pins a wave-uniform pointer into scalar registers so that loads take the
+// "scalar base + 32-bit lane offset" addressing form.
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* ptr) {
+  const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// Global-memory load at (wave-uniform base) + (32-bit lane offset).
+template <typename T>
+__device__ __forceinline__ T gload(const unsigned char* sbase, uint32_t voff) {
+  typedef const __attribute__((address_space(1))) T* gp;
+  return *(gp)((const __attribute__((address_space(1))) unsigned char*)sbase + voff);
+}
+
+constexpr int kRowPitch = 272;   // LDS bytes per 256-byte K/Q row: the 16-byte pad spreads rows over banks
 
 template <int NB, int NW, bool CAUSAL, bool COLLECT>
 __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p) {
   // K staging (NW x 8 KB), reused for the cross-wave merge of the output accumulators.
-  __shared__ __attribute__((aligned(16))) unsigned char smem[NW * 8192];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[NW * 32 * kRowPitch];
+  __shared__ __attribute__((aligned(16))) unsigned char qlds[NB * 32 * kRowPitch];
   __shared__ float sm_m[NW][NB * 32];
   __shared__ float sm_l[NW][NB * 32];
 
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5;
   const int l32 = lane & 31;
   const int h = blockIdx.x % p.Hkv;
@@ -60,63 +90,92 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
   const int nblk = (n + kPage - 1) / kPage;
   const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
 
-  // ---- query rows -> B operand of S^T = K Q^T: lane (row = l32, half) holds q[row][16kk+8half .. +8]
-  bf16x8 qreg[NB][8];
-  int limit[NB];                             // last visible token of this lane's row
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int row = nb * 32 + l32;
-    const bool valid = row < p.R;
-    const int t = valid ? row / p.g : 0;
-    const int j = valid ? row % p.g : 0;
-    const uint16_t* qp = p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + half * 8;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      u32x4 raw = {0u, 0u, 0u, 0u};
-      if (valid) raw = *reinterpret_cast<const u32x4*>(qp + kk * 16);
-      qreg[nb][kk] = __builtin_bit_cast(bf16x8, raw);
-    }
-    limit[nb] = CAUSAL ? (n - p.G + t) : (n - 1);
-  }
-
-  // ---- per-lane constant offsets
+  // ---- per-lane constants
   const int64_t head_off = static_cast<int64_t>(h) * p.head_stride;
-  // K load i: token 4i + lane/16 of the tile, 16-byte chunk lane%16
-  const int k_tok = lane >> 4;
-  const int k_chunk = lane & 15;
-  // V load (s, jj): token 16s + 8(jj/4) + 4*half + jj%4, head dims 4*l32 .. 4*l32+3
-  unsigned char* kst = smem + wave * 8192;
+  const int k_tok = lane >> 4;               // K load i: token 4i + lane/16 of the tile ...
+  const int k_chunk = lane & 15;             // ... 16-byte chunk lane%16
+  unsigned char* kst = smem + wave * (32 * kRowPitch);
 
-  auto issue = [&](int tile, TileRegs& r) {
-    const int pg0 = tile * 2;
-    const int pg1 = (pg0 + 1 < nblk) ? pg0 + 1 : pg0;          // a missing second page aliases the first
-    int64_t ph0 = table[pg0];
-    int64_t ph1 = table[pg1];
-    ph0 = ph0 < 0 ? 0 : (ph0 >= p.num_pages ? p.num_pages - 1 : ph0);
-    ph1 = ph1 < 0 ? 0 : (ph1 >= p.num_pages ? p.num_pages - 1 : ph1);
-    const uint16_t* kb0 = p.k + ph0 * p.page_stride + head_off;
-    const uint16_t* kb1 = p.k + ph1 * p.page_stride + head_off;
-    const uint16_t* vb0 = p.v + ph0 * p.page_stride + head_off;
-    const uint16_t* vb1 = p.v + ph1 * p.page_stride + head_off;
+  // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit per-lane byte offset.
+  const uint32_t ts_bytes = static_cast<uint32_t>(p.token_stride) * 2u;
+  const uint32_t k_lane_off = static_cast<uint32_t>(k_tok) * ts_bytes + static_cast<uint32_t>(k_chunk) * 16u;
+  const uint32_t v_lane_off = static_cast<uint32_t>(4 * half) * ts_bytes + static_cast<uint32_t>(l32) * 8u;
+  const int tile_end = (c1 + kTile - 1) / kTile;
+  const int tile_first = c0 / kTile + wave;
+
+  // Physical page ids of the wave's next 32 tiles live in one register: lane (k, half) holds the id of
+  // page `half` of tile tile_first + k*NW.  They are read back with readlane, so the streaming loop
+  // never waits on a page-table load.
+  int pagevec = 0;
+  auto load_pagevec = [&](int kbase) {
+    int page = 2 * (tile_first + (kbase + l32) * NW) + half;
+    page = page < nblk ? page : nblk - 1;
+    int64_t ph = table[page];
+    ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
+    pagevec = static_cast<int>(ph);
+  };
+  auto page_base = [&](const uint16_t* cache, int ph) -> const unsigned char* {
+    return uniform_ptr(reinterpret_cast<const unsigned char*>(cache + static_cast<int64_t>(ph) * p.page_stride + head_off));
+  };
+  // tile index k counts this wave's tiles: tile = tile_first + k*NW
+  auto issue_k = [&](int k, u32x4 (&kr)[8]) {
+    if ((k & 31) == 0) load_pagevec(k);
+    const int ph0 = __builtin_amdgcn_readlane(pagevec, k & 31);
+    const int ph1 = __builtin_amdgcn_readlane(pagevec, 32 + (k & 31));
+    const unsigned char* kb0 = page_base(p.k, ph0);
+    const unsigned char* kb1 = page_base(p.k, ph1);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int slot = (4 * i + k_tok) & 15;
-      const uint16_t* base = (i < 4) ? kb0 : kb1;
-      r.k[i] = *reinterpret_cast<const u32x4*>(base + slot * p.token_stride + k_chunk * 8);
+      const unsigned char* base = ((i < 4) ? kb0 : kb1) + static_cast<uint32_t>(4 * (i & 3)) * ts_bytes;
+      kr[i] = gload<u32x4>(base, k_lane_off);
     }
+  };
+  // V load (s, jj): token 16s + 8(jj/4) + 4*half + jj%4 of the tile, head dims 4*l32 .. 4*l32+3
+  auto issue_v = [&](int k, u32x2 (&vr)[16]) {
+    const int ph0 = __builtin_amdgcn_readlane(pagevec, k & 31);
+    const int ph1 = __builtin_amdgcn_readlane(pagevec, 32 + (k & 31));
+    const unsigned char* vb0 = page_base(p.v, ph0);
+    const unsigned char* vb1 = page_base(p.v, ph1);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      const uint16_t* base = s ? vb1 : vb0;
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
-        const int slot = 8 * (jj >> 2) + 4 * half + (jj & 3);
-        r.v[s * 8 + jj] = *reinterpret_cast<const u32x2*>(base + slot * p.token_stride + l32 * 4);
+        const unsigned char* base = (s ? vb1 : vb0) + static_cast<uint32_t>(8 * (jj >> 2) + (jj & 3)) * ts_bytes;
+        vr[s * 8 + jj] = gload<u32x2>(base, v_lane_off);
       }
     }
   };
 
-  // ---- running state: lane (row, half) keeps max m (shared by both halves), its half's partial sum l,
-  //      and O^T accumulators acc[nb][blk][i] = O[row][d = 4*(8(i/4) + 4half + i%4) + blk]
+  // ---- first tile's loads go out before anything else
+  u32x4 kr[8];
+  u32x2 va[16], vb[16];
+  if (tile_first < tile_end) {
+    issue_k(0, kr);
+    issue_v(0, va);
+  }
+
+  // ---- query rows -> LDS [row][16 chunks of 16 B], padded rows; rows past R are zero
+  for (int idx = tid; idx < NB * 32 * 16; idx += NW * 64) {
+    const int row = idx >> 4, chunk = idx & 15;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (row < p.R) {
+      const int t = row / p.g, j = row % p.g;
+      raw = *reinterpret_cast<const u32x4*>(
+          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + chunk * 8);
+    }
+    *reinterpret_cast<u32x4*>(qlds + row * kRowPitch + chunk * 16) = raw;
+  }
+  int limit[NB];                             // last visible token of this lane's row
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int row = nb * 32 + l32;
+    const int t = (row < p.R) ? row / p.g : 0;
+    limit[nb] = CAUSAL ? (n - p.G + t) : (n - 1);
+  }
+  __syncthreads();
+
+  // ---- running state: lane (row, half) keeps the row max m (same in both halves), its half's
+  //      partial sum l, and O^T accumulators acc[nb][blk][i] = O[row][4*(8(i/4) + 4half + i%4) + blk]
   float m_run[NB], l_run[NB];
   f32x16 acc[NB][4];
 #pragma unroll
@@ -129,14 +188,19 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
       for (int i = 0; i < 16; ++i) acc[nb][blk][i] = 0.f;
   }
 
-  auto compute = [&](int tile, TileRegs& r) {
-    const int tok0 = tile * kTile;
-    // K: registers -> swizzled LDS tile [32 tokens][16 chunks of 16 B]
+  // One tile: vcur holds this tile's V, vnxt receives the next tile's.
+  // (has_next is a compile-time property of the call site: a prefetch under a run-time branch would
+  // make the compiler's load-counter waits assume the worst case and drain the prefetch early.)
+  auto step = [&](int k, u32x2 (&vcur)[16], u32x2 (&vnxt)[16], auto has_next_tag) {
+    constexpr bool has_next = decltype(has_next_tag)::value;
+    const int cur = tile_first + k * NW;
+    const int tok0 = cur * kTile;
+    // K: registers -> LDS tile [32 tokens][16 chunks of 16 B]; then refill the registers
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int tok = 4 * i + k_tok;
-      *reinterpret_cast<u32x4*>(kst + tok * 256 + ((k_chunk ^ (tok & 15)) << 4)) = r.k[i];
+      *reinterpret_cast<u32x4*>(kst + (4 * i + k_tok) * kRowPitch + k_chunk * 16) = kr[i];
     }
+    if (has_next) issue_k(k + 1, kr);
     wave_lds_fence();
     f32x16 st[NB];
 #pragma unroll
@@ -145,52 +209,52 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
       for (int i = 0; i < 16; ++i) st[nb][i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const int chunk = 2 * kk + half;
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(kst + l32 * 256 + ((chunk ^ (l32 & 15)) << 4));
-      const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+      const int off = l32 * kRowPitch + half * 16 + kk * 32;
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kst + off));
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[nb][kk], st[nb], 0, 0, 0);
+      for (int nb = 0; nb < NB; ++nb) {
+        const bf16x8 qb =
+            __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qlds + nb * 32 * kRowPitch + off));
+        st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qb, st[nb], 0, 0, 0);
+      }
     }
     wave_lds_fence();
+    if (has_next) issue_v(k + 1, vnxt);
 
     const bool tail = (tok0 + kTile > n) || (CAUSAL && (tok0 + kTile - 1 > n - p.G));
     bf16x8 pb[NB][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      float s[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = st[nb][i] * p.scale_log2e;
       if (tail) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int tok = tok0 + 8 * (i >> 2) + 4 * half + (i & 3);
-          if (tok > limit[nb]) s[i] = -INFINITY;
+          if (tok > limit[nb]) st[nb][i] = -INFINITY;
         }
       }
-      float tmax = s[0];
+      float tmax = st[nb][0];
 #pragma unroll
-      for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, s[i]);
-      tmax = fmaxf(tmax, xhalf(tmax));
+      for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, st[nb][i]);
+      tmax = half_max(tmax) * p.scale_log2e;               // scale > 0: max commutes with scaling
       const float m_new = fmaxf(m_run[nb], tmax);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
       const float alpha = fast_exp2(m_run[nb] - m_use);
       float pr[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) pr[i] = fast_exp2(s[i] - m_use);
+      for (int i = 0; i < 16; ++i) pr[i] = fast_exp2(__builtin_fmaf(st[nb][i], p.scale_log2e, -m_use));
       float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) { ps0 += pr[i]; ps1 += pr[8 + i]; }
       l_run[nb] = l_run[nb] * alpha + (ps0 + ps1);
       m_run[nb] = m_new;
       if (COLLECT) {
-        const float f0 = ps0 + xhalf(ps0);
-        const float f1 = ps1 + xhalf(ps1);
+        const float f0 = half_sum(ps0);
+        const float f1 = half_sum(ps1);
         const int row = nb * 32 + l32;
-        const int page = tile * 2 + half;
+        const int page = cur * 2 + half;
         if (row < p.R && page < nblk) {
           const float lse = m_use + fast_log2(half ? f1 : f0);
-          p.page_lse[((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + page) * p.R + row] = lse;
+          p.page_lse[((static_cast<int64_t>(b) * p.lse_pages + page) * p.Hkv + h) * p.R + row] = lse;
         }
       }
       if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
@@ -211,7 +275,7 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
           const int tok = tok0 + 16 * s2 + 8 * (jj >> 2) + 4 * half + (jj & 3);
-          if (tok >= n) r.v[s2 * 8 + jj] = u32x2{0u, 0u};
+          if (tok >= n) vcur[s2 * 8 + jj] = u32x2{0u, 0u};
         }
     }
 #pragma unroll
@@ -221,8 +285,8 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
         u32x4 raw;
 #pragma unroll
         for (int pp = 0; pp < 4; ++pp) {
-          const u32x2 ev = r.v[s2 * 8 + 2 * pp];
-          const u32x2 od = r.v[s2 * 8 + 2 * pp + 1];
+          const u32x2 ev = vcur[s2 * 8 + 2 * pp];
+          const u32x2 od = vcur[s2 * 8 + 2 * pp + 1];
           const unsigned lo = (blk < 2) ? ev[0] : ev[1];
           const unsigned hi = (blk < 2) ? od[0] : od[1];
           raw[pp] = __builtin_amdgcn_perm(hi, lo, (blk & 1) ? 0x07060302u : 0x05040100u);
@@ -235,25 +299,22 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
     }
   };
 
-  // ---- stream the chunk's tiles, next tile's loads in flight during the current tile's math
-  {
-    TileRegs ra, rb;
-    int tile = c0 / kTile + wave;
-    const int tile_end = (c1 + kTile - 1) / kTile;
-    if (tile < tile_end) {
-      issue(tile, ra);
-      while (true) {
-        int nxt = tile + NW;
-        if (nxt < tile_end) issue(nxt, rb);
-        compute(tile, ra);
-        if (nxt >= tile_end) break;
-        tile = nxt;
-        nxt = tile + NW;
-        if (nxt < tile_end) issue(nxt, ra);
-        compute(tile, rb);
-        if (nxt >= tile_end) break;
-        tile = nxt;
-      }
+  // ---- stream the chunk's tiles
+  if (tile_first < tile_end) {
+    const int ntiles = (tile_end - tile_first + NW - 1) / NW;      // this wave's tiles
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int k = 0;
+    while (k + 2 < ntiles) {
+      step(k, va, vb, yes{});
+      step(k + 1, vb, va, yes{});
+      k += 2;
+    }
+    if (k + 1 < ntiles) {
+      step(k, va, vb, yes{});
+      step(k + 1, vb, va, no{});
+    } else {
+      step(k, va, vb, no{});
     }
   }
 
@@ -272,8 +333,7 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
     m_wg[nb] = mw;
     const float m_use = (mw == -INFINITY) ? 0.f : mw;
     const float sc = fast_exp2(m_run[nb] - m_use);
-    float lsum = l_run[nb] * sc;
-    lsum += xhalf(lsum);
+    const float lsum = half_sum(l_run[nb] * sc);
     if (half == 0) sm_l[wave][nb * 32 + l32] = lsum;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)

@@ -3,6 +3,7 @@
 #include "../../include/vegas.h"
 
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "attn_finalize.hpp"
 #include "attn_split.hpp"
@@ -43,7 +44,7 @@ int check_common(const vegas_desc* d) {
 // Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
 int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, SplitPlan* pl) {
   pl->R = rows_per_head;
-  if (rows_per_head <= 32) { pl->NB = 1; pl->NW = 8; }
+  if (rows_per_head <= 32) { pl->NB = 1; pl->NW = 8; if (getenv("VEGAS_NW4")) pl->NW = 4; }
   else if (rows_per_head <= 64) { pl->NB = 2; pl->NW = 4; }
   else return VEGAS_ERR_UNSUPPORTED;
   const int unit = kTile * pl->NW;
@@ -86,7 +87,9 @@ int plan_draft(const vegas_desc* d, SplitPlan* pl) {
 template <bool CAUSAL, bool COLLECT>
 int launch_split(const SplitPlan& pl, const SplitParams& sp, int batch, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
-  if (pl.NB == 1)
+  if (pl.NB == 1 && pl.NW == 4)
+    hipLaunchKernelGGL((attn_split_kernel<1, 4, CAUSAL, COLLECT>), grid, dim3(256), 0, st, sp);
+  else if (pl.NB == 1)
     hipLaunchKernelGGL((attn_split_kernel<1, 8, CAUSAL, COLLECT>), grid, dim3(512), 0, st, sp);
   else
     hipLaunchKernelGGL((attn_split_kernel<2, 4, CAUSAL, COLLECT>), grid, dim3(256), 0, st, sp);
@@ -189,7 +192,7 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
                                                                      : (desc->num_queries > 1 ? 2 : 1);
     sc.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
     const size_t shm = static_cast<size_t>(sp.Hkv) * pl.R * sizeof(float);
-    hipLaunchKernelGGL(block_score_kernel, dim3((desc->max_blocks + 255) / 256, desc->batch), dim3(256), shm, st, sc);
+    hipLaunchKernelGGL(block_score_kernel, dim3((desc->max_blocks + 3) / 4, desc->batch), dim3(256), shm, st, sc);
     if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
   }
   return VEGAS_OK;
