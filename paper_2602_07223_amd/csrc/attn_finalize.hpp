@@ -6,28 +6,61 @@ namespace vegas {
 
 // One workgroup of 128 threads (= head dims) per (query row, KV head, sequence): merges the
 // chunk partials of that row with the usual max/sum bookkeeping (all in log2 units), writes the
-// bf16 output row (Eq. 1) and the row's global log2-sum-exp2.
+// bf16 output row (Eq. 1) and the row's global log2-sum-exp2.  The per-chunk (max, sum) pairs are
+// fetched by one thread each, so the whole merge costs two dependent memory round trips.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p) {
+  __shared__ float sw[128];
+  __shared__ float sred[4];
   const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int d = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
+  const float2* ml = p.part_ml + pbase * p.R + r;                 // stride R between chunks
+  const float* po = p.part_o + (pbase * p.R + r) * kHeadDim + tid; // stride R*128 between chunks
+  const int64_t ostride = static_cast<int64_t>(p.R) * kHeadDim;
+
+  // pass 1: global max over chunks
   float m = -INFINITY;
-  for (int s = 0; s < ns; ++s) m = fmaxf(m, p.part_ml[(pbase + s) * p.R + r].x);
+  for (int s = tid; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  if ((tid & 63) == 0) sred[wave] = m;
+  __syncthreads();
+  m = fmaxf(sred[0], sred[1]);
   const float m_use = (m == -INFINITY) ? 0.f : m;
+
+  // pass 2: weights of up to 128 chunks at a time, then the weighted sum of the partial rows
   float accv = 0.f, L = 0.f;
-  for (int s = 0; s < ns; ++s) {
-    const float2 ml = p.part_ml[(pbase + s) * p.R + r];
-    const float w = fast_exp2(ml.x - m_use);
-    L += w * ml.y;
-    accv += w * p.part_o[((pbase + s) * p.R + r) * kHeadDim + d];
+  for (int s0 = 0; s0 < ns; s0 += 128) {
+    const int cnt = min(128, ns - s0);
+    float wl = 0.f;
+    if (tid < cnt) {
+      const float2 v = ml[static_cast<int64_t>(s0 + tid) * p.R];
+      const float w = fast_exp2(v.x - m_use);
+      sw[tid] = w;
+      wl = w * v.y;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 64);
+    if ((tid & 63) == 0) sred[2 + wave] = wl;
+    __syncthreads();
+    L += sred[2] + sred[3];
+    int s = 0;
+    for (; s + 4 <= cnt; s += 4) {
+      const float x0 = po[(s0 + s) * ostride], x1 = po[(s0 + s + 1) * ostride];
+      const float x2 = po[(s0 + s + 2) * ostride], x3 = po[(s0 + s + 3) * ostride];
+      accv += sw[s] * x0 + sw[s + 1] * x1 + sw[s + 2] * x2 + sw[s + 3] * x3;
+    }
+    for (; s < cnt; ++s) accv += sw[s] * po[(s0 + s) * ostride];
+    __syncthreads();
   }
   const float o = (L > 0.f) ? accv / L : 0.f;
   const int t = r / p.g, j = r % p.g;
-  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + d] = float_to_bf16_bits(o);
-  if (p.row_lse != nullptr && d == 0)
+  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
+  if (p.row_lse != nullptr && tid == 0)
     p.row_lse[(static_cast<int64_t>(b) * p.Hkv + h) * p.R + r] = (L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
 }
 

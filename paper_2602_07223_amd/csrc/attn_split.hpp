@@ -65,13 +65,17 @@ __device__ __forceinline__ T gload(const unsigned char* sbase, uint32_t voff) {
 
 constexpr int kRowPitch = 272;   // LDS bytes per 256-byte K/Q row: the 16-byte pad spreads rows over banks
 
-template <int NB, int NW, bool CAUSAL, bool COLLECT>
-__global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p) {
-  // K staging (NW x 8 KB), reused for the cross-wave merge of the output accumulators.
-  __shared__ __attribute__((aligned(16))) unsigned char smem[NW * 32 * kRowPitch];
-  __shared__ __attribute__((aligned(16))) unsigned char qlds[NB * 32 * kRowPitch];
-  __shared__ float sm_m[NW][NB * 32];
-  __shared__ float sm_l[NW][NB * 32];
+constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffer (128 + pad)
+
+// NB: 32-row blocks of query rows; NW: waves per workgroup; WPS: waves per SIMD the register
+// budget is sized for (2 -> at most 256 registers per lane).
+template <int NB, int NW, int WPS, bool CAUSAL, bool COLLECT>
+__global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
+  // Dynamic LDS: [K staging, NW tiles | merge buffer NW x R rows][queries][row maxima][row sums]
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* qlds = smem + p.lds_q_off;
+  float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
+  float* sm_l = sm_m + NW * NB * 32;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -318,83 +322,63 @@ __global__ __launch_bounds__(NW * 64) void attn_split_kernel(const SplitParams p
     }
   }
 
-  // ---- merge the NW waves
+  // ---- merge the NW waves: exchange row maxima, rescale, park the valid rows of every wave's
+  //      accumulators in LDS as [wave][row][d], then all threads add across waves and write the
+  //      workgroup's partial result with consecutive threads on consecutive addresses.
   if (half == 0) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) sm_m[wave][nb * 32 + l32] = m_run[nb];
+    for (int nb = 0; nb < NB; ++nb) sm_m[wave * (NB * 32) + nb * 32 + l32] = m_run[nb];
   }
-  __syncthreads();
-  float m_wg[NB];
+  __syncthreads();                                       // also: every wave is done with its K tile
+  float* red = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
+    const int row = nb * 32 + l32;
     float mw = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) mw = fmaxf(mw, sm_m[w][nb * 32 + l32]);
-    m_wg[nb] = mw;
+    for (int w = 0; w < NW; ++w) mw = fmaxf(mw, sm_m[w * (NB * 32) + row]);
     const float m_use = (mw == -INFINITY) ? 0.f : mw;
     const float sc = fast_exp2(m_run[nb] - m_use);
     const float lsum = half_sum(l_run[nb] * sc);
-    if (half == 0) sm_l[wave][nb * 32 + l32] = lsum;
+    if (half == 0) sm_l[wave * (NB * 32) + row] = lsum;
+    if (row < p.R) {
+      float* dst = red + (wave * p.R + row) * kRedPitch;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[nb][blk][i] *= sc;
-  }
-  f32x4* red = reinterpret_cast<f32x4*>(smem);          // [slot][16 quads][64 lanes] per row block
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-    for (int stride = NW / 2; stride >= 1; stride >>= 1) {
-      __syncthreads();
-      if (wave >= stride && wave < 2 * stride) {
-        f32x4* dst = red + (wave - stride) * 16 * 64;
-#pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-          for (int qd = 0; qd < 4; ++qd)
-            dst[(blk * 4 + qd) * 64 + lane] = f32x4{acc[nb][blk][4 * qd], acc[nb][blk][4 * qd + 1],
-                                                    acc[nb][blk][4 * qd + 2], acc[nb][blk][4 * qd + 3]};
-      }
-      __syncthreads();
-      if (wave < stride) {
-        const f32x4* src = red + wave * 16 * 64;
-#pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-          for (int qd = 0; qd < 4; ++qd) {
-            const f32x4 x = src[(blk * 4 + qd) * 64 + lane];
-            acc[nb][blk][4 * qd] += x[0];
-            acc[nb][blk][4 * qd + 1] += x[1];
-            acc[nb][blk][4 * qd + 2] += x[2];
-            acc[nb][blk][4 * qd + 3] += x[3];
-          }
+      for (int i = 0; i < 16; ++i) {
+        const int d0 = 4 * (8 * (i >> 2) + 4 * half + (i & 3));
+        *reinterpret_cast<f32x4*>(dst + d0) =
+            f32x4{acc[nb][0][i] * sc, acc[nb][1][i] * sc, acc[nb][2][i] * sc, acc[nb][3][i] * sc};
       }
     }
   }
-  if (NW == 1) __syncthreads();
+  __syncthreads();
+  const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
+  float* po = p.part_o + pbase * p.R * kHeadDim;
+  for (int e = tid; e < p.R * kHeadDim; e += NW * 64) {
+    const int row = e >> 7, d = e & 127;
+    float sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) sum += red[(w * p.R + row) * kRedPitch + d];
+    po[e] = sum;
+  }
+  if (tid < p.R) {
+    float mw = -INFINITY, lw = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      mw = fmaxf(mw, sm_m[w * (NB * 32) + tid]);
+      lw += sm_l[w * (NB * 32) + tid];
+    }
+    p.part_ml[pbase * p.R + tid] = make_float2(mw, lw);
+  }
+}
 
-  if (wave == 0) {
-    const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int row = nb * 32 + l32;
-      if (row < p.R) {
-        float* po = p.part_o + (pbase * p.R + row) * kHeadDim;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int d0 = 4 * (8 * (i >> 2) + 4 * half + (i & 3));
-          *reinterpret_cast<f32x4*>(po + d0) =
-              f32x4{acc[nb][0][i], acc[nb][1][i], acc[nb][2][i], acc[nb][3][i]};
-        }
-        if (half == 0) {
-          float lw = 0.f;
-#pragma unroll
-          for (int w = 0; w < NW; ++w) lw += sm_l[w][row];
-          p.part_ml[pbase * p.R + row] = make_float2(m_wg[nb], lw);
-        }
-      }
-    }
-  }
+// Dynamic LDS bytes of attn_split_kernel<NB, NW, ...> for R valid rows.
+inline size_t split_lds_bytes(int NB, int NW, int R) {
+  size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch;
+  const size_t red = static_cast<size_t>(NW) * R * kRedPitch * sizeof(float);
+  if (red > stage) stage = red;
+  stage = (stage + 15) / 16 * 16;
+  return stage + static_cast<size_t>(NB) * 32 * kRowPitch + 2 * static_cast<size_t>(NW) * NB * 32 * sizeof(float);
 }
 
 }  // namespace vegas

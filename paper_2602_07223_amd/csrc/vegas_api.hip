@@ -42,16 +42,25 @@ int check_common(const vegas_desc* d) {
 }
 
 // Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
+// max_len bounds the lengths the call may see; small problems get small workgroups.
 int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, SplitPlan* pl) {
   pl->R = rows_per_head;
-  if (rows_per_head <= 32) { pl->NB = 1; pl->NW = 8; if (getenv("VEGAS_NW4")) pl->NW = 4; }
-  else if (rows_per_head <= 64) { pl->NB = 2; pl->NW = 4; }
-  else return VEGAS_ERR_UNSUPPORTED;
+  const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
+  const int64_t tiles = heads * ((max_len + kTile - 1) / kTile);       // upper bound on 32-token tiles
+  if (rows_per_head <= 32) {
+    pl->NB = 1;
+    pl->NW = (tiles >= 4 * 8 * kNumCU) ? 8 : 4;      // enough work for 8-wave groups of >= 4 tiles per wave
+    if (const char* e = getenv("VEGAS_NW")) pl->NW = (atoi(e) == 8) ? 8 : 4;
+  } else if (rows_per_head <= 64) {
+    pl->NB = 2;
+    pl->NW = 4;
+  } else {
+    return VEGAS_ERR_UNSUPPORTED;
+  }
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
-    const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
-    const int64_t slots = kNumCU * (pl->NW == 8 ? 1 : 2);
+    const int64_t slots = kNumCU * ((pl->NB == 1 && pl->NW == 4) ? 2 : 1);
     int64_t splits = slots / heads;
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
@@ -62,12 +71,12 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_ls
   pl->chunk = chunk;
   pl->nsplit = (max_len + chunk - 1) / chunk;
   pl->lse_pages = with_lse ? (max_len + kPage - 1) / kPage : 0;
-  const size_t heads = static_cast<size_t>(d->batch) * d->num_kv_heads;
   size_t off = 0;
-  pl->off_part_o = off;  off += align_up(heads * pl->nsplit * pl->R * kHeadDim * sizeof(float));
-  pl->off_part_ml = off; off += align_up(heads * pl->nsplit * pl->R * sizeof(float2));
-  pl->off_row_lse = off; off += align_up(heads * pl->R * sizeof(float));
-  pl->off_page_lse = off; off += align_up(heads * static_cast<size_t>(pl->lse_pages) * pl->R * sizeof(float));
+  const size_t hs = static_cast<size_t>(heads);
+  pl->off_part_o = off;  off += align_up(hs * pl->nsplit * pl->R * kHeadDim * sizeof(float));
+  pl->off_part_ml = off; off += align_up(hs * pl->nsplit * pl->R * sizeof(float2));
+  pl->off_row_lse = off; off += align_up(hs * pl->R * sizeof(float));
+  pl->off_page_lse = off; off += align_up(hs * static_cast<size_t>(pl->lse_pages) * pl->R * sizeof(float));
   pl->total = off;
   return VEGAS_OK;
 }
@@ -84,16 +93,32 @@ int plan_draft(const vegas_desc* d, SplitPlan* pl) {
   return plan_split(d, g, d->max_seq_len, false, pl);
 }
 
-template <bool CAUSAL, bool COLLECT>
-int launch_split(const SplitPlan& pl, const SplitParams& sp, int batch, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
-  if (pl.NB == 1 && pl.NW == 4)
-    hipLaunchKernelGGL((attn_split_kernel<1, 4, CAUSAL, COLLECT>), grid, dim3(256), 0, st, sp);
-  else if (pl.NB == 1)
-    hipLaunchKernelGGL((attn_split_kernel<1, 8, CAUSAL, COLLECT>), grid, dim3(512), 0, st, sp);
-  else
-    hipLaunchKernelGGL((attn_split_kernel<2, 4, CAUSAL, COLLECT>), grid, dim3(256), 0, st, sp);
+// Launch with dynamic LDS; sizes above 64 KB need the attribute raised once per kernel.
+template <typename Kern>
+int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, const SplitParams& sp) {
+  static size_t allowed = 64 * 1024;                 // per instantiation of this template
+  if (lds > allowed) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(160 * 1024)) != hipSuccess)
+      return VEGAS_ERR_LAUNCH;
+    allowed = 160 * 1024;
+  }
+  hipLaunchKernelGGL(kern, grid, block, lds, st, sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+template <bool CAUSAL, bool COLLECT>
+int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st) {
+  const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
+  const size_t lds = split_lds_bytes(pl.NB, pl.NW, pl.R);
+  sp.lds_q_off = static_cast<int32_t>(lds - static_cast<size_t>(pl.NB) * 32 * kRowPitch -
+                                      2 * static_cast<size_t>(pl.NW) * pl.NB * 32 * sizeof(float));
+  if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
+  if (pl.NB == 1 && pl.NW == 4)
+    return launch_one(attn_split_kernel<1, 4, 2, CAUSAL, COLLECT>, grid, dim3(256), lds, st, sp);
+  if (pl.NB == 1)
+    return launch_one(attn_split_kernel<1, 8, 2, CAUSAL, COLLECT>, grid, dim3(512), lds, st, sp);
+  return launch_one(attn_split_kernel<2, 4, 1, CAUSAL, COLLECT>, grid, dim3(256), lds, st, sp);
 }
 
 void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const void* q, const void* k,

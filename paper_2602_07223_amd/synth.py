@@ -15,7 +15,7 @@ a KV budget of a few percent of the context, gamma of 4-6.
 Draw order inside one ``make_layer`` call (fixed; changing it changes every tensor):
   1. seq_lens                      (ragged configs only)
   2. physical page permutation     (shuffled configs only)
-  3. K pool normals, V pool normals (physical order, float32)
+  3. K pool, V pool (physical order; jumped streams of the same seed, see normal_pool_bf16)
   4. verify-query normals
   5. per (sequence, KV head) directions u [, v_old, v_new]
   6. hitter run starts / positions per sequence [, drift positions]
@@ -34,9 +34,19 @@ BF16_NAN = np.uint16(0x7FC0)
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """float32 -> bf16 bit pattern, round to nearest even (finite inputs)."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
-    return r.astype(np.uint16)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    flat_in, flat_out = x.reshape(-1).view(np.uint32), out.reshape(-1)
+    step = 1 << 20                                    # cache-sized pieces, few temporaries
+    for i in range(0, flat_in.size, step):
+        u = flat_in[i:i + step]
+        r = u >> np.uint32(16)
+        r &= np.uint32(1)
+        r += np.uint32(0x7FFF)
+        r += u
+        r >>= np.uint32(16)
+        flat_out[i:i + step] = r
+    return out
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -127,6 +137,30 @@ class LayerInputs:
         return int(self.block_table.shape[1])
 
 
+_POOL_CHUNK_PAGES = 1024
+
+
+def normal_pool_bf16(seed: int, stream: int, shape, std: float, workers: int = 8) -> np.ndarray:
+    """bf16 bits of N(0, std^2) samples of `shape`, drawn in pieces of 1024 leading-axis entries.
+    Piece c of stream s uses PCG64(seed).jumped(1 + 65536*s + c), so the result does not depend on
+    the number of worker threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    out = np.empty(shape, dtype=np.uint16)
+    n0 = shape[0]
+    pieces = [(c, lo, min(lo + _POOL_CHUNK_PAGES, n0)) for c, lo in enumerate(range(0, n0, _POOL_CHUNK_PAGES))]
+
+    def work(item):
+        c, lo, hi = item
+        g = np.random.Generator(np.random.PCG64(seed).jumped(1 + 65536 * stream + c))
+        x = g.standard_normal((hi - lo,) + tuple(shape[1:]), dtype=np.float32)
+        x *= np.float32(std)
+        out[lo:hi] = f32_to_bf16_bits(x)
+
+    with ThreadPoolExecutor(max_workers=max(1, workers)) as ex:
+        list(ex.map(work, pieces))
+    return out
+
+
 def _unit_rows(rng: np.random.Generator, shape) -> np.ndarray:
     x = rng.standard_normal(shape, dtype=np.float32)
     x /= np.linalg.norm(x, axis=-1, keepdims=True)
@@ -194,13 +228,9 @@ def make_layer(spec: WorkloadSpec, layer: int = 0) -> LayerInputs:
         off += int(nblk[b])
     spare_ids = perm[off:]
 
-    # 3. pools
-    def pool() -> np.ndarray:
-        x = rng.standard_normal((num_pages, PAGE, Hkv, D), dtype=np.float32)
-        x *= np.float32(std)
-        return x
-    k_pool = pool()
-    v_pool = pool()
+    # 3. pools (bf16 bits; drawn from jumped streams of the same seed, in parallel)
+    k_bits = normal_pool_bf16(seed, 0, (num_pages, PAGE, Hkv, D), std)
+    v_bits = normal_pool_bf16(seed, 1, (num_pages, PAGE, Hkv, D), std)
 
     # 4. verify queries
     qv = rng.standard_normal((B, G, Hq, D), dtype=np.float32) * np.float32(std)
@@ -224,8 +254,9 @@ def make_layer(spec: WorkloadSpec, layer: int = 0) -> LayerInputs:
             return
         pages = block_table[b, pos // PAGE]
         slots = pos % PAGE
-        # direction: [Hkv, D]
-        k_pool[pages, slots] += np.float32(gain) * key_gain * direction[None, :, :]
+        # direction: [Hkv, D]; the planted component is added to the (already rounded) base key
+        base = bf16_bits_to_f32(k_bits[pages, slots])
+        k_bits[pages, slots] = f32_to_bf16_bits(base + np.float32(gain) * key_gain * direction[None, :, :])
 
     for b in range(B):
         n = int(seq_lens[b])
@@ -270,11 +301,6 @@ def make_layer(spec: WorkloadSpec, layer: int = 0) -> LayerInputs:
     qd = np.transpose(q_base, (1, 0, 2, 3)) + noise + u_q[None, :, :, :]
     if spec.drift > 0:
         qd += np.repeat(v_new, g, axis=1)[None, :, :, :]
-
-    k_bits = f32_to_bf16_bits(k_pool)
-    del k_pool
-    v_bits = f32_to_bf16_bits(v_pool)
-    del v_pool
 
     # poison: spare pages and (optionally) the unused slots of partial last pages
     if spare_ids.size:

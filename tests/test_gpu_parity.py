@@ -116,6 +116,32 @@ def test_baseline_config2_full():
     assert set(np.unique(L.sinks[0] // PAGE)).issubset(ids)
 
 
+def test_baseline_config3_full():
+    """128K context, gamma = 6, heavy hitters drifting between verify and draft queries."""
+    L = synth.make_layer(synth.CONFIGS["ctx128k_drift"])
+    path, _, _ = run_chain(L, L.spec.budget_tokens, name="ctx128k_drift")
+    sel = path.sel_table.cpu().numpy()[0]
+    inv = {int(p): j for j, p in enumerate(L.block_table[0])}
+    ids = {inv[int(p)] for p in sel if p >= 0}
+    assert set(np.unique(L.hitters[0] // PAGE)).issubset(ids)        # what the verify queries saw is kept
+    assert ids.__len__() == L.spec.budget_tokens // PAGE
+
+
+def test_baseline_config4_full():
+    """Batch 16, ragged 8K-64K contexts, 64 query heads (40 rows per KV head), shuffled pages,
+    NaN poison in spare pages and in the slack of partial last pages."""
+    L = synth.make_layer(synth.CONFIGS["ragged16"])
+    assert len(set(int(x) % PAGE for x in L.seq_lens)) > 1            # partial last pages occur
+    run_chain(L, L.spec.budget_tokens, name="ragged16")
+
+
+@pytest.mark.parametrize("layer", [0, 13, 31])
+def test_baseline_config5_sampled_layers(layer):
+    """The 32-layer stack is 32 independent single-layer calls; three layers are checked in full."""
+    L = synth.make_layer(synth.CONFIGS["stack32"], layer=layer)
+    run_chain(L, L.spec.budget_tokens, name=f"stack32.layer{layer}")
+
+
 def test_empty_and_short_sequences():
     L = synth.make_random_case(seed=79, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
                                seq_lens=[0, 3, 40], spare_pages=2)
