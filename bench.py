@@ -10,9 +10,10 @@ Cold-cache protocol: the 128 MiB of K+V of this workload would fit in the last-l
 serving engine never enjoys (dozens of layers' caches pass between two visits of the same layer),
 so consecutive steps rotate over several device copies of the cache (>= 1 GiB in total).
 
-Prints ONE JSON line: whole-path us per iteration, the roofline of the dominant kernel (the
-KV-streaming verification kernel, timed with HIP events recorded on the launch stream around that
-kernel inside the timed region) and the CPU oracle timed on the host cores as a reported baseline.
+Prints ONE JSON line: whole-path us per iteration (timed region = K iterations, nothing else on the
+stream), the roofline of the dominant kernel (the KV-streaming verification kernel: K back-to-back
+launches of that kernel alone over the same rotating caches, bracketed by two HIP events on the
+launch stream) and the CPU oracle timed on the host cores as a reported baseline.
 """
 from __future__ import annotations
 
@@ -27,6 +28,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the verification streaming kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until measured.
+VERIFY_TRAFFIC_BYTES = None
 WORKLOAD = "ctx32k"
 
 
@@ -91,44 +95,60 @@ def main() -> int:
                                           block_table=base.block_table, seq_lens=base.seq_lens))
     path = harness.VegasPath.for_layer(L, verify_chunk=args.verify_chunk, draft_chunk=args.draft_chunk)
     G = spec.num_queries
-    stream = torch.cuda.current_stream(dev)
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
 
     K, W = args.steps, args.warmup
-    use_ev = not args.no_kernel_events
-    ev = [(vb.HipEvent(), vb.HipEvent()) for _ in range(K)] if use_ev else []
 
-    def step(i: int, timed: bool) -> None:
-        dl = copies[i % len(copies)]
-        if use_ev and timed:
-            path.desc_verify.ev_kernel_begin = ev[i][0].handle
-            path.desc_verify.ev_kernel_end = ev[i][1].handle
-        path.iteration(dl)
+    def step(i: int) -> None:
+        path.iteration(copies[i % len(copies)])
 
     for i in range(W):
-        step(i, False)
+        step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        step(i, True)
+        step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    path.desc_verify.ev_kernel_begin = None
-    path.desc_verify.ev_kernel_end = None
-
     us_per_step = dt / K * 1e6
+
     n_tokens = int(L.seq_lens.sum())
     bytes_per_token = 2 * spec.num_kv_heads * spec.head_dim * 2          # K and V, bf16: 4096 B
     verify_bytes = n_tokens * bytes_per_token                            # algorithmic bytes of one launch
-    roofline = {"bound": "hbm", "kernel": "attn_split_kernel<1,8,causal,collect> (verification)",
-                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None,
+    sel_tokens = int(path.sel_seq_lens.sum().item())
+    draft_bytes = sel_tokens * bytes_per_token
+
+    def kernel_leg(call, desc, reps: int) -> float:
+        """Average duration of one KV-streaming kernel: `reps` back-to-back launches of that kernel
+        alone (launch_stages = STREAM), bracketed by two HIP events on the launch stream."""
+        desc.launch_stages = vb.STAGE_STREAM
+        e0, e1 = vb.HipEvent(), vb.HipEvent()
+        for i in range(5):
+            call(i)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(reps):
+            call(i)
+        e1.record(stream)
+        e1.synchronize()
+        desc.launch_stages = 0
+        return e0.elapsed_ms(e1) / reps * 1e3
+
+    roofline = {"bound": "hbm", "kernel": "attn_split_kernel<causal, collect> (KV-streaming kernel of vegas_verify_attention)",
+                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": VERIFY_TRAFFIC_BYTES,
                 "bytes_per_launch": verify_bytes}
-    if use_ev:
-        ms = [a.elapsed_ms(b) for a, b in ev]
-        avg_ms = sum(ms) / len(ms)
-        roofline["kernel_us"] = avg_ms * 1e3
-        roofline["achieved"] = verify_bytes / (avg_ms * 1e-3) / 1e9
+    roofline_draft = None
+    if not args.no_kernel_events:
+        v_us = kernel_leg(lambda i: path.verify(copies[i % len(copies)]), path.desc_verify, K)
+        roofline["kernel_us"] = v_us
+        roofline["achieved"] = verify_bytes / (v_us * 1e-6) / 1e9
         roofline["frac"] = roofline["achieved"] / HBM_PEAK_GBS
-    iter_bytes = verify_bytes + G * int(path.sel_seq_lens.sum().item()) * bytes_per_token
+        d_us = kernel_leg(lambda i: path.draft(copies[i % len(copies)], i % G), path.desc_draft, K)
+        roofline_draft = {"bound": "hbm", "kernel": "attn_split_kernel (KV-streaming kernel of vegas_draft_attention)",
+                          "kernel_us": d_us, "achieved": draft_bytes / (d_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": draft_bytes / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                          "bytes_per_launch": draft_bytes, "traffic": None}
+    iter_bytes = verify_bytes + G * draft_bytes
     out = {
         "metric": "us_per_verify_select_draft_iteration", "value": us_per_step, "unit": "us",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": us_per_step / 1e3,
@@ -143,6 +163,8 @@ def main() -> int:
         "iteration_gbps": iter_bytes / (us_per_step * 1e-6) / 1e9,
         "roofline": roofline,
     }
+    if roofline_draft is not None:
+        out["roofline_draft"] = roofline_draft
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens)
     print(json.dumps(out), flush=True)

@@ -55,6 +55,12 @@ enum {
   VEGAS_COLLECT_FIRST_LAST = 2  /* Eq. 3: first draft row and bonus row */
 };
 
+/* Kernels of an attention call, for vegas_desc.launch_stages. */
+enum {
+  VEGAS_STAGE_STREAM = 1,  /* the KV-streaming kernel (reads the cache, writes chunk partials) */
+  VEGAS_STAGE_MERGE = 2    /* merge of the chunk partials, and the page scores for verification */
+};
+
 typedef struct vegas_desc {
   int32_t batch;           /* B: sequences */
   int32_t num_q_heads;     /* H_q */
@@ -68,6 +74,8 @@ typedef struct vegas_desc {
                               launch grid and the workspace; <= max_blocks*page_size */
   int32_t collect_rows;    /* VEGAS_COLLECT_* */
   int32_t kv_chunk_tokens; /* tokens of one sequence handled by one workgroup; 0 = choose */
+  int32_t launch_stages;   /* profiling aid: 0 = whole call; else VEGAS_STAGE_* bits to launch only
+                              those kernels of an attention call (outputs then incomplete) */
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
   int64_t num_pages;       /* pages in each cache (device-side clamp of page ids) */
   int64_t kv_page_stride;  /* elements between pages */

@@ -25,6 +25,9 @@ COLLECT_NONE = 0
 COLLECT_ALL_ROWS = 1
 COLLECT_FIRST_LAST = 2
 
+STAGE_STREAM = 1
+STAGE_MERGE = 2
+
 EXPORTS = ("vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
            "vegas_draft_attention", "vegas_strerror")
 
@@ -43,6 +46,7 @@ class VegasDesc(ctypes.Structure):
         ("max_seq_len", ctypes.c_int32),
         ("collect_rows", ctypes.c_int32),
         ("kv_chunk_tokens", ctypes.c_int32),
+        ("launch_stages", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
         ("num_pages", ctypes.c_int64),
         ("kv_page_stride", ctypes.c_int64),
@@ -123,6 +127,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
     d.head_dim, d.page_size, d.num_queries = head_dim, page_size, num_queries
     d.max_blocks, d.max_sel_blocks, d.max_seq_len = max_blocks, max_sel_blocks, max_seq_len
     d.collect_rows, d.kv_chunk_tokens, d.softmax_scale = collect_rows, kv_chunk_tokens, softmax_scale
+    d.launch_stages = 0
     d.num_pages = num_pages
     d.kv_head_stride = kv_head_stride or head_dim
     d.kv_token_stride = kv_token_stride or num_kv_heads * head_dim

@@ -38,6 +38,7 @@ int check_common(const vegas_desc* d) {
   if ((d->kv_head_stride % 8) || (d->kv_token_stride % 8) || (d->kv_page_stride % 8)) return VEGAS_ERR_ALIGN;
   if (d->kv_chunk_tokens < 0 || (d->kv_chunk_tokens % kTile) != 0) return VEGAS_ERR_SHAPE;
   if (!(d->softmax_scale > 0.f)) return VEGAS_ERR_SHAPE;
+  if (d->launch_stages < 0 || d->launch_stages > (VEGAS_STAGE_STREAM | VEGAS_STAGE_MERGE)) return VEGAS_ERR_SHAPE;
   return VEGAS_OK;
 }
 
@@ -197,10 +198,15 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
 
   SplitParams sp;
   fill_split_params(desc, pl, desc->num_queries, q, k_cache, v_cache, block_table, desc->max_blocks, seq_lens, ws, &sp);
-  if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-  rc = collect ? launch_split<true, true>(pl, sp, desc->batch, st) : launch_split<true, false>(pl, sp, desc->batch, st);
-  if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
-  if (rc != VEGAS_OK) return rc;
+  const bool do_stream = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM);
+  const bool do_merge = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_MERGE);
+  if (do_stream) {
+    if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
+    rc = collect ? launch_split<true, true>(pl, sp, desc->batch, st) : launch_split<true, false>(pl, sp, desc->batch, st);
+    if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
+    if (rc != VEGAS_OK) return rc;
+  }
+  if (!do_merge) return VEGAS_OK;
   float* row_lse = reinterpret_cast<float*>(ws + pl.off_row_lse);
   rc = launch_combine(desc, pl, sp, out, collect ? row_lse : nullptr, st);
   if (rc != VEGAS_OK) return rc;
@@ -279,10 +285,13 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   SplitParams sp;
   fill_split_params(desc, pl, 1, q, k_cache, v_cache, sel_table, desc->max_sel_blocks, sel_seq_lens, ws, &sp);
-  if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-  rc = launch_split<false, false>(pl, sp, desc->batch, st);
-  if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
-  if (rc != VEGAS_OK) return rc;
+  if (desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM)) {
+    if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
+    rc = launch_split<false, false>(pl, sp, desc->batch, st);
+    if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
+    if (rc != VEGAS_OK) return rc;
+  }
+  if (desc->launch_stages != 0 && !(desc->launch_stages & VEGAS_STAGE_MERGE)) return VEGAS_OK;
   return launch_combine(desc, pl, sp, out, nullptr, st);
 }
 
