@@ -25,7 +25,10 @@
 //     and two byte-permutes per register pair build the operand.
 //   * All query rows of the GQA group (x G verification rows) are stacked in the N dimension, so
 //     every K/V byte is loaded once per workgroup and never re-read.  The queries sit in LDS
-//     (padded like K) and are shared by the workgroup's waves.
+//     (padded like K) and are shared by the workgroup's waves.  More than 32 rows per KV head are
+//     split into 32-row blocks handled by sibling workgroups whose ids differ by the number of KV
+//     heads: ids are dealt round-robin to the 8 XCDs, so siblings share an L2 and the second
+//     reader of a K/V line is served from it -- HBM still sees each byte once.
 //   * Loads run one tile ahead: K(next) is issued as soon as K(current) has been handed to LDS
 //     (same registers), V(next) after the first MFMA batch into a second register set.
 //   * At the end the NW waves merge their (max, sum, O) through LDS and the workgroup writes one
@@ -67,12 +70,13 @@ constexpr int kRowPitch = 272;   // LDS bytes per 256-byte K/Q row: the 16-byte 
 
 constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffer (128 + pad)
 
-// NB: 32-row blocks of query rows; NW: waves per workgroup; WPS: waves per SIMD the register
-// budget is sized for (2 -> at most 256 registers per lane).
-template <int NB, int NW, int WPS, bool CAUSAL, bool COLLECT>
+// NW: waves per workgroup; WPS: waves per SIMD the register budget is sized for (2 -> at most
+// 256 registers per lane).  One workgroup handles up to 32 query rows of one KV head.
+template <int NW, int WPS, bool CAUSAL, bool COLLECT>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
   // Dynamic LDS: [K staging, NW tiles | merge buffer NW x R rows][queries][row maxima][row sums]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int NB = 1;                      // one 32-row block per workgroup
   unsigned char* qlds = smem + p.lds_q_off;
   float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
   float* sm_l = sm_m + NW * NB * 32;
@@ -83,8 +87,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   const int half = lane >> 5;
   const int l32 = lane & 31;
   const int h = blockIdx.x % p.Hkv;
-  const int split = blockIdx.x / p.Hkv;
+  const int rb = (blockIdx.x / p.Hkv) % p.row_blocks;
+  const int split = blockIdx.x / (p.Hkv * p.row_blocks);
   const int b = blockIdx.y;
+  const int row0 = rb * 32;                  // first query row (of this KV head) handled here
+  const int Rl = min(32, p.R - row0);        // valid rows in this block
 
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
@@ -162,8 +169,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   for (int idx = tid; idx < NB * 32 * 16; idx += NW * 64) {
     const int row = idx >> 4, chunk = idx & 15;
     u32x4 raw = {0u, 0u, 0u, 0u};
-    if (row < p.R) {
-      const int t = row / p.g, j = row % p.g;
+    if (row < Rl) {
+      const int t = (row0 + row) / p.g, j = (row0 + row) % p.g;
       raw = *reinterpret_cast<const u32x4*>(
           p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + chunk * 8);
     }
@@ -172,8 +179,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   int limit[NB];                             // last visible token of this lane's row
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const int row = nb * 32 + l32;
-    const int t = (row < p.R) ? row / p.g : 0;
+    const int t = (l32 < Rl) ? (row0 + l32) / p.g : 0;
     limit[nb] = CAUSAL ? (n - p.G + t) : (n - 1);
   }
   __syncthreads();
@@ -254,11 +260,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       if (COLLECT) {
         const float f0 = half_sum(ps0);
         const float f1 = half_sum(ps1);
-        const int row = nb * 32 + l32;
         const int page = cur * 2 + half;
-        if (row < p.R && page < nblk) {
+        if (l32 < Rl && page < nblk) {
           const float lse = m_use + fast_log2(half ? f1 : f0);
-          p.page_lse[((static_cast<int64_t>(b) * p.lse_pages + page) * p.Hkv + h) * p.R + row] = lse;
+          p.page_lse[((static_cast<int64_t>(b) * p.lse_pages + page) * p.Hkv + h) * p.R + row0 + l32] = lse;
         }
       }
       if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
@@ -341,8 +346,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     const float sc = fast_exp2(m_run[nb] - m_use);
     const float lsum = half_sum(l_run[nb] * sc);
     if (half == 0) sm_l[wave * (NB * 32) + row] = lsum;
-    if (row < p.R) {
-      float* dst = red + (wave * p.R + row) * kRedPitch;
+    if (row < Rl) {
+      float* dst = red + (wave * Rl + row) * kRedPitch;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int d0 = 4 * (8 * (i >> 2) + 4 * half + (i & 3));
@@ -353,32 +358,35 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   }
   __syncthreads();
   const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
-  float* po = p.part_o + pbase * p.R * kHeadDim;
-  for (int e = tid; e < p.R * kHeadDim; e += NW * 64) {
+  float* po = p.part_o + (pbase * p.R + row0) * kHeadDim;
+  for (int e = tid; e < Rl * kHeadDim; e += NW * 64) {
     const int row = e >> 7, d = e & 127;
     float sum = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) sum += red[(w * p.R + row) * kRedPitch + d];
+    for (int w = 0; w < NW; ++w) sum += red[(w * Rl + row) * kRedPitch + d];
     po[e] = sum;
   }
-  if (tid < p.R) {
+  if (tid < Rl) {
     float mw = -INFINITY, lw = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
       mw = fmaxf(mw, sm_m[w * (NB * 32) + tid]);
       lw += sm_l[w * (NB * 32) + tid];
     }
-    p.part_ml[pbase * p.R + tid] = make_float2(mw, lw);
+    p.part_ml[pbase * p.R + row0 + tid] = make_float2(mw, lw);
   }
 }
 
-// Dynamic LDS bytes of attn_split_kernel<NB, NW, ...> for R valid rows.
-inline size_t split_lds_bytes(int NB, int NW, int R) {
+// Dynamic LDS bytes of attn_split_kernel<NW, ...> when a workgroup holds up to `rows` (<= 32) valid rows.
+inline size_t split_lds_tail_bytes(int NW) {
+  return static_cast<size_t>(32) * kRowPitch + 2 * static_cast<size_t>(NW) * 32 * sizeof(float);
+}
+inline size_t split_lds_bytes(int NW, int rows) {
   size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch;
-  const size_t red = static_cast<size_t>(NW) * R * kRedPitch * sizeof(float);
+  const size_t red = static_cast<size_t>(NW) * rows * kRedPitch * sizeof(float);
   if (red > stage) stage = red;
   stage = (stage + 15) / 16 * 16;
-  return stage + static_cast<size_t>(NB) * 32 * kRowPitch + 2 * static_cast<size_t>(NW) * NB * 32 * sizeof(float);
+  return stage + split_lds_tail_bytes(NW);
 }
 
 }  // namespace vegas

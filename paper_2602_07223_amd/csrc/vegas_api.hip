@@ -47,22 +47,16 @@ int check_common(const vegas_desc* d) {
 int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, SplitPlan* pl) {
   pl->R = rows_per_head;
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
-  const int64_t tiles = heads * ((max_len + kTile - 1) / kTile);       // upper bound on 32-token tiles
-  if (rows_per_head <= 32) {
-    pl->NB = 1;
-    pl->NW = (tiles >= 4 * 8 * kNumCU) ? 8 : 4;      // enough work for 8-wave groups of >= 4 tiles per wave
-    if (const char* e = getenv("VEGAS_NW")) pl->NW = (atoi(e) == 8) ? 8 : 4;
-  } else if (rows_per_head <= 64) {
-    pl->NB = 2;
-    pl->NW = 4;
-  } else {
-    return VEGAS_ERR_UNSUPPORTED;
-  }
+  if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
+  pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks, one workgroup each
+  const int64_t tiles = heads * pl->NB * ((max_len + kTile - 1) / kTile);   // upper bound on 32-token tiles
+  pl->NW = (tiles >= 4 * 8 * kNumCU) ? 8 : 4;        // enough work for 8-wave groups of >= 4 tiles per wave
+  if (const char* e = getenv("VEGAS_NW")) pl->NW = (atoi(e) == 8) ? 8 : 4;
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
-    const int64_t slots = kNumCU * ((pl->NB == 1 && pl->NW == 4) ? 2 : 1);
-    int64_t splits = slots / heads;
+    const int64_t slots = kNumCU * (pl->NW == 4 ? 2 : 1);
+    int64_t splits = slots / (heads * pl->NB);
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
@@ -110,16 +104,13 @@ int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, con
 
 template <bool CAUSAL, bool COLLECT>
 int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
-  const size_t lds = split_lds_bytes(pl.NB, pl.NW, pl.R);
-  sp.lds_q_off = static_cast<int32_t>(lds - static_cast<size_t>(pl.NB) * 32 * kRowPitch -
-                                      2 * static_cast<size_t>(pl.NW) * pl.NB * 32 * sizeof(float));
+  const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
+  const size_t lds = split_lds_bytes(pl.NW, pl.R < 32 ? pl.R : 32);
+  sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW));
+  sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
-  if (pl.NB == 1 && pl.NW == 4)
-    return launch_one(attn_split_kernel<1, 4, 2, CAUSAL, COLLECT>, grid, dim3(256), lds, st, sp);
-  if (pl.NB == 1)
-    return launch_one(attn_split_kernel<1, 8, 2, CAUSAL, COLLECT>, grid, dim3(512), lds, st, sp);
-  return launch_one(attn_split_kernel<2, 4, 1, CAUSAL, COLLECT>, grid, dim3(256), lds, st, sp);
+  if (pl.NW == 4) return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT>, grid, dim3(256), lds, st, sp);
+  return launch_one(attn_split_kernel<8, 2, CAUSAL, COLLECT>, grid, dim3(512), lds, st, sp);
 }
 
 void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const void* q, const void* k,
@@ -300,7 +291,7 @@ const char* vegas_strerror(int status) {
     case VEGAS_OK: return "ok";
     case VEGAS_ERR_NULL: return "a required pointer is NULL";
     case VEGAS_ERR_SHAPE: return "a size is non-positive or inconsistent";
-    case VEGAS_ERR_UNSUPPORTED: return "shape not supported by this build (head_dim 128, page_size 16, <= 64 rows per KV head)";
+    case VEGAS_ERR_UNSUPPORTED: return "shape not supported by this build (head_dim 128, page_size 16, <= 128 rows per KV head)";
     case VEGAS_ERR_ALIGN: return "pointer or stride alignment";
     case VEGAS_ERR_WORKSPACE: return "workspace missing or too small";
     case VEGAS_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";

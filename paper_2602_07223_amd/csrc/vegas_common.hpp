@@ -54,6 +54,7 @@ struct SplitParams {
   int32_t G, g, R, Hq, Hkv;
   int32_t chunk_tokens, nsplit, lse_pages, max_tokens;
   int32_t lds_q_off;        // byte offset of the query tile inside dynamic LDS
+  int32_t row_blocks;       // ceil(R / 32): 32-row blocks of one KV head, one workgroup each
   int64_t page_stride, token_stride, head_stride, num_pages;
   float scale_log2e;
 };

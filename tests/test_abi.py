@@ -61,7 +61,7 @@ A = 4096  # a 16-byte aligned fake device address: never dereferenced because va
     (dict(page_size=32), vb.VEGAS_ERR_UNSUPPORTED),
     (dict(max_seq_len=32769), vb.VEGAS_ERR_SHAPE),
     (dict(num_queries=0), vb.VEGAS_ERR_SHAPE),
-    (dict(num_queries=17), vb.VEGAS_ERR_UNSUPPORTED),          # 68 rows per KV head
+    (dict(num_queries=33), vb.VEGAS_ERR_UNSUPPORTED),          # 132 rows per KV head
     (dict(collect_rows=3), vb.VEGAS_ERR_SHAPE),
     (dict(kv_chunk_tokens=100), vb.VEGAS_ERR_SHAPE),
     (dict(kv_token_stride=1028), vb.VEGAS_ERR_ALIGN),

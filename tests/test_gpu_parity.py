@@ -68,6 +68,7 @@ SMALL = [
     ("single_query", 1, 32, 8, 1, [777], {}),
     ("gamma11_g4", 1, 32, 8, 12, [2000], {}),
     ("mha_like", 1, 8, 8, 3, [900], {}),
+    ("rows96", 2, 64, 8, 12, [1100, 300], {}),
 ]
 
 
