@@ -66,36 +66,43 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
 
 // Page criticality (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the last
 // paragraph of Sec. 3.3): score[b][j] = inv_norm * sum_h sum_{rows in R} 2^(page_lse - row_lse).
-// One wave per page: the Hkv*R values of a page are contiguous, lanes stride over them and a
-// wave reduction adds them up.  Pages at or beyond the sequence's page count are written as 0.
+// A workgroup of 256 threads covers 64 pages: lane = page, the 4 waves split the KV heads; a thread
+// walks the R values of its (head, page) -- neighbouring lanes read neighbouring R-float pieces, so
+// every fetched line is used in full -- and the waves' sums meet in LDS.  Pages at or beyond the
+// sequence's page count are written as 0.
 __global__ __launch_bounds__(256) void block_score_kernel(const ScoreParams p) {
-  extern __shared__ float sm_row[];           // [Hkv * R] global row lse; -inf for rows not collected
+  extern __shared__ float sm_row[];           // [Hkv * R] global row lse (-inf: row not collected), then [4][64] sums
   const int b = blockIdx.y;
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   const int nblk = (n + kPage - 1) / kPage;
   const int HR = p.Hkv * p.R;
+  float* sm_sum = sm_row + HR;
   for (int i = threadIdx.x; i < HR; i += blockDim.x) {
     const int t = (i % p.R) / p.g;
     const bool use = (p.collect_rows == 1) || (t == 0) || (t == p.G - 1);
     sm_row[i] = use ? p.row_lse[static_cast<int64_t>(b) * HR + i] : -INFINITY;
   }
   __syncthreads();
-  const int lane = threadIdx.x & 63;
-  const int j = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (j >= p.max_blocks) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
   float s = 0.f;
   if (j < nblk) {
-    const float* pl = p.page_lse + (static_cast<int64_t>(b) * p.lse_pages + j) * HR;
-    for (int i = lane; i < HR; i += 64) {
-      const float rl = sm_row[i];
-      if (rl != -INFINITY) s += fast_exp2(pl[i] - rl);
+    for (int h = wave; h < p.Hkv; h += 4) {
+      const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
+      const float* rl = sm_row + h * p.R;
+      for (int r = 0; r < p.R; ++r) {
+        const float x = rl[r];
+        if (x != -INFINITY) s += fast_exp2(pl[r] - x);
+      }
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-    s *= p.inv_norm;
   }
-  if (lane == 0) p.block_scores[static_cast<int64_t>(b) * p.max_blocks + j] = s;
+  sm_sum[wave * 64 + lane] = s;
+  __syncthreads();
+  if (wave == 0 && j < p.max_blocks) {
+    const float tot = (sm_sum[lane] + sm_sum[64 + lane]) + (sm_sum[128 + lane] + sm_sum[192 + lane]);
+    p.block_scores[static_cast<int64_t>(b) * p.max_blocks + j] = (j < nblk) ? tot * p.inv_norm : 0.f;
+  }
 }
 
 }  // namespace vegas

@@ -29,8 +29,9 @@
 //     split into 32-row blocks handled by sibling workgroups whose ids differ by the number of KV
 //     heads: ids are dealt round-robin to the 8 XCDs, so siblings share an L2 and the second
 //     reader of a K/V line is served from it -- HBM still sees each byte once.
-//   * Loads run one tile ahead: K(next) is issued as soon as K(current) has been handed to LDS
-//     (same registers), V(next) after the first MFMA batch into a second register set.
+//   * Loads run one tile ahead: as soon as K(current) has been handed to LDS, K(next) goes into
+//     the same registers and V(next) into a second register set, so a wave keeps a full tile
+//     (16 KB) in flight for the whole duration of the math.
 //   * At the end the NW waves merge their (max, sum, O) through LDS and the workgroup writes one
 //     partial result.
 #pragma once
@@ -74,12 +75,15 @@ constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffe
 // 256 registers per lane).  One workgroup handles up to 32 query rows of one KV head.
 template <int NW, int WPS, bool CAUSAL, bool COLLECT>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
-  // Dynamic LDS: [K staging, NW tiles | merge buffer NW x R rows][queries][row maxima][row sums]
+  // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NB = 1;                      // one 32-row block per workgroup
   unsigned char* qlds = smem + p.lds_q_off;
   float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
   float* sm_l = sm_m + NW * NB * 32;
+  // [pages of the chunk][Rl] page log-sum-exp (COLLECT only): behind the K tiles; the merge buffer may
+  // overlap it because it is flushed (and a barrier passed) before the merge starts.
+  float* lse_lds = reinterpret_cast<float*>(smem + NW * 32 * kRowPitch);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -210,7 +214,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     for (int i = 0; i < 8; ++i) {
       *reinterpret_cast<u32x4*>(kst + (4 * i + k_tok) * kRowPitch + k_chunk * 16) = kr[i];
     }
-    if (has_next) issue_k(k + 1, kr);
+    if (has_next) {
+      issue_k(k + 1, kr);
+      issue_v(k + 1, vnxt);
+    }
     wave_lds_fence();
     f32x16 st[NB];
 #pragma unroll
@@ -229,7 +236,6 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       }
     }
     wave_lds_fence();
-    if (has_next) issue_v(k + 1, vnxt);
 
     const bool tail = (tok0 + kTile > n) || (CAUSAL && (tok0 + kTile - 1 > n - p.G));
     bf16x8 pb[NB][2];
@@ -260,11 +266,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       if (COLLECT) {
         const float f0 = half_sum(ps0);
         const float f1 = half_sum(ps1);
-        const int page = cur * 2 + half;
-        if (l32 < Rl && page < nblk) {
-          const float lse = m_use + fast_log2(half ? f1 : f0);
-          p.page_lse[((static_cast<int64_t>(b) * p.lse_pages + page) * p.Hkv + h) * p.R + row0 + l32] = lse;
-        }
+        const int page = cur * 2 + half;                 // parked in LDS, written out in bulk at the end
+        if (l32 < Rl && page < nblk) lse_lds[(page - c0 / kPage) * Rl + l32] = m_use + fast_log2(half ? f1 : f0);
       }
       if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
@@ -335,6 +338,19 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     for (int nb = 0; nb < NB; ++nb) sm_m[wave * (NB * 32) + nb * 32 + l32] = m_run[nb];
   }
   __syncthreads();                                       // also: every wave is done with its K tile
+  if (COLLECT) {
+    // One contiguous, coalesced write of the chunk's page log-sum-exps (a store per tile inside the
+    // streaming loop costs ~14 % of the kernel: small scattered writes disturb the read stream).
+    const int pg0 = c0 / kPage;
+    const int npg = min(nblk, (c1 + kPage - 1) / kPage) - pg0;
+    float* dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + pg0) * p.R + row0;
+    if (Rl == p.R) {
+      for (int e = tid; e < npg * Rl; e += NW * 64) dst[e] = lse_lds[e];
+    } else {
+      for (int e = tid; e < npg * Rl; e += NW * 64) dst[(e / Rl) * p.R + (e % Rl)] = lse_lds[e];
+    }
+    __syncthreads();
+  }
   float* red = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -381,8 +397,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 inline size_t split_lds_tail_bytes(int NW) {
   return static_cast<size_t>(32) * kRowPitch + 2 * static_cast<size_t>(NW) * 32 * sizeof(float);
 }
-inline size_t split_lds_bytes(int NW, int rows) {
-  size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch;
+// lse_tokens > 0: page scores are collected and the chunk's page log-sum-exps (chunk_pages x rows floats)
+// sit right behind the K tiles.
+inline size_t split_lds_bytes(int NW, int rows, int lse_tokens = 0) {
+  size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch +
+                 static_cast<size_t>(lse_tokens / kPage) * rows * sizeof(float);
   const size_t red = static_cast<size_t>(NW) * rows * kRedPitch * sizeof(float);
   if (red > stage) stage = red;
   stage = (stage + 15) / 16 * 16;

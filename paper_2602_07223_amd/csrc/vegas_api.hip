@@ -105,7 +105,8 @@ int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, con
 template <bool CAUSAL, bool COLLECT>
 int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st) {
   const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
-  const size_t lds = split_lds_bytes(pl.NW, pl.R < 32 ? pl.R : 32);
+  const int rows = pl.R < 32 ? pl.R : 32;
+  const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT ? pl.chunk : 0);
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW));
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
@@ -213,8 +214,8 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
     const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
                                                                      : (desc->num_queries > 1 ? 2 : 1);
     sc.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
-    const size_t shm = static_cast<size_t>(sp.Hkv) * pl.R * sizeof(float);
-    hipLaunchKernelGGL(block_score_kernel, dim3((desc->max_blocks + 3) / 4, desc->batch), dim3(256), shm, st, sc);
+    const size_t shm = (static_cast<size_t>(sp.Hkv) * pl.R + 256) * sizeof(float);
+    hipLaunchKernelGGL(block_score_kernel, dim3((desc->max_blocks + 63) / 64, desc->batch), dim3(256), shm, st, sc);
     if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
   }
   return VEGAS_OK;

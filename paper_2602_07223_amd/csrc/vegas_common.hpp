@@ -49,7 +49,7 @@ struct SplitParams {
   const int32_t* lens;      // [B] valid tokens
   float* part_o;            // [B, Hkv, nsplit, R, D] un-normalised partial outputs
   float2* part_ml;          // [B, Hkv, nsplit, R]    (running max in log2 units, partial sum)
-  float* page_lse;          // [B, lse_pages, Hkv, R] log2-sum-exp2 of each page's scaled logits
+  float* page_lse;          // [B, Hkv, lse_pages, R] log2-sum-exp2 of each page's scaled logits
   int32_t table_stride;
   int32_t G, g, R, Hq, Hkv;
   int32_t chunk_tokens, nsplit, lse_pages, max_tokens;
