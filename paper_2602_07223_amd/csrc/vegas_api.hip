@@ -199,25 +199,26 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
     if (rc != VEGAS_OK) return rc;
   }
   if (!do_merge) return VEGAS_OK;
-  float* row_lse = reinterpret_cast<float*>(ws + pl.off_row_lse);
-  rc = launch_combine(desc, pl, sp, out, collect ? row_lse : nullptr, st);
-  if (rc != VEGAS_OK) return rc;
-  if (collect) {
-    ScoreParams sc;
-    sc.page_lse = sp.page_lse;
-    sc.row_lse = row_lse;
-    sc.lens = seq_lens;
-    sc.block_scores = block_scores;
-    sc.G = desc->num_queries; sc.g = sp.g; sc.R = pl.R; sc.Hkv = sp.Hkv;
-    sc.max_blocks = desc->max_blocks; sc.lse_pages = pl.lse_pages; sc.max_tokens = desc->max_seq_len;
-    sc.collect_rows = desc->collect_rows;
-    const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
-                                                                     : (desc->num_queries > 1 ? 2 : 1);
-    sc.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
-    const size_t shm = (static_cast<size_t>(sp.Hkv) * pl.R + 256) * sizeof(float);
-    hipLaunchKernelGGL(block_score_kernel, dim3((desc->max_blocks + 63) / 64, desc->batch), dim3(256), shm, st, sc);
-    if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
-  }
+  if (!collect) return launch_combine(desc, pl, sp, out, nullptr, st);
+  FinalizeParams fp;
+  fp.part_o = sp.part_o;
+  fp.part_ml = sp.part_ml;
+  fp.page_lse = sp.page_lse;
+  fp.lens = seq_lens;
+  fp.out = static_cast<uint16_t*>(out);
+  fp.block_scores = block_scores;
+  fp.G = desc->num_queries; fp.g = sp.g; fp.R = pl.R; fp.Hq = sp.Hq; fp.Hkv = sp.Hkv;
+  fp.chunk_tokens = pl.chunk; fp.nsplit = pl.nsplit; fp.max_tokens = desc->max_seq_len;
+  fp.max_blocks = desc->max_blocks; fp.lse_pages = pl.lse_pages; fp.collect_rows = desc->collect_rows;
+  fp.nA = (sp.Hkv * pl.R + 1) / 2;
+  const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
+                                                                   : (desc->num_queries > 1 ? 2 : 1);
+  fp.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
+  const int nB = (desc->max_blocks + 31) / 32;
+  const size_t hr = static_cast<size_t>(sp.Hkv) * pl.R;
+  const size_t shm = (hr + 256 > 264 ? hr + 256 : 264) * sizeof(float);
+  hipLaunchKernelGGL(verify_finalize_kernel, dim3(fp.nA + nB, desc->batch), dim3(256), shm, st, fp);
+  if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
   return VEGAS_OK;
 }
 

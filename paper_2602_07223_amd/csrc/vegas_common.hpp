@@ -68,12 +68,16 @@ struct CombineParams {
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
 };
 
-struct ScoreParams {
+struct FinalizeParams {
+  const float* part_o;
+  const float2* part_ml;
   const float* page_lse;
-  const float* row_lse;
   const int32_t* lens;
+  uint16_t* out;            // bf16 [B, G, Hq, D]
   float* block_scores;      // [B, max_blocks]
-  int32_t G, g, R, Hkv, max_blocks, lse_pages, max_tokens, collect_rows;
+  int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
+  int32_t max_blocks, lse_pages, collect_rows;
+  int32_t nA;               // workgroups that merge rows (two rows each); the rest score pages
   float inv_norm;
 };
 
