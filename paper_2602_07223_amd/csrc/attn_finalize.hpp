@@ -72,7 +72,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
 // A score workgroup derives the global row log-sum-exps itself from the chunks' (max, sum) pairs,
 // so it does not depend on the merge workgroups.  Pages at or beyond the sequence's page count get 0.
 __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizeParams p) {
-  extern __shared__ float smf[];              // role A: [2][128] weights + [2][4]; role B: [Hkv*R] + [8][32]
+  extern __shared__ float smf[];              // role A: [2][128] weights + [2][4]; role B: [Hkv*R] + [8][32] + [Hkv*R][8] pairs
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
   int n = p.lens[b];
@@ -144,18 +144,55 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   }
   float* sm_row = smf;                        // [HR] global row lse; -inf for rows that do not count
   float* sm_sum = smf + HR;                   // [8][32]
+  float2* sm_pair = reinterpret_cast<float2*>(smf + HR + 256);   // [HR][8] (max, sum) of a row over 1/8 of the chunks
+  // Each (row, eighth of the chunks) pair is one unit of work.  A thread first issues the (max, sum)
+  // loads of four units (up to 16 independent loads), then merges them, so the whole table costs
+  // about one memory round trip instead of one per chunk.
+  for (int s0 = 0; s0 < ns; s0 += 32) {
+    for (int u0 = tid; u0 < HR * 8; u0 += 4 * 256) {
+      float2 v[4][4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int u = u0 + 256 * a;
+        const bool uv = u < HR * 8;
+        const int i = uv ? (u >> 3) : 0, sg = u & 7;
+        const int h = i / p.R, r = i % p.R;
+        const float2* ml = p.part_ml + (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit * p.R + r;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int sidx = s0 + sg + 8 * q;
+          v[a][q] = (uv && sidx < ns) ? ml[static_cast<int64_t>(sidx) * p.R] : make_float2(-INFINITY, 0.f);
+        }
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int u = u0 + 256 * a;
+        if (u < HR * 8) {
+          float2 cur = (s0 == 0) ? make_float2(-INFINITY, 0.f) : sm_pair[u];
+          float m = cur.x;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) m = fmaxf(m, v[a][q].x);
+          const float mu = (m == -INFINITY) ? 0.f : m;
+          float L = cur.y * fast_exp2(cur.x - mu);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) L += v[a][q].y * fast_exp2(v[a][q].x - mu);
+          sm_pair[u] = make_float2(m, L);
+        }
+      }
+    }
+  }
+  __syncthreads();
   for (int i = tid; i < HR; i += 256) {
-    const int h = i / p.R, r = i % p.R, t = r / p.g;
+    const int t = (i % p.R) / p.g;
     const bool use = (p.collect_rows == 1) || (t == 0) || (t == p.G - 1);
-    const float2* ml = p.part_ml + (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit * p.R + r;
     float m = -INFINITY;
-#pragma unroll 4
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) m = fmaxf(m, sm_pair[i * 8 + q].x);
     const float m_use = (m == -INFINITY) ? 0.f : m;
     float L = 0.f;
-#pragma unroll 4
-    for (int s = 0; s < ns; ++s) {
-      const float2 v = ml[static_cast<int64_t>(s) * p.R];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float2 v = sm_pair[i * 8 + q];
       L += fast_exp2(v.x - m_use) * v.y;
     }
     sm_row[i] = (use && L > 0.f) ? m_use + fast_log2(L) : -INFINITY;

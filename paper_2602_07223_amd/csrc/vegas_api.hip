@@ -216,7 +216,15 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   fp.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
   const int nB = (desc->max_blocks + 31) / 32;
   const size_t hr = static_cast<size_t>(sp.Hkv) * pl.R;
-  const size_t shm = (hr + 256 > 264 ? hr + 256 : 264) * sizeof(float);
+  const size_t shm = (hr + 256 + 16 * hr) * sizeof(float);   // role B needs the most; role A fits inside
+  if (shm > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
+  static bool big_lds = false;
+  if (shm > 64 * 1024 && !big_lds) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(verify_finalize_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VEGAS_ERR_LAUNCH;
+    big_lds = true;
+  }
   hipLaunchKernelGGL(verify_finalize_kernel, dim3(fp.nA + nB, desc->batch), dim3(256), shm, st, fp);
   if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
   return VEGAS_OK;
