@@ -12,6 +12,7 @@
 namespace vegas {
 
 constexpr int kSelectThreads = 1024;
+constexpr int kSelectKeyCap = 16384;   // keys kept in LDS (64 KB); longer prefixes re-read the scores
 
 // Order-preserving key of a score (larger float <=> larger unsigned); -0 is folded onto +0.
 __device__ __forceinline__ uint32_t score_key(float s) {
@@ -20,7 +21,8 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 }
 
 __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const SelectParams p) {
-  __shared__ uint32_t hist[256];
+  extern __shared__ uint32_t skeys[];                 // [min(prefix pages, key_cap)]
+  __shared__ uint32_t hist[4][256];
   __shared__ uint32_t sh_prefix, sh_need;
   __shared__ uint32_t wave_take[kSelectThreads / 64], wave_eq[kSelectThreads / 64];
 
@@ -48,28 +50,54 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
   k = min(k, p.max_sel_blocks);                      // device-side clamp; the host rejects this case
   nF = min(nF, k);
   const int kc = k - nF;                             // pages to take from the prefix [0, f0)
+  const bool need_search = kc > 0 && kc < f0;
+  const bool take_all = kc >= f0;
+
+  // ---- keys of the prefix scores go to LDS once; the four digit histograms start at zero
+  const bool in_lds = f0 <= p.key_cap;
+  hist[tid >> 8][tid & 255] = 0u;
+  if (need_search && in_lds)
+    for (int j = tid; j < f0; j += kSelectThreads) skeys[j] = score_key(scores[j]);
+  __syncthreads();
+  auto key_at = [&](int j) -> uint32_t { return in_lds ? skeys[j] : score_key(scores[j]); };
 
   // ---- radix select: key of the kc-th largest prefix score, and how many of its ties to take
   uint32_t T = 0u, need_eq = 0u;
-  bool take_all = false;
-  if (kc >= f0) {
-    take_all = true;
-  } else if (kc > 0) {
+  if (need_search) {
     uint32_t prefix = 0u, mask = 0u, need = static_cast<uint32_t>(kc);
 #pragma unroll 1
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      if (tid < 256) hist[tid] = 0u;
-      __syncthreads();
-      for (int j = tid; j < f0; j += kSelectThreads) {
-        const uint32_t key = score_key(scores[j]);
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      uint32_t* h = hist[pass];
+      for (int base = 0; base < f0; base += kSelectThreads) {
+        const int j = base + tid;
+        uint32_t key = 0u;
+        bool act = false;
+        if (j < f0) {
+          key = key_at(j);
+          act = (key & mask) == prefix;
+        }
+        const uint32_t d = (key >> shift) & 255u;
+        // Scores cluster (the top byte of most keys is identical): lanes with the leader's digit
+        // are counted by one atomic; what is left after two rounds adds itself.
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+          const uint64_t am = __builtin_amdgcn_ballot_w64(act);
+          if (am == 0ull) break;
+          const int leader = __builtin_ctzll(am);
+          const uint32_t dl = __builtin_amdgcn_readlane(d, leader);
+          const uint64_t same = __builtin_amdgcn_ballot_w64(act && d == dl);
+          if (lane == leader) atomicAdd(&h[dl], static_cast<uint32_t>(__popcll(same)));
+          if (d == dl) act = false;
+        }
+        if (act) atomicAdd(&h[d], 1u);
       }
       __syncthreads();
       if (wave == 0) {
         // lane l owns bins 4l .. 4l+3; count from the top bin downwards
         uint32_t c[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = hist[4 * lane + i];
+        for (int i = 0; i < 4; ++i) c[i] = h[4 * lane + i];
         const uint32_t mine = c[0] + c[1] + c[2] + c[3];
         uint32_t incl = mine;                          // sum over lanes >= lane
 #pragma unroll
@@ -104,7 +132,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       const int j = start + tid;
       uint32_t key = 0u;
       const bool in = j < f0;
-      if (in) key = score_key(scores[j]);
+      if (in && !take_all) key = key_at(j);
       const bool eq = in && !take_all && key == T;
       const bool gt = in && (take_all || key > T);
       const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);

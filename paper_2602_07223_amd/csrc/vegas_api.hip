@@ -261,7 +261,17 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const
   sp.max_blocks = desc->max_blocks;
   sp.max_sel_blocks = desc->max_sel_blocks;
   sp.max_tokens = desc->max_seq_len;
-  hipLaunchKernelGGL(select_blocks_kernel, dim3(desc->batch), dim3(kSelectThreads), 0,
+  const int64_t max_pages = (static_cast<int64_t>(desc->max_seq_len) + kPage - 1) / kPage;
+  sp.key_cap = static_cast<int32_t>(max_pages < kSelectKeyCap ? max_pages : kSelectKeyCap);
+  static bool big_lds = false;
+  const size_t shm = static_cast<size_t>(sp.key_cap) * sizeof(uint32_t);
+  if (shm > 48 * 1024 && !big_lds) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(select_blocks_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess)
+      return VEGAS_ERR_LAUNCH;
+    big_lds = true;
+  }
+  hipLaunchKernelGGL(select_blocks_kernel, dim3(desc->batch), dim3(kSelectThreads), shm,
                      static_cast<hipStream_t>(hip_stream), sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }

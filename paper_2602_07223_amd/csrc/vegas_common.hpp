@@ -89,6 +89,7 @@ struct SelectParams {
   int32_t* sel_table;
   int32_t* sel_seq_lens;
   int32_t budget_tokens, G, max_blocks, max_sel_blocks, max_tokens;
+  int32_t key_cap;          // score keys that fit the kernel's dynamic LDS
 };
 
 }  // namespace vegas
