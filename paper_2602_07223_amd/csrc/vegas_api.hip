@@ -110,8 +110,13 @@ int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st)
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW));
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
-  if (pl.NW == 4) return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT>, grid, dim3(256), lds, st, sp);
-  return launch_one(attn_split_kernel<8, 2, CAUSAL, COLLECT>, grid, dim3(512), lds, st, sp);
+  constexpr bool kVerify = CAUSAL;                  // the verification pass is the only causal caller
+  if (kVerify && pl.NB == 1) {                      // one reader per K/V line, read once: stream it
+    if (pl.NW == 4) return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(256), lds, st, sp);
+    return launch_one(attn_split_kernel<8, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(512), lds, st, sp);
+  }
+  if (pl.NW == 4) return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, false>, grid, dim3(256), lds, st, sp);
+  return launch_one(attn_split_kernel<8, 2, CAUSAL, COLLECT, false>, grid, dim3(512), lds, st, sp);
 }
 
 void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const void* q, const void* k,
