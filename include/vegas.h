@@ -95,7 +95,7 @@ size_t vegas_workspace_bytes(const vegas_desc* desc);
  *   k_cache/v_cache bf16 NHD caches; the G tokens' own K/V are already the last G entries of each
  *                sequence, and seq_lens counts them
  *   block_table  int32 [B, max_blocks]     physical page of each logical page; entries at or
- *                                          beyond ceil(seq_lens[b]/16) are never read
+ *                                          beyond ceil(seq_lens[b]/16) may be read but are never used
  *   seq_lens     int32 [B]
  *   out          bf16 [B, G, H_q, D]       row t attends to keys 0 .. seq_lens[b]-G+t (causal);
  *                                          a row with no visible key gets 0

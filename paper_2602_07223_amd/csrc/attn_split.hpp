@@ -104,13 +104,29 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   const int row0 = rb * 32;                  // first query row (of this KV head) handled here
   const int Rl = min(32, p.R - row0);        // valid rows in this block
 
+  // Physical page ids of the wave's next 32 tiles live in one register: lane (k, half) holds the id of
+  // page `half` of tile tile_first + k*NW.  They are read back with readlane, so the streaming loop
+  // never waits on a page-table load.  The first batch is requested before the sequence length is
+  // known (one memory round trip less at the head of the kernel): indices are clamped to the table
+  // row, entries past the sequence's pages are read but never used.
+  const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
+  const int c0 = split * p.chunk_tokens;
+  const int tile_first = c0 / kTile + wave;
+  int pagevec = 0;
+  auto load_pagevec = [&](int kbase) {
+    int page = 2 * (tile_first + (kbase + l32) * NW) + half;
+    page = page < p.table_stride ? page : p.table_stride - 1;
+    int64_t ph = table[page];
+    ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
+    pagevec = static_cast<int>(ph);
+  };
+  load_pagevec(0);
+
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-  const int c0 = split * p.chunk_tokens;
   if (c0 >= n) return;                       // whole workgroup: nothing to do, no partial is read
   const int c1 = min(c0 + p.chunk_tokens, n);
   const int nblk = (n + kPage - 1) / kPage;
-  const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
 
   // ---- per-lane constants
   const int64_t head_off = static_cast<int64_t>(h) * p.head_stride;
@@ -123,25 +139,12 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   const uint32_t k_lane_off = static_cast<uint32_t>(k_tok) * ts_bytes + static_cast<uint32_t>(k_chunk) * 16u;
   const uint32_t v_lane_off = static_cast<uint32_t>(4 * half) * ts_bytes + static_cast<uint32_t>(l32) * 8u;
   const int tile_end = (c1 + kTile - 1) / kTile;
-  const int tile_first = c0 / kTile + wave;
-
-  // Physical page ids of the wave's next 32 tiles live in one register: lane (k, half) holds the id of
-  // page `half` of tile tile_first + k*NW.  They are read back with readlane, so the streaming loop
-  // never waits on a page-table load.
-  int pagevec = 0;
-  auto load_pagevec = [&](int kbase) {
-    int page = 2 * (tile_first + (kbase + l32) * NW) + half;
-    page = page < nblk ? page : nblk - 1;
-    int64_t ph = table[page];
-    ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
-    pagevec = static_cast<int>(ph);
-  };
   auto page_base = [&](const uint16_t* cache, int ph) -> const unsigned char* {
     return uniform_ptr(reinterpret_cast<const unsigned char*>(cache + static_cast<int64_t>(ph) * p.page_stride + head_off));
   };
   // tile index k counts this wave's tiles: tile = tile_first + k*NW
   auto issue_k = [&](int k, u32x4 (&kr)[8]) {
-    if ((k & 31) == 0) load_pagevec(k);
+    if ((k & 31) == 0 && k > 0) load_pagevec(k);
     const int ph0 = __builtin_amdgcn_readlane(pagevec, k & 31);
     const int ph1 = __builtin_amdgcn_readlane(pagevec, 32 + (k & 31));
     const unsigned char* kb0 = page_base(p.k, ph0);
