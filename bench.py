@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the verification streaming kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9987 and 1.0).
-VERIFY_TRAFFIC_BYTES = 138_763_264   # (131375 KiB fetched + 4136 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
+# runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9990 and 1.0).
+VERIFY_TRAFFIC_BYTES = 138_504_192   # (131378 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
 WORKLOAD = "ctx32k"
 
 
