@@ -88,23 +88,50 @@ class VegasPath:
     def stream(self) -> int:
         return int(torch.cuda.current_stream(self.device).cuda_stream)
 
-    def verify(self, dl: DeviceLayer) -> None:
-        vb.vegas_verify_attention(self.desc_verify, dl.q_verify, dl.k_cache, dl.v_cache, dl.block_table,
-                                  dl.seq_lens, self.out_verify, self.block_scores, self.workspace,
-                                  stream=self.stream())
+    # The calls below pass raw device addresses (cached per DeviceLayer) so that the host cost of one
+    # call stays at a few microseconds: at batch 1 the kernels are that short.
+    def _addrs(self, dl: DeviceLayer):
+        a = getattr(dl, "_addrs", None)
+        if a is None:
+            step_bytes = dl.q_draft[0].numel() * dl.q_draft.element_size()
+            a = dict(qv=dl.q_verify.data_ptr(), k=dl.k_cache.data_ptr(), v=dl.v_cache.data_ptr(),
+                     bt=dl.block_table.data_ptr(), sl=dl.seq_lens.data_ptr(),
+                     qd=[dl.q_draft.data_ptr() + i * step_bytes for i in range(dl.q_draft.shape[0])])
+            dl._addrs = a
+        return a
 
-    def select(self, dl: DeviceLayer, block_scores: Optional[torch.Tensor] = None, budgets=None) -> None:
-        vb.vegas_select_blocks(self.desc_verify, self.block_scores if block_scores is None else block_scores,
-                               dl.block_table, dl.seq_lens, self.budget_tokens, self.sel_table,
-                               self.sel_seq_lens, budgets=budgets, stream=self.stream())
+    def _own(self):
+        o = getattr(self, "_own_addrs", None)
+        if o is None:
+            step_bytes = self.out_draft[0].numel() * self.out_draft.element_size()
+            o = dict(ws=self.workspace.data_ptr(), wsn=self.workspace.numel(), ov=self.out_verify.data_ptr(),
+                     bs=self.block_scores.data_ptr(), st=self.sel_table.data_ptr(), ssl=self.sel_seq_lens.data_ptr(),
+                     od=[self.out_draft.data_ptr() + i * step_bytes for i in range(self.out_draft.shape[0])])
+            self._own_addrs = o
+        return o
 
-    def draft(self, dl: DeviceLayer, step: int) -> None:
-        vb.vegas_draft_attention(self.desc_draft, dl.q_draft[step], dl.k_cache, dl.v_cache, self.sel_table,
-                                 self.sel_seq_lens, self.out_draft[step], self.workspace, stream=self.stream())
+    def verify(self, dl: DeviceLayer, stream=None) -> None:
+        a, o = self._addrs(dl), self._own()
+        vb.vegas_verify_attention(self.desc_verify, a["qv"], a["k"], a["v"], a["bt"], a["sl"], o["ov"], o["bs"],
+                                  o["ws"], stream=self.stream() if stream is None else stream,
+                                  workspace_bytes=o["wsn"])
+
+    def select(self, dl: DeviceLayer, block_scores: Optional[torch.Tensor] = None, budgets=None, stream=None) -> None:
+        a, o = self._addrs(dl), self._own()
+        vb.vegas_select_blocks(self.desc_verify, o["bs"] if block_scores is None else block_scores,
+                               a["bt"], a["sl"], self.budget_tokens, o["st"], o["ssl"], budgets=budgets,
+                               stream=self.stream() if stream is None else stream)
+
+    def draft(self, dl: DeviceLayer, step: int, stream=None) -> None:
+        a, o = self._addrs(dl), self._own()
+        vb.vegas_draft_attention(self.desc_draft, a["qd"][step], a["k"], a["v"], o["st"], o["ssl"], o["od"][step],
+                                 o["ws"], stream=self.stream() if stream is None else stream,
+                                 workspace_bytes=o["wsn"])
 
     def iteration(self, dl: DeviceLayer) -> None:
         """One decoding iteration's attention work for one layer: verify, select, G draft steps."""
-        self.verify(dl)
-        self.select(dl)
+        st = self.stream()
+        self.verify(dl, st)
+        self.select(dl, stream=st)
         for s in range(self.G):
-            self.draft(dl, s)
+            self.draft(dl, s, st)
