@@ -6,7 +6,7 @@ namespace vegas {
 
 // One workgroup of 128 threads (= head dims) per (query row, KV head, sequence): merges the
 // chunk partials of that row with the usual max/sum bookkeeping (all in log2 units), writes the
-// bf16 output row (Eq. 1) and the row's global log2-sum-exp2.  The per-chunk (max, sum) pairs are
+// bf16 output row (Eq. 1).  The per-chunk (max, sum) pairs are
 // fetched by one thread each, so the whole merge costs two dependent memory round trips.
 __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p) {
   __shared__ float sw[128];
@@ -60,8 +60,6 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
   const float o = (L > 0.f) ? accv / L : 0.f;
   const int t = r / p.g, j = r % p.g;
   p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
-  if (p.row_lse != nullptr && tid == 0)
-    p.row_lse[(static_cast<int64_t>(b) * p.Hkv + h) * p.R + r] = (L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
 }
 
 // Verification epilogue in ONE launch (a kernel boundary costs ~3 us on this GPU): workgroups

@@ -3,7 +3,6 @@
 #include "../../include/vegas.h"
 
 #include <hip/hip_runtime.h>
-#include <stdlib.h>
 
 #include "attn_finalize.hpp"
 #include "attn_split.hpp"
@@ -22,7 +21,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct SplitPlan {
   int R = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;
-  size_t off_part_o = 0, off_part_ml = 0, off_row_lse = 0, off_page_lse = 0, total = 0;
+  size_t off_part_o = 0, off_part_ml = 0, off_page_lse = 0, total = 0;
 };
 
 int check_common(const vegas_desc* d) {
@@ -51,7 +50,6 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_ls
   pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks, one workgroup each
   const int64_t tiles = heads * pl->NB * ((max_len + kTile - 1) / kTile);   // upper bound on 32-token tiles
   pl->NW = (tiles >= 4 * 8 * kNumCU) ? 8 : 4;        // enough work for 8-wave groups of >= 4 tiles per wave
-  if (const char* e = getenv("VEGAS_NW")) pl->NW = (atoi(e) == 8) ? 8 : 4;
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
@@ -70,7 +68,6 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_ls
   const size_t hs = static_cast<size_t>(heads);
   pl->off_part_o = off;  off += align_up(hs * pl->nsplit * pl->R * kHeadDim * sizeof(float));
   pl->off_part_ml = off; off += align_up(hs * pl->nsplit * pl->R * sizeof(float2));
-  pl->off_row_lse = off; off += align_up(hs * pl->R * sizeof(float));
   pl->off_page_lse = off; off += align_up(hs * static_cast<size_t>(pl->lse_pages) * pl->R * sizeof(float));
   pl->total = off;
   return VEGAS_OK;
@@ -147,14 +144,12 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->scale_log2e = d->softmax_scale * 1.4426950408889634f;
 }
 
-int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& sp, void* out, float* row_lse,
-                   hipStream_t st) {
+int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& sp, void* out, hipStream_t st) {
   CombineParams cp;
   cp.part_o = sp.part_o;
   cp.part_ml = sp.part_ml;
   cp.lens = sp.lens;
   cp.out = static_cast<uint16_t*>(out);
-  cp.row_lse = row_lse;
   cp.G = sp.G; cp.g = sp.g; cp.R = sp.R; cp.Hq = sp.Hq; cp.Hkv = sp.Hkv;
   cp.chunk_tokens = pl.chunk; cp.nsplit = pl.nsplit; cp.max_tokens = d->max_seq_len;
   hipLaunchKernelGGL(attn_combine_kernel, dim3(pl.R, sp.Hkv, d->batch), dim3(128), 0, st, cp);
@@ -204,7 +199,7 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
     if (rc != VEGAS_OK) return rc;
   }
   if (!do_merge) return VEGAS_OK;
-  if (!collect) return launch_combine(desc, pl, sp, out, nullptr, st);
+  if (!collect) return launch_combine(desc, pl, sp, out, st);
   FinalizeParams fp;
   fp.part_o = sp.part_o;
   fp.part_ml = sp.part_ml;
@@ -308,7 +303,7 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
     if (rc != VEGAS_OK) return rc;
   }
   if (desc->launch_stages != 0 && !(desc->launch_stages & VEGAS_STAGE_MERGE)) return VEGAS_OK;
-  return launch_combine(desc, pl, sp, out, nullptr, st);
+  return launch_combine(desc, pl, sp, out, st);
 }
 
 const char* vegas_strerror(int status) {

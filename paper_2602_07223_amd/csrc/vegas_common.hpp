@@ -64,7 +64,6 @@ struct CombineParams {
   const float2* part_ml;
   const int32_t* lens;
   uint16_t* out;            // bf16 [B, G, Hq, D]
-  float* row_lse;           // [B, Hkv, R] or nullptr
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
 };
 

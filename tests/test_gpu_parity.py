@@ -143,6 +143,40 @@ def test_baseline_config5_sampled_layers(layer):
     run_chain(L, L.spec.budget_tokens, name=f"stack32.layer{layer}")
 
 
+def test_long_chunk_reloads_the_page_id_batch():
+    """A chunk of 8192 tokens gives every wave 64 tiles: the 32-tile page-id batch is reloaded mid-stream."""
+    L = synth.make_random_case(seed=83, batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[9000 + 7], logit_std=1.0, outliers=2)
+    run_chain(L, 512, verify_chunk=8192, draft_chunk=8192, name="chunk8192")
+
+
+def test_strided_cache_views():
+    """The cache strides come from the descriptor: a cache that is a view into a larger allocation
+    (padded token rows, an unused extra KV head) must give the same results as the packed one."""
+    L = synth.make_random_case(seed=84, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[1500, 700], logit_std=1.0)
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=256)
+    path.iteration(dl)
+    torch.cuda.synchronize()
+    want = (path.out_verify.clone(), path.block_scores.clone(), path.sel_table.clone(), path.out_draft.clone())
+    P, Hkv, D = L.num_pages, 8, 128
+    big_k = torch.full((P, PAGE, Hkv + 1, D + 64), float("nan"), dtype=torch.bfloat16, device=path.device)
+    big_v = torch.full_like(big_k, float("nan"))
+    big_k[:, :, :Hkv, :D] = dl.k_cache
+    big_v[:, :, :Hkv, :D] = dl.v_cache
+    kview, vview = big_k[:, :, :Hkv, :D], big_v[:, :, :Hkv, :D]
+    for desc in (path.desc_verify, path.desc_draft):
+        desc.kv_page_stride, desc.kv_token_stride, desc.kv_head_stride = kview.stride(0), kview.stride(1), kview.stride(2)
+    dl2 = harness.DeviceLayer(dl.q_verify, dl.q_draft, kview, vview, dl.block_table, dl.seq_lens)
+    path.iteration(dl2)
+    torch.cuda.synchronize()
+    got = (path.out_verify, path.block_scores, path.sel_table, path.out_draft)
+    for a, b in zip(want, got):
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                           b.view(torch.int16) if b.dtype == torch.bfloat16 else b)
+
+
 def test_empty_and_short_sequences():
     L = synth.make_random_case(seed=79, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
                                seq_lens=[0, 3, 40], spare_pages=2)
