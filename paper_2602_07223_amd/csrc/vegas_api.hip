@@ -48,17 +48,19 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_ls
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
   if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
   pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks, one workgroup each
-  const int64_t tiles = heads * pl->NB * ((max_len + kTile - 1) / kTile);   // upper bound on 32-token tiles
-  pl->NW = (tiles >= 4 * 8 * kNumCU) ? 8 : 4;        // enough work for 8-wave groups of >= 4 tiles per wave
+  pl->NW = 4;                                        // measured: 4-wave groups match or beat 8-wave groups everywhere
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
-    const int64_t slots = kNumCU * (pl->NW == 4 ? 2 : 1);
-    int64_t splits = slots / (heads * pl->NB);
+    // One workgroup per CU when the batch is small (at 32K context 256 equal workgroups beat 512);
+    // with many (sequence, head) columns, shorter chunks balance ragged lengths better.
+    const int64_t columns = heads * pl->NB;
+    int64_t splits = kNumCU / columns;
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
-    if (c > 4096) c = 4096;
+    const int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
+    if (c > cap) c = cap;
     chunk = static_cast<int>(c);
   }
   pl->chunk = chunk;
@@ -108,12 +110,9 @@ int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st)
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
   constexpr bool kVerify = CAUSAL;                  // the verification pass is the only causal caller
-  if (kVerify && pl.NB == 1) {                      // one reader per K/V line, read once: stream it
-    if (pl.NW == 4) return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(256), lds, st, sp);
-    return launch_one(attn_split_kernel<8, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(512), lds, st, sp);
-  }
-  if (pl.NW == 4) return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, false>, grid, dim3(256), lds, st, sp);
-  return launch_one(attn_split_kernel<8, 2, CAUSAL, COLLECT, false>, grid, dim3(512), lds, st, sp);
+  if (kVerify && pl.NB == 1)                        // one reader per K/V line, read once: stream it
+    return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(256), lds, st, sp);
+  return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, false>, grid, dim3(256), lds, st, sp);
 }
 
 void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const void* q, const void* k,
