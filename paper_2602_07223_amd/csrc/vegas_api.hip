@@ -43,7 +43,7 @@ int check_common(const vegas_desc* d) {
 
 // Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
 // max_len bounds the lengths the call may see; small problems get small workgroups.
-int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, SplitPlan* pl) {
+int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, int wg_per_cu, SplitPlan* pl) {
   pl->R = rows_per_head;
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
   if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
@@ -52,10 +52,11 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_ls
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
-    // One workgroup per CU when the batch is small (at 32K context 256 equal workgroups beat 512);
-    // with many (sequence, head) columns, shorter chunks balance ragged lengths better.
+    // Verification: one workgroup per CU when the batch is small (at 32K context 256 equal workgroups
+    // beat 512); draft calls are latency-bound and like two small workgroups per CU.  With many
+    // (sequence, head) columns, shorter chunks balance ragged lengths better.
     const int64_t columns = heads * pl->NB;
-    int64_t splits = kNumCU / columns;
+    int64_t splits = static_cast<int64_t>(kNumCU) * wg_per_cu / columns;
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
@@ -79,12 +80,12 @@ int plan_verify(const vegas_desc* d, SplitPlan* pl) {
   if (d->num_queries <= 0) return VEGAS_ERR_SHAPE;
   if (d->collect_rows < 0 || d->collect_rows > 2) return VEGAS_ERR_SHAPE;
   const int g = d->num_q_heads / d->num_kv_heads;
-  return plan_split(d, d->num_queries * g, d->max_seq_len, d->collect_rows != 0, pl);
+  return plan_split(d, d->num_queries * g, d->max_seq_len, d->collect_rows != 0, 1, pl);
 }
 
 int plan_draft(const vegas_desc* d, SplitPlan* pl) {
   const int g = d->num_q_heads / d->num_kv_heads;
-  return plan_split(d, g, d->max_seq_len, false, pl);
+  return plan_split(d, g, d->max_seq_len, false, 2, pl);
 }
 
 // Launch with dynamic LDS; sizes above 64 KB need the attribute raised once per kernel.
