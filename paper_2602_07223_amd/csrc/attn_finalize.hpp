@@ -64,8 +64,8 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
 
 // Verification epilogue in ONE launch (a kernel boundary costs ~3 us on this GPU): workgroups
 // [0, nA) merge the chunk partials of two query rows each (as attn_combine_kernel does) and write
-// the bf16 output rows (Eq. 1); workgroups [nA, nA + nB) turn the per-(row, page) log-sum-exps of 32
-// pages into page criticalities (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the
+// the bf16 output rows (Eq. 1); workgroups [nA, nA + nB) turn the per-(row, page) log-sum-exps of
+// page_groups x 32 pages into page criticalities (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the
 // last paragraph of Sec. 3.3): score[b][j] = inv_norm * sum_h sum_{rows in R} 2^(page_lse - row_lse).
 // A score workgroup derives the global row log-sum-exps itself from the chunks' (max, sum) pairs,
 // so it does not depend on the merge workgroups.  Pages at or beyond the sequence's page count get 0.
@@ -134,10 +134,10 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   // ---- role B: 32 pages; thread = (page, head slot)
   const int nblk = (n + kPage - 1) / kPage;
   const int pg = tid & 31, slot = tid >> 5;
-  const int j = (blockIdx.x - p.nA) * 32 + pg;
+  const int jbase = (blockIdx.x - p.nA) * 32 * p.page_groups;       // page_groups x 32 pages per workgroup
   float* out_row = p.block_scores + static_cast<int64_t>(b) * p.max_blocks;
-  if (static_cast<int>(blockIdx.x - p.nA) * 32 >= nblk) {        // whole workgroup past the sequence
-    if (slot == 0 && j < p.max_blocks) out_row[j] = 0.f;
+  if (jbase >= nblk) {                                             // whole workgroup past the sequence
+    for (int j = jbase + tid; j < jbase + 32 * p.page_groups && j < p.max_blocks; j += 256) out_row[j] = 0.f;
     return;
   }
   float* sm_row = smf;                        // [HR] global row lse; -inf for rows that do not count
@@ -196,31 +196,35 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     sm_row[i] = (use && L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
   }
   __syncthreads();
-  float sc = 0.f;
-  if (j < nblk) {
-    for (int h = slot; h < p.Hkv; h += 8) {
-      const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
-      const float* rl = sm_row + h * p.R;
-      if ((p.R & 3) == 0) {
-        for (int r = 0; r < p.R; r += 4) {
-          const f32x4 x = *reinterpret_cast<const f32x4*>(pl + r);
+  for (int grp = 0; grp < p.page_groups; ++grp) {
+    const int j = jbase + grp * 32 + pg;
+    float sc = 0.f;
+    if (j < nblk) {
+      for (int h = slot; h < p.Hkv; h += 8) {
+        const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
+        const float* rl = sm_row + h * p.R;
+        if ((p.R & 3) == 0) {
+          for (int r = 0; r < p.R; r += 4) {
+            const f32x4 x = *reinterpret_cast<const f32x4*>(pl + r);
 #pragma unroll
-          for (int q = 0; q < 4; ++q)
-            if (rl[r + q] != -INFINITY) sc += fast_exp2(x[q] - rl[r + q]);
+            for (int q = 0; q < 4; ++q)
+              if (rl[r + q] != -INFINITY) sc += fast_exp2(x[q] - rl[r + q]);
+          }
+        } else {
+          for (int r = 0; r < p.R; ++r)
+            if (rl[r] != -INFINITY) sc += fast_exp2(pl[r] - rl[r]);
         }
-      } else {
-        for (int r = 0; r < p.R; ++r)
-          if (rl[r] != -INFINITY) sc += fast_exp2(pl[r] - rl[r]);
       }
     }
-  }
-  sm_sum[slot * 32 + pg] = sc;
-  __syncthreads();
-  if (slot == 0 && j < p.max_blocks) {
-    float tot = 0.f;
+    sm_sum[slot * 32 + pg] = sc;
+    __syncthreads();
+    if (slot == 0 && j < p.max_blocks) {
+      float tot = 0.f;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) tot += sm_sum[q * 32 + pg];
-    out_row[j] = (j < nblk) ? tot * p.inv_norm : 0.f;
+      for (int q = 0; q < 8; ++q) tot += sm_sum[q * 32 + pg];
+      out_row[j] = (j < nblk) ? tot * p.inv_norm : 0.f;
+    }
+    __syncthreads();
   }
 }
 

@@ -22,7 +22,7 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 
 __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const SelectParams p) {
   extern __shared__ uint32_t skeys[];                 // [min(prefix pages, key_cap)]
-  __shared__ uint32_t hist[4][256];
+  __shared__ uint32_t hist[kSelectThreads / 64][256];   // one digit histogram per wave: no cross-wave contention
   __shared__ uint32_t sh_prefix, sh_need;
   __shared__ uint32_t wave_take[kSelectThreads / 64], wave_eq[kSelectThreads / 64];
 
@@ -53,9 +53,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
   const bool need_search = kc > 0 && kc < f0;
   const bool take_all = kc >= f0;
 
-  // ---- keys of the prefix scores go to LDS once; the four digit histograms start at zero
+  // ---- keys of the prefix scores go to LDS once
   const bool in_lds = f0 <= p.key_cap;
-  hist[tid >> 8][tid & 255] = 0u;
   if (need_search && in_lds)
     for (int j = tid; j < f0; j += kSelectThreads) skeys[j] = score_key(scores[j]);
   __syncthreads();
@@ -68,7 +67,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
 #pragma unroll 1
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
-      uint32_t* h = hist[pass];
+      uint32_t* h = hist[wave];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) h[lane + 64 * i] = 0u;       // wave-private: ordered by the wave's own LDS stream
       for (int base = 0; base < f0; base += kSelectThreads) {
         const int j = base + tid;
         uint32_t key = 0u;
@@ -95,9 +96,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       __syncthreads();
       if (wave == 0) {
         // lane l owns bins 4l .. 4l+3; count from the top bin downwards
-        uint32_t c[4];
+        uint32_t c[4] = {0u, 0u, 0u, 0u};
+        for (int w = 0; w < kSelectThreads / 64; ++w) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = h[4 * lane + i];
+          for (int i = 0; i < 4; ++i) c[i] += hist[w][4 * lane + i];
+        }
         const uint32_t mine = c[0] + c[1] + c[2] + c[3];
         uint32_t incl = mine;                          // sum over lanes >= lane
 #pragma unroll
@@ -124,44 +127,71 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     need_eq = need;
   }
 
-  // ---- ordered compaction of the prefix
-  uint32_t out_base = 0u, eq_seen = 0u;
+  // ---- ordered compaction of the prefix: wave w owns the contiguous pages [w*span, (w+1)*span) and
+  //      walks them 64 at a time (lane = page), so page order is (wave, step, lane) and every memory
+  //      access is coalesced.  Ballots count ties and takes; two 16-entry prefixes over the wave totals
+  //      turn the counts into global ranks and output positions.
   if (kc > 0) {
-#pragma unroll 1
-    for (int start = 0; start < f0; start += kSelectThreads) {
-      const int j = start + tid;
-      uint32_t key = 0u;
-      const bool in = j < f0;
-      if (in && !take_all) key = key_at(j);
-      const bool eq = in && !take_all && key == T;
-      const bool gt = in && (take_all || key > T);
-      const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
-      const uint64_t lt = (1ull << lane) - 1ull;
-      if (lane == 0) wave_eq[wave] = __popcll(beq);
-      __syncthreads();
-      uint32_t eq_before = eq_seen, eq_total = 0u;
-      for (int w = 0; w < kSelectThreads / 64; ++w) {
-        const uint32_t c = wave_eq[w];
-        if (w < wave) eq_before += c;
-        eq_total += c;
+    constexpr int kWaves = kSelectThreads / 64;
+    const int span = ((f0 + kWaves - 1) / kWaves + 63) / 64 * 64;
+    const int w0 = min(wave * span, f0), w1 = min(w0 + span, f0);
+    const uint64_t lt = (1ull << lane) - 1ull;
+    // pass A: ties in this wave's pages
+    uint32_t eq_wave = 0u;
+    if (!take_all)
+      for (int base = w0; base < w1; base += 64) {
+        const int j = base + lane;
+        const bool eq = j < w1 && key_at(j) == T;
+        eq_wave += __popcll(__builtin_amdgcn_ballot_w64(eq));
       }
-      const uint32_t eq_rank = eq_before + __popcll(beq & lt);
-      const bool take = gt || (eq && eq_rank < need_eq);
+    if (lane == 0) wave_eq[wave] = eq_wave;
+    __syncthreads();
+    uint32_t eq_before = 0u;
+    for (int w = 0; w < wave; ++w) eq_before += wave_eq[w];
+    // pass B: pages taken by this wave
+    uint32_t take_wave = 0u, eq_run = eq_before;
+    for (int base = w0; base < w1; base += 64) {
+      const int j = base + lane;
+      bool take = j < w1 && take_all;
+      if (!take_all) {
+        bool eq = false, gt = false;
+        if (j < w1) {
+          const uint32_t key = key_at(j);
+          eq = key == T;
+          gt = key > T;
+        }
+        const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
+        take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
+        eq_run += __popcll(beq);
+      }
+      take_wave += __popcll(__builtin_amdgcn_ballot_w64(take));
+    }
+    if (lane == 0) wave_take[wave] = take_wave;
+    __syncthreads();
+    uint32_t pos_run = 0u;
+    for (int w = 0; w < wave; ++w) pos_run += wave_take[w];
+    // pass C: same decisions, now with positions; gather the physical page ids
+    eq_run = eq_before;
+    for (int base = w0; base < w1; base += 64) {
+      const int j = base + lane;
+      bool take = j < w1 && take_all;
+      if (!take_all) {
+        bool eq = false, gt = false;
+        if (j < w1) {
+          const uint32_t key = key_at(j);
+          eq = key == T;
+          gt = key > T;
+        }
+        const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
+        take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
+        eq_run += __popcll(beq);
+      }
       const uint64_t btk = __builtin_amdgcn_ballot_w64(take);
-      if (lane == 0) wave_take[wave] = __popcll(btk);
-      __syncthreads();
-      uint32_t tk_before = out_base, tk_total = 0u;
-      for (int w = 0; w < kSelectThreads / 64; ++w) {
-        const uint32_t c = wave_take[w];
-        if (w < wave) tk_before += c;
-        tk_total += c;
-      }
       if (take) {
-        const uint32_t pos = tk_before + __popcll(btk & lt);
+        const uint32_t pos = pos_run + __popcll(btk & lt);
         if (pos < static_cast<uint32_t>(p.max_sel_blocks)) sel[pos] = table[j];
       }
-      out_base += tk_total;
-      eq_seen += eq_total;
+      pos_run += __popcll(btk);
     }
   }
 

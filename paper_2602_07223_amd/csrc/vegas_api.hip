@@ -214,8 +214,15 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
                                                                    : (desc->num_queries > 1 ? 2 : 1);
   fp.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
-  const int nB = (desc->max_blocks + 31) / 32;
+  // Every score workgroup rebuilds the (rows x chunks) table of (max, sum) pairs; when that table is
+  // big, give each workgroup more pages so the redundant reads stay within a few MB per sequence.
   const size_t hr = static_cast<size_t>(sp.Hkv) * pl.R;
+  const size_t table_bytes = hr * pl.nsplit * sizeof(float2);
+  const int groups32 = (desc->max_blocks + 31) / 32;
+  int page_groups = 1;
+  (void)table_bytes;   // measured: larger page groups lose more to serialisation than the table re-reads cost
+  fp.page_groups = page_groups;
+  const int nB = (groups32 + page_groups - 1) / page_groups;
   const size_t shm = (hr + 256 + 16 * hr) * sizeof(float);   // role B needs the most; role A fits inside
   if (shm > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
   static bool big_lds = false;

@@ -77,6 +77,7 @@ struct FinalizeParams {
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t max_blocks, lse_pages, collect_rows;
   int32_t nA;               // workgroups that merge rows (two rows each); the rest score pages
+  int32_t page_groups;      // 32-page groups scored by one workgroup (more when its row table is big)
   float inv_norm;
 };
 
