@@ -14,6 +14,15 @@ Prints ONE JSON line: whole-path us per iteration (timed region = K iterations, 
 stream), the roofline of the dominant kernel (the KV-streaming verification kernel: K back-to-back
 launches of that kernel alone over the same rotating caches, bracketed by two HIP events on the
 launch stream) and the CPU oracle timed on the host cores as a reported baseline.
+
+Beyond the default run:
+  --workload NAME      another synthetic workload (ctx4k, ctx128k_drift, ragged16, stack32); the
+                       CPU baseline and the counter-derived traffic belong to the default workload only
+  --extras             adds per-iteration percentiles, the warm-cache figure (one cache copy) and the
+                       iteration replayed from captured HIP graphs to the same JSON line
+  --sweep collect      the collection-overhead curve (Sec. 3.3, Fig. 6 analogue): the verification call
+                       at G = 2..12 rows for collect_rows = none / all rows (Eq. 2) / first + bonus
+                       row (Eq. 3); prints one JSON line holding the table
 """
 from __future__ import annotations
 
@@ -29,12 +38,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the verification streaming kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9990 and 1.0).
-VERIFY_TRAFFIC_BYTES = 138_504_192   # (131378 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
-WORKLOAD = "ctx32k"
+# runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9989 and 1.0).
+VERIFY_TRAFFIC_BYTES = 138_511_360   # (131385 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
+DEFAULT_WORKLOAD = "ctx32k"
+ROTATE_BYTES = 1.2e9           # rotate cache copies up to about this much K+V in total
 
 
-def cpu_baseline(L, budget: int, target_seconds: float = 12.0):
+def cpu_baseline(L, budget: int, workload: str, target_seconds: float = 12.0):
     """Time the oracle as it stands on the host cores: whole iterations of the same workload."""
     from oracle import vegas_oracle as O
     try:
@@ -56,8 +66,82 @@ def cpu_baseline(L, budget: int, target_seconds: float = 12.0):
         one()
     dt = (time.perf_counter() - t0) / reps
     return {"value": dt * 1e6, "unit": "us", "cores": threads, "kind": "oracle",
-            "sample": f"{reps} whole iterations of the {WORKLOAD} workload (verify + select + "
+            "sample": f"{reps} whole iterations of the {workload} workload (verify + select + "
                       f"{L.spec.num_queries} draft steps), float64 NumPy oracle, mean"}
+
+
+def device_copies(harness, base, want: int):
+    """`want` device layers that share queries and tables with `base` but own their K/V caches."""
+    copies = [base]
+    for _ in range(want - 1):
+        copies.append(harness.DeviceLayer(q_verify=base.q_verify, q_draft=base.q_draft,
+                                          k_cache=base.k_cache.clone(), v_cache=base.v_cache.clone(),
+                                          block_table=base.block_table, seq_lens=base.seq_lens))
+    return copies
+
+
+def copies_for(base, asked: int) -> int:
+    kv_bytes = 2 * base.k_cache.numel() * base.k_cache.element_size()
+    return max(1, min(asked, int(ROTATE_BYTES // kv_bytes) + 1))
+
+
+def percentile(sorted_vals, q: float) -> float:
+    i = min(len(sorted_vals) - 1, max(0, int(round(q * (len(sorted_vals) - 1)))))
+    return sorted_vals[i]
+
+
+def sweep_collect(args, torch, vb, harness, synth) -> int:
+    """Collection-overhead curve: time of the verification call versus the number of verification
+    rows G and what is collected.  Sec. 3.3 measures that cost for an instrumented dense kernel
+    (all rows against two rows); this is the same question asked of the kernel here."""
+    dev = torch.device("cuda:0")
+    base_spec = synth.CONFIGS[args.workload]
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
+    K = args.steps
+    rows = []
+    modes = ((vb.COLLECT_NONE, "none"), (vb.COLLECT_ALL_ROWS, "all_rows"), (vb.COLLECT_FIRST_LAST, "first_last"))
+    for G in range(2, 13):
+        spec = synth.scaled(base_spec, gamma=G - 1)
+        L = synth.make_layer(spec)
+        base = harness.DeviceLayer.upload(L, dev)
+        copies = device_copies(harness, base, copies_for(base, args.copies))
+        verify_bytes = int(L.seq_lens.sum()) * 2 * spec.num_kv_heads * spec.head_dim * 2
+        entry = {"G": G, "rows_per_kv_head": G * spec.num_q_heads // spec.num_kv_heads}
+        for mode, name in modes:
+            path = harness.VegasPath.for_layer(L, collect_rows=mode, verify_chunk=args.verify_chunk)
+
+            def leg(stages: int) -> float:
+                path.desc_verify.launch_stages = stages
+                e0, e1 = vb.HipEvent(), vb.HipEvent()
+                for i in range(5):
+                    path.verify(copies[i % len(copies)])
+                torch.cuda.synchronize()
+                e0.record(stream)
+                for i in range(K):
+                    path.verify(copies[i % len(copies)])
+                e1.record(stream)
+                e1.synchronize()
+                path.desc_verify.launch_stages = 0
+                return e0.elapsed_ms(e1) / K * 1e3
+            call_us, stream_us = leg(0), leg(vb.STAGE_STREAM)
+            entry[name] = {"call_us": call_us, "stream_kernel_us": stream_us,
+                           "stream_gbps": verify_bytes / (stream_us * 1e-6) / 1e9}
+            del path
+        for name in ("all_rows", "first_last"):
+            entry[name]["overhead_pct_call"] = 100.0 * (entry[name]["call_us"] / entry["none"]["call_us"] - 1.0)
+            entry[name]["overhead_pct_stream_kernel"] = 100.0 * (entry[name]["stream_kernel_us"]
+                                                                 / entry["none"]["stream_kernel_us"] - 1.0)
+        rows.append(entry)
+        print(f"G={G:2d} none {entry['none']['call_us']:7.1f} us | all rows {entry['all_rows']['call_us']:7.1f} us "
+              f"({entry['all_rows']['overhead_pct_call']:+.1f}%) | first+last {entry['first_last']['call_us']:7.1f} us "
+              f"({entry['first_last']['overhead_pct_call']:+.1f}%)", file=sys.stderr, flush=True)
+        del copies, base, L
+        torch.cuda.empty_cache()
+    print(json.dumps({"sweep": "collect", "workload": args.workload, "steps": K, "unit": "us",
+                      "what": "vegas_verify_attention per call (streaming kernel + merge/score kernel) and its "
+                              "streaming kernel alone, cold caches, versus verification rows G and collect_rows",
+                      "rows": rows}), flush=True)
+    return 0
 
 
 def main() -> int:
@@ -65,11 +149,15 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--copies", type=int, default=8, help="device copies of the KV cache to rotate over")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--layer", type=int, default=0, help="layer of a multi-layer workload (own seed each)")
+    ap.add_argument("--copies", type=int, default=8, help="device copies of the KV cache to rotate over (at most)")
     ap.add_argument("--verify-chunk", type=int, default=0)
     ap.add_argument("--draft-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--extras", action="store_true")
+    ap.add_argument("--sweep", choices=["collect"], default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -84,15 +172,18 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     vb.load_library()                                   # fail loudly if the HIP library is not built
-    spec = synth.CONFIGS[WORKLOAD]
-    L = synth.make_layer(spec)
+    if args.workload not in synth.CONFIGS:
+        print(f"bench.py: unknown workload {args.workload!r}; one of {sorted(synth.CONFIGS)}", file=sys.stderr)
+        return 2
+    if args.sweep == "collect":
+        return sweep_collect(args, torch, vb, harness, synth)
+
+    workload = args.workload
+    spec = synth.CONFIGS[workload]
+    L = synth.make_layer(spec, args.layer)
     dev = torch.device("cuda:0")
     base = harness.DeviceLayer.upload(L, dev)
-    copies = [base]
-    for _ in range(max(1, args.copies) - 1):
-        copies.append(harness.DeviceLayer(q_verify=base.q_verify, q_draft=base.q_draft,
-                                          k_cache=base.k_cache.clone(), v_cache=base.v_cache.clone(),
-                                          block_table=base.block_table, seq_lens=base.seq_lens))
+    copies = device_copies(harness, base, copies_for(base, args.copies))
     path = harness.VegasPath.for_layer(L, verify_chunk=args.verify_chunk, draft_chunk=args.draft_chunk)
     G = spec.num_queries
     stream = int(torch.cuda.current_stream(dev).cuda_stream)
@@ -134,8 +225,9 @@ def main() -> int:
         desc.launch_stages = 0
         return e0.elapsed_ms(e1) / reps * 1e3
 
+    traffic = VERIFY_TRAFFIC_BYTES if workload == DEFAULT_WORKLOAD and args.verify_chunk == 0 else None
     roofline = {"bound": "hbm", "kernel": "attn_split_kernel<causal, collect> (KV-streaming kernel of vegas_verify_attention)",
-                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": VERIFY_TRAFFIC_BYTES,
+                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": traffic,
                 "bytes_per_launch": verify_bytes}
     roofline_draft = None
     if not args.no_kernel_events:
@@ -154,7 +246,8 @@ def main() -> int:
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": us_per_step / 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD, "batch": spec.batch, "context": int(L.seq_lens.max()),
+        "config": {"workload": workload, "batch": spec.batch, "context": int(L.seq_lens.max()),
+                   "context_tokens_total": n_tokens, "layer": args.layer,
                    "num_q_heads": spec.num_q_heads, "num_kv_heads": spec.num_kv_heads,
                    "head_dim": spec.head_dim, "page_size": 16, "gamma": spec.gamma,
                    "kv_budget_tokens": spec.budget_tokens, "draft_steps": G,
@@ -165,8 +258,54 @@ def main() -> int:
     }
     if roofline_draft is not None:
         out["roofline_draft"] = roofline_draft
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens)
+
+    if args.extras:
+        # (1) per-iteration HIP events: spread of single iterations (the events add a little to each)
+        evs = [(vb.HipEvent(), vb.HipEvent()) for _ in range(K)]
+        torch.cuda.synchronize()
+        for i in range(K):
+            evs[i][0].record(stream)
+            step(i)
+            evs[i][1].record(stream)
+        torch.cuda.synchronize()
+        per = sorted(a.elapsed_ms(b) * 1e3 for a, b in evs)
+        # (2) warm caches: every step reads the same cache copy
+        for i in range(W):
+            path.iteration(copies[0])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            path.iteration(copies[0])
+        torch.cuda.synchronize()
+        warm_us = (time.perf_counter() - t0) / K * 1e6
+        # (3) the iteration replayed from captured HIP graphs (one graph per cache copy)
+        graphs = []
+        side = torch.cuda.Stream(device=dev)
+        side.wait_stream(torch.cuda.current_stream(dev))
+        with torch.cuda.stream(side):
+            for c in copies:
+                path.iteration(c)                      # settle one-time set-up outside capture
+        torch.cuda.synchronize()
+        for c in copies:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                path.iteration(c)
+            graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(W):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / K * 1e6
+        out["extras"] = {"iteration_us_p10": percentile(per, 0.1), "iteration_us_p50": percentile(per, 0.5),
+                         "iteration_us_p90": percentile(per, 0.9), "iteration_us_warm_cache": warm_us,
+                         "iteration_us_hip_graph": graph_us}
+
+    if not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0:
+        out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens, workload)
     print(json.dumps(out), flush=True)
     return 0
 

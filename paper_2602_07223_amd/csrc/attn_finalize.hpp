@@ -62,69 +62,145 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
   p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
 }
 
+// The same merge for at most MAXS (<= 64) chunks, in ONE memory round trip: the sequence length, the
+// chunks' (max, sum) pairs (lane s of every wave fetches chunk s) and the thread's element of every
+// chunk's partial row are all requested before any of them is used.  Chunks at or past the end of the
+// sequence were never written; their slots are loaded all the same (the workspace holds nsplit of them)
+// and then discarded.  Addresses are a scalar base plus a 32-bit offset: the kernel is so short that
+// 64-bit address arithmetic per load would show in its run time.
+template <int MAXS>
+struct RowMerge {
+  f32x2 mine;        // (max, sum) of chunk `lane`
+  float x[MAXS];     // this thread's head dim of every chunk's partial row
+  // ml, po: the row's first chunk (wave-uniform); d: head dim of this thread
+  __device__ __forceinline__ void issue(const float2* ml, const float* po, int d, int R, int nsplit) {
+    const int lane = threadIdx.x & 63;
+    const unsigned char* mlb = uniform_ptr(reinterpret_cast<const unsigned char*>(ml));
+    const unsigned char* pob = uniform_ptr(reinterpret_cast<const unsigned char*>(po));
+    const uint32_t last = static_cast<uint32_t>(nsplit - 1);
+    mine = gload<f32x2, false>(mlb, min(static_cast<uint32_t>(lane), last) * static_cast<uint32_t>(R) * 8u);
+    const uint32_t stride = static_cast<uint32_t>(R) * kHeadDim * 4u;
+    const uint32_t off = static_cast<uint32_t>(d) * 4u;
+#pragma unroll
+    for (int s = 0; s < MAXS; ++s) x[s] = gload<float, false>(pob, off + min(static_cast<uint32_t>(s), last) * stride);
+    __builtin_amdgcn_sched_barrier(0);     // every request leaves before the first use
+  }
+  // Output element: sum_s 2^(m_s - m) x_s / sum_s 2^(m_s - m) l_s over the first ns chunks; 0 if no key was visible.
+  __device__ __forceinline__ float finish(int ns) const {
+    const int lane = threadIdx.x & 63;
+    const float ms = lane < ns ? mine[0] : -INFINITY;
+    float m = ms;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    const float m_use = (m == -INFINITY) ? 0.f : m;
+    const float w = fast_exp2(ms - m_use);              // 0 for lanes at or past ns
+    float L = lane < ns ? w * mine[1] : 0.f;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off, 64);
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < MAXS; ++s) {
+      const float ws = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), s));
+      acc += (s < ns) ? ws * x[s] : 0.f;
+    }
+    return (L > 0.f) ? acc / L : 0.f;
+  }
+};
+
+template <int MAXS>
+__global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombineParams p) {
+  const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
+  int n = p.lens[b];
+  RowMerge<MAXS> rm;
+  rm.issue(p.part_ml + pbase * p.R + r, p.part_o + (pbase * p.R + r) * kHeadDim, tid, p.R, p.nsplit);
+  n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+  const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+  const float o = rm.finish(ns);
+  const int t = r / p.g, j = r % p.g;
+  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
+}
+
 // Verification epilogue in ONE launch (a kernel boundary costs ~3 us on this GPU): workgroups
-// [0, nA) merge the chunk partials of two query rows each (as attn_combine_kernel does) and write
+// [0, nA) merge the chunk partials of two query rows each (as the combine kernels do) and write
 // the bf16 output rows (Eq. 1); workgroups [nA, nA + nB) turn the per-(row, page) log-sum-exps of
 // page_groups x 32 pages into page criticalities (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the
 // last paragraph of Sec. 3.3): score[b][j] = inv_norm * sum_h sum_{rows in R} 2^(page_lse - row_lse).
 // A score workgroup derives the global row log-sum-exps itself from the chunks' (max, sum) pairs,
 // so it does not depend on the merge workgroups.  Pages at or beyond the sequence's page count get 0.
+// MAXS > 0: at most MAXS chunks, the merge workgroups take the one-round-trip path; 0: any number.
+// Loads are ordered so that a workgroup's dependent memory round trips are as few as possible: the
+// kernel runs for a handful of microseconds and every trip is a sizeable part of that.
+constexpr int kFinUnits = 6;     // (row, eighth of the chunks) units a score thread loads per batch
+constexpr int kFinPre = 8;       // page log-sum-exps a score thread keeps in registers: 4 * kFinPre rows
+
+template <int MAXS>
 __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizeParams p) {
-  extern __shared__ float smf[];              // role A: [2][128] weights + [2][4]; role B: [Hkv*R] + [8][32] + [Hkv*R][8] pairs
+  extern __shared__ float smf[];              // role A (general path): [2][128] weights + [2][4]; role B: [Hkv*R] + [8][32] + [Hkv*R][8] pairs
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
-  int n = p.lens[b];
-  n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-  const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const int HR = p.Hkv * p.R;
 
   if (static_cast<int>(blockIdx.x) < p.nA) {
     // ---- role A: rows 2*bx and 2*bx+1 of the Hkv*R rows, 128 threads (= head dims) each
     const int sub = tid >> 7, t128 = tid & 127, wv = (tid >> 6) & 1;
-    float* sw = smf + sub * 128;
-    float* sred = smf + 256 + sub * 4;
     const int rr_raw = 2 * blockIdx.x + sub;
     const bool valid = rr_raw < HR;
     const int rr = valid ? rr_raw : HR - 1;
     const int h = rr / p.R, r = rr % p.R;
     const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
     const float2* ml = p.part_ml + pbase * p.R + r;
-    const float* po = p.part_o + (pbase * p.R + r) * kHeadDim + t128;
-    const int64_t ostride = static_cast<int64_t>(p.R) * kHeadDim;
-    float m = -INFINITY;
-    for (int s = t128; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
+    float o;
+    if constexpr (MAXS > 0) {
+      int n = p.lens[b];
+      RowMerge<MAXS> rm;
+      rm.issue(ml, p.part_o + (pbase * p.R + r) * kHeadDim, t128, p.R, p.nsplit);
+      n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+      o = rm.finish((n + p.chunk_tokens - 1) / p.chunk_tokens);
+    } else {
+      int n = p.lens[b];
+      n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+      const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+      const float* po = p.part_o + (pbase * p.R + r) * kHeadDim + t128;
+      float* sw = smf + sub * 128;
+      float* sred = smf + 256 + sub * 4;
+      const int64_t ostride = static_cast<int64_t>(p.R) * kHeadDim;
+      float m = -INFINITY;
+      for (int s = t128; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-    if ((tid & 63) == 0) sred[wv] = m;
-    __syncthreads();
-    m = fmaxf(sred[0], sred[1]);
-    const float m_use = (m == -INFINITY) ? 0.f : m;
-    float accv = 0.f, L = 0.f;
-    for (int s0 = 0; s0 < ns; s0 += 128) {
-      const int cnt = min(128, ns - s0);
-      float wl = 0.f;
-      if (t128 < cnt) {
-        const float2 v = ml[static_cast<int64_t>(s0 + t128) * p.R];
-        const float w = fast_exp2(v.x - m_use);
-        sw[t128] = w;
-        wl = w * v.y;
-      }
+      for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      if ((tid & 63) == 0) sred[wv] = m;
+      __syncthreads();
+      m = fmaxf(sred[0], sred[1]);
+      const float m_use = (m == -INFINITY) ? 0.f : m;
+      float accv = 0.f, L = 0.f;
+      for (int s0 = 0; s0 < ns; s0 += 128) {
+        const int cnt = min(128, ns - s0);
+        float wl = 0.f;
+        if (t128 < cnt) {
+          const float2 v = ml[static_cast<int64_t>(s0 + t128) * p.R];
+          const float w = fast_exp2(v.x - m_use);
+          sw[t128] = w;
+          wl = w * v.y;
+        }
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 64);
-      if ((tid & 63) == 0) sred[2 + wv] = wl;
-      __syncthreads();
-      L += sred[2] + sred[3];
-      int s = 0;
-      for (; s + 4 <= cnt; s += 4) {
-        const float x0 = po[(s0 + s) * ostride], x1 = po[(s0 + s + 1) * ostride];
-        const float x2 = po[(s0 + s + 2) * ostride], x3 = po[(s0 + s + 3) * ostride];
-        accv += sw[s] * x0 + sw[s + 1] * x1 + sw[s + 2] * x2 + sw[s + 3] * x3;
+        for (int off = 32; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 64);
+        if ((tid & 63) == 0) sred[2 + wv] = wl;
+        __syncthreads();
+        L += sred[2] + sred[3];
+        int s = 0;
+        for (; s + 4 <= cnt; s += 4) {
+          const float x0 = po[(s0 + s) * ostride], x1 = po[(s0 + s + 1) * ostride];
+          const float x2 = po[(s0 + s + 2) * ostride], x3 = po[(s0 + s + 3) * ostride];
+          accv += sw[s] * x0 + sw[s + 1] * x1 + sw[s + 2] * x2 + sw[s + 3] * x3;
+        }
+        for (; s < cnt; ++s) accv += sw[s] * po[(s0 + s) * ostride];
+        __syncthreads();
       }
-      for (; s < cnt; ++s) accv += sw[s] * po[(s0 + s) * ostride];
-      __syncthreads();
+      o = (L > 0.f) ? accv / L : 0.f;
     }
     if (valid) {
-      const float o = (L > 0.f) ? accv / L : 0.f;
       const int t = r / p.g, j = r % p.g;
       p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + t128] = float_to_bf16_bits(o);
     }
@@ -132,44 +208,70 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   }
 
   // ---- role B: 32 pages; thread = (page, head slot)
-  const int nblk = (n + kPage - 1) / kPage;
   const int pg = tid & 31, slot = tid >> 5;
   const int jbase = (blockIdx.x - p.nA) * 32 * p.page_groups;       // page_groups x 32 pages per workgroup
   float* out_row = p.block_scores + static_cast<int64_t>(b) * p.max_blocks;
+  float* sm_row = smf;                        // [HR] global row lse; -inf for rows that do not count
+  float* sm_sum = smf + HR;                   // [8][32]
+  float2* sm_pair = reinterpret_cast<float2*>(smf + HR + 256);   // [HR][8] (max, sum) of a row over 1/8 of the chunks
+
+  // Each (row, eighth of the chunks) pair is one unit of work: a thread requests the (max, sum) pairs of
+  // kFinUnits units (four chunks each) at once and merges them afterwards, so the table costs about one
+  // memory round trip per batch instead of one per chunk.  Slots of chunks past the sequence's end are
+  // loaded too (the workspace holds nsplit of them) and dropped at the merge.
+  float2 v[kFinUnits][4];
+  auto load_units = [&](int s0, int u0) {
+#pragma unroll
+    for (int a = 0; a < kFinUnits; ++a) {
+      const int u = u0 + 256 * a;
+      const int i = u < HR * 8 ? (u >> 3) : 0, sg = u & 7;
+      const int h = i / p.R, r = i % p.R;
+      const float2* ml = p.part_ml + (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit * p.R + r;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int sidx = min(s0 + sg + 8 * q, p.nsplit - 1);
+        v[a][q] = ml[static_cast<int64_t>(sidx) * p.R];
+      }
+    }
+  };
+  // The first batch, and (with one 32-page group and few rows) this thread's page log-sum-exps, are
+  // requested before the sequence length is needed.
+  const bool pre_ok = p.page_groups == 1 && (p.R & 3) == 0 && p.R <= 4 * kFinPre && p.Hkv <= 8;
+  f32x4 pre[kFinPre];
+  const int jpre = min(jbase + pg, p.lse_pages - 1);
+  if (pre_ok && slot < p.Hkv) {
+    const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + slot) * p.lse_pages + jpre) * p.R;
+#pragma unroll
+    for (int q = 0; q < kFinPre; ++q)
+      if (4 * q < p.R) pre[q] = *reinterpret_cast<const f32x4*>(pl + 4 * q);
+  }
+  load_units(0, tid);
+
+  int n = p.lens[b];
+  n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+  const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+  const int nblk = (n + kPage - 1) / kPage;
   if (jbase >= nblk) {                                             // whole workgroup past the sequence
     for (int j = jbase + tid; j < jbase + 32 * p.page_groups && j < p.max_blocks; j += 256) out_row[j] = 0.f;
     return;
   }
-  float* sm_row = smf;                        // [HR] global row lse; -inf for rows that do not count
-  float* sm_sum = smf + HR;                   // [8][32]
-  float2* sm_pair = reinterpret_cast<float2*>(smf + HR + 256);   // [HR][8] (max, sum) of a row over 1/8 of the chunks
-  // Each (row, eighth of the chunks) pair is one unit of work.  A thread first issues the (max, sum)
-  // loads of four units (up to 16 independent loads), then merges them, so the whole table costs
-  // about one memory round trip instead of one per chunk.
+  bool loaded = true;
   for (int s0 = 0; s0 < ns; s0 += 32) {
-    for (int u0 = tid; u0 < HR * 8; u0 += 4 * 256) {
-      float2 v[4][4];
+    for (int u0 = tid; u0 < HR * 8; u0 += kFinUnits * 256) {
+      if (!loaded) load_units(s0, u0);
+      loaded = false;
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int u = u0 + 256 * a;
-        const bool uv = u < HR * 8;
-        const int i = uv ? (u >> 3) : 0, sg = u & 7;
-        const int h = i / p.R, r = i % p.R;
-        const float2* ml = p.part_ml + (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit * p.R + r;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int sidx = s0 + sg + 8 * q;
-          v[a][q] = (uv && sidx < ns) ? ml[static_cast<int64_t>(sidx) * p.R] : make_float2(-INFINITY, 0.f);
-        }
-      }
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
+      for (int a = 0; a < kFinUnits; ++a) {
         const int u = u0 + 256 * a;
         if (u < HR * 8) {
+          const int sg = u & 7;
           float2 cur = (s0 == 0) ? make_float2(-INFINITY, 0.f) : sm_pair[u];
           float m = cur.x;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) m = fmaxf(m, v[a][q].x);
+          for (int q = 0; q < 4; ++q) {
+            if (s0 + sg + 8 * q >= ns) v[a][q] = make_float2(-INFINITY, 0.f);
+            m = fmaxf(m, v[a][q].x);
+          }
           const float mu = (m == -INFINITY) ? 0.f : m;
           float L = cur.y * fast_exp2(cur.x - mu);
 #pragma unroll
@@ -190,8 +292,8 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     float L = 0.f;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const float2 v = sm_pair[i * 8 + q];
-      L += fast_exp2(v.x - m_use) * v.y;
+      const float2 pr = sm_pair[i * 8 + q];
+      L += fast_exp2(pr.x - m_use) * pr.y;
     }
     sm_row[i] = (use && L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
   }
@@ -200,19 +302,33 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     const int j = jbase + grp * 32 + pg;
     float sc = 0.f;
     if (j < nblk) {
-      for (int h = slot; h < p.Hkv; h += 8) {
-        const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
-        const float* rl = sm_row + h * p.R;
-        if ((p.R & 3) == 0) {
-          for (int r = 0; r < p.R; r += 4) {
-            const f32x4 x = *reinterpret_cast<const f32x4*>(pl + r);
+      if (pre_ok) {
+        if (slot < p.Hkv) {
+          const float* rl = sm_row + slot * p.R;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-              if (rl[r + q] != -INFINITY) sc += fast_exp2(x[q] - rl[r + q]);
+          for (int q = 0; q < kFinPre; ++q) {
+            if (4 * q < p.R) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (rl[4 * q + e] != -INFINITY) sc += fast_exp2(pre[q][e] - rl[4 * q + e]);
+            }
           }
-        } else {
-          for (int r = 0; r < p.R; ++r)
-            if (rl[r] != -INFINITY) sc += fast_exp2(pl[r] - rl[r]);
+        }
+      } else {
+        for (int h = slot; h < p.Hkv; h += 8) {
+          const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
+          const float* rl = sm_row + h * p.R;
+          if ((p.R & 3) == 0) {
+            for (int r = 0; r < p.R; r += 4) {
+              const f32x4 x = *reinterpret_cast<const f32x4*>(pl + r);
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                if (rl[r + q] != -INFINITY) sc += fast_exp2(x[q] - rl[r + q]);
+            }
+          } else {
+            for (int r = 0; r < p.R; ++r)
+              if (rl[r] != -INFINITY) sc += fast_exp2(pl[r] - rl[r]);
+          }
         }
       }
     }

@@ -51,26 +51,6 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Pins a wave-uniform pointer into scalar registers so that loads take the
-// "scalar base + 32-bit lane offset" addressing form.
-__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* ptr) {
-  const uint64_t v = reinterpret_cast<uint64_t>(ptr);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
-  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
-  return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
-}
-
-// Global-memory load at (wave-uniform base) + (32-bit lane offset).  STREAMING marks data that is
-// read once (the verification pass over the whole cache): the non-temporal hint keeps it from
-// displacing useful lines and was worth 7-12 % of the kernel time.
-template <typename T, bool STREAMING>
-__device__ __forceinline__ T gload(const unsigned char* sbase, uint32_t voff) {
-  typedef const __attribute__((address_space(1))) T* gp;
-  gp ptr = (gp)((const __attribute__((address_space(1))) unsigned char*)sbase + voff);
-  if (STREAMING) return __builtin_nontemporal_load(ptr);
-  return *ptr;
-}
-
 constexpr int kRowPitch = 272;   // LDS bytes per 256-byte K/Q row: the 16-byte pad spreads rows over banks
 
 constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffer (128 + pad)

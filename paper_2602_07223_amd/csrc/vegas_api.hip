@@ -4,6 +4,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "attn_finalize.hpp"
 #include "attn_split.hpp"
 #include "select_blocks.hpp"
@@ -88,16 +92,27 @@ int plan_draft(const vegas_desc* d, SplitPlan* pl) {
   return plan_split(d, g, d->max_seq_len, false, 2, pl);
 }
 
-// Launch with dynamic LDS; sizes above 64 KB need the attribute raised once per kernel.
+// A kernel whose static + dynamic LDS passes the default 64 KB limit needs its limit raised first: once
+// per (device, kernel function).  The table is keyed by the function's address because every
+// instantiation of the streaming kernel has the same C++ type.
+int ensure_dynamic_lds(const void* kern, size_t lds) {
+  if (lds <= 32 * 1024) return VEGAS_OK;
+  static std::mutex mu;
+  static std::set<std::pair<int, const void*>> raised;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return VEGAS_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  const std::pair<int, const void*> key(dev, kern);
+  if (raised.count(key)) return VEGAS_OK;
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+    return VEGAS_ERR_LAUNCH;
+  raised.insert(key);
+  return VEGAS_OK;
+}
+
 template <typename Kern>
 int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, const SplitParams& sp) {
-  static size_t allowed = 64 * 1024;                 // per instantiation of this template
-  if (lds > allowed) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(160 * 1024)) != hipSuccess)
-      return VEGAS_ERR_LAUNCH;
-    allowed = 160 * 1024;
-  }
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds)) return rc;
   hipLaunchKernelGGL(kern, grid, block, lds, st, sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
@@ -152,7 +167,21 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   cp.out = static_cast<uint16_t*>(out);
   cp.G = sp.G; cp.g = sp.g; cp.R = sp.R; cp.Hq = sp.Hq; cp.Hkv = sp.Hkv;
   cp.chunk_tokens = pl.chunk; cp.nsplit = pl.nsplit; cp.max_tokens = d->max_seq_len;
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(pl.R, sp.Hkv, d->batch), dim3(128), 0, st, cp);
+  const dim3 grid(pl.R, sp.Hkv, d->batch);
+  if (pl.nsplit <= 8)
+    hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 12)
+    hipLaunchKernelGGL(attn_combine_small_kernel<12>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 16)
+    hipLaunchKernelGGL(attn_combine_small_kernel<16>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 20)
+    hipLaunchKernelGGL(attn_combine_small_kernel<20>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 24)
+    hipLaunchKernelGGL(attn_combine_small_kernel<24>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 32)
+    hipLaunchKernelGGL(attn_combine_small_kernel<32>, grid, dim3(128), 0, st, cp);
+  else
+    hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(128), 0, st, cp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
@@ -225,14 +254,16 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   const int nB = (groups32 + page_groups - 1) / page_groups;
   const size_t shm = (hr + 256 + 16 * hr) * sizeof(float);   // role B needs the most; role A fits inside
   if (shm > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
-  static bool big_lds = false;
-  if (shm > 64 * 1024 && !big_lds) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(verify_finalize_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VEGAS_ERR_LAUNCH;
-    big_lds = true;
-  }
-  hipLaunchKernelGGL(verify_finalize_kernel, dim3(fp.nA + nB, desc->batch), dim3(256), shm, st, fp);
+  const dim3 fgrid(fp.nA + nB, desc->batch);
+  auto launch_finalize = [&](auto kern) -> int {
+    if (int lrc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), shm)) return lrc;
+    hipLaunchKernelGGL(kern, fgrid, dim3(256), shm, st, fp);
+    return VEGAS_OK;
+  };
+  if (pl.nsplit <= 16) rc = launch_finalize(verify_finalize_kernel<16>);
+  else if (pl.nsplit <= 32) rc = launch_finalize(verify_finalize_kernel<32>);
+  else rc = launch_finalize(verify_finalize_kernel<0>);
+  if (rc != VEGAS_OK) return rc;
   if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
   return VEGAS_OK;
 }
@@ -270,14 +301,8 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const
   sp.max_tokens = desc->max_seq_len;
   const int64_t max_pages = (static_cast<int64_t>(desc->max_seq_len) + kPage - 1) / kPage;
   sp.key_cap = static_cast<int32_t>(max_pages < kSelectKeyCap ? max_pages : kSelectKeyCap);
-  static bool big_lds = false;
   const size_t shm = static_cast<size_t>(sp.key_cap) * sizeof(uint32_t);
-  if (shm > 48 * 1024 && !big_lds) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(select_blocks_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess)
-      return VEGAS_ERR_LAUNCH;
-    big_lds = true;
-  }
+  if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(select_blocks_kernel), shm)) return rc;
   hipLaunchKernelGGL(select_blocks_kernel, dim3(desc->batch), dim3(kSelectThreads), shm,
                      static_cast<hipStream_t>(hip_stream), sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;

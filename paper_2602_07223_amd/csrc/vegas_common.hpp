@@ -12,6 +12,7 @@ constexpr int kTile = 32;       // tokens per MFMA tile (two pages)
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
@@ -38,6 +39,26 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return static_cast<uint16_t>(u >> 16);
+}
+
+// Pins a wave-uniform pointer into scalar registers so that loads take the
+// "scalar base + 32-bit lane offset" addressing form.
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* ptr) {
+  const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return reinterpret_cast<const unsigned char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// Global-memory load at (wave-uniform base) + (32-bit lane offset).  STREAMING marks data that is
+// read once (the verification pass over the whole cache): the non-temporal hint keeps it from
+// displacing useful lines and was worth 7-12 % of the kernel time.
+template <typename T, bool STREAMING>
+__device__ __forceinline__ T gload(const unsigned char* sbase, uint32_t voff) {
+  typedef const __attribute__((address_space(1))) T* gp;
+  gp ptr = (gp)((const __attribute__((address_space(1))) unsigned char*)sbase + voff);
+  if constexpr (STREAMING) return __builtin_nontemporal_load(ptr);
+  else return *ptr;
 }
 
 // Arguments of the KV-streaming attention kernel (verification and draft share it).

@@ -90,6 +90,19 @@ def test_collect_modes(collect):
     run_chain(L, 256, collect=collect, name=f"collect{collect}")
 
 
+def test_many_chunks_take_the_general_merge():
+    """More than 32 chunks per row: the merge kernels leave their few-chunk fast paths (verification with
+    and without collection, and the draft steps)."""
+    L = synth.make_random_case(seed=81, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[9000, 300], logit_std=1.5, outliers=2)
+    path, ref_out, _ = run_chain(L, 6000, verify_chunk=128, draft_chunk=128, name="many_chunks")
+    dl = harness.DeviceLayer.upload(L)
+    plain = harness.VegasPath.for_layer(L, budget_tokens=6000, collect_rows=vb.COLLECT_NONE, verify_chunk=128)
+    plain.verify(dl)
+    torch.cuda.synchronize()
+    U.check_out("many_chunks.collect_none", plain.out_verify, ref_out, U.vmax_visible(L))
+
+
 def test_collect_none_leaves_scores_untouched_and_out_correct():
     L = synth.make_random_case(seed=78, batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, seq_lens=[2500])
     dl = harness.DeviceLayer.upload(L)
@@ -232,6 +245,51 @@ def test_run_to_run_bit_reproducible():
                       path.sel_table.cpu().numpy().copy(), path.out_draft.view(torch.int16).cpu().numpy().copy()))
     for s in snaps[1:]:
         for a, b in zip(snaps[0], s):
+            assert np.array_equal(a, b)
+
+
+def test_hip_graph_replays_match_eager():
+    """The three calls only enqueue kernels on the caller's stream, so a whole iteration can be captured
+    into a HIP graph.  Every replay (with eager work and synchronisations in between, outputs wiped before
+    each) must reproduce the eager results bit for bit."""
+    L = synth.make_layer(synth.scaled(synth.CONFIGS["ctx4k"], seq_len=3072 + 5))
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L)
+
+    def snap():
+        torch.cuda.synchronize()
+        return (path.out_verify.view(torch.int16).cpu().numpy().copy(), path.block_scores.cpu().numpy().copy(),
+                path.sel_table.cpu().numpy().copy(), path.sel_seq_lens.cpu().numpy().copy(),
+                path.out_draft.view(torch.int16).cpu().numpy().copy())
+
+    def wipe():
+        path.out_verify.fill_(float("nan"))
+        path.block_scores.fill_(float("nan"))
+        path.sel_table.fill_(-7)
+        path.sel_seq_lens.fill_(-7)
+        path.out_draft.fill_(float("nan"))
+        path.workspace.fill_(0xFF)
+
+    path.iteration(dl)
+    eager = snap()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        path.iteration(dl)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        path.iteration(dl)
+    for replay in range(4):
+        wipe()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snap()
+        for a, b in zip(eager, got):
+            assert np.array_equal(a, b), f"replay {replay} differs from the eager run"
+        wipe()
+        path.iteration(dl)                      # eager work between replays
+        for a, b in zip(eager, snap()):
             assert np.array_equal(a, b)
 
 
