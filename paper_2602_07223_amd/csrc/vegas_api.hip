@@ -104,7 +104,10 @@ int ensure_dynamic_lds(const void* kern, size_t lds) {
   std::lock_guard<std::mutex> lock(mu);
   const std::pair<int, const void*> key(dev, kern);
   if (raised.count(key)) return VEGAS_OK;
-  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+  hipFuncAttributes attr;
+  if (hipFuncGetAttributes(&attr, kern) != hipSuccess) return VEGAS_ERR_LAUNCH;
+  const int room = 160 * 1024 - static_cast<int>(attr.sharedSizeBytes);   // the CU's LDS minus the kernel's static part
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, room) != hipSuccess)
     return VEGAS_ERR_LAUNCH;
   raised.insert(key);
   return VEGAS_OK;
@@ -180,6 +183,12 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
     hipLaunchKernelGGL(attn_combine_small_kernel<24>, grid, dim3(128), 0, st, cp);
   else if (pl.nsplit <= 32)
     hipLaunchKernelGGL(attn_combine_small_kernel<32>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 40)
+    hipLaunchKernelGGL(attn_combine_small_kernel<40>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 48)
+    hipLaunchKernelGGL(attn_combine_small_kernel<48>, grid, dim3(128), 0, st, cp);
+  else if (pl.nsplit <= 64)
+    hipLaunchKernelGGL(attn_combine_small_kernel<64>, grid, dim3(128), 0, st, cp);
   else
     hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(128), 0, st, cp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;

@@ -91,13 +91,13 @@ def test_collect_modes(collect):
 
 
 def test_many_chunks_take_the_general_merge():
-    """More than 32 chunks per row: the merge kernels leave their few-chunk fast paths (verification with
+    """More than 64 chunks per row: the merge kernels leave their few-chunk fast paths (verification with
     and without collection, and the draft steps)."""
     L = synth.make_random_case(seed=81, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=5,
                                seq_lens=[9000, 300], logit_std=1.5, outliers=2)
-    path, ref_out, _ = run_chain(L, 6000, verify_chunk=128, draft_chunk=128, name="many_chunks")
+    path, ref_out, _ = run_chain(L, 8800, verify_chunk=128, draft_chunk=128, name="many_chunks")
     dl = harness.DeviceLayer.upload(L)
-    plain = harness.VegasPath.for_layer(L, budget_tokens=6000, collect_rows=vb.COLLECT_NONE, verify_chunk=128)
+    plain = harness.VegasPath.for_layer(L, budget_tokens=8800, collect_rows=vb.COLLECT_NONE, verify_chunk=128)
     plain.verify(dl)
     torch.cuda.synchronize()
     U.check_out("many_chunks.collect_none", plain.out_verify, ref_out, U.vmax_visible(L))
@@ -318,3 +318,33 @@ def test_select_bit_exact_with_ties_and_budgets():
         ref_sel, ref_ssl, _ = O.select_blocks(scores, table, lens, G, 640, mb, budgets if use_per_seq else None)
         assert np.array_equal(sel.cpu().numpy(), ref_sel)
         assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
+
+
+@pytest.mark.parametrize("pages", [9000, 16384, 20011])
+def test_select_long_sequences(pages):
+    """Page counts above what the other cases reach: keys that fill the kernel's LDS budget and, past it,
+    the path that re-reads the scores; scores drawn like attention mass (a few large, most tiny, ties)."""
+    rng = np.random.default_rng(pages)
+    B, G = 2, 5
+    lens = np.array([pages * PAGE - 3, (pages // 2) * PAGE + 1], dtype=np.int32)
+    nblk = (lens + PAGE - 1) // PAGE
+    scores = np.zeros((B, pages), dtype=np.float32)
+    for b in range(B):
+        x = rng.random(nblk[b]).astype(np.float32) ** 8
+        x[rng.integers(0, nblk[b], size=nblk[b] // 4)] = np.float32(2.0 ** -14)        # many exact ties
+        scores[b, :nblk[b]] = x / x.sum()
+    table = np.stack([rng.permutation(pages + 50)[:pages] for _ in range(B)]).astype(np.int32)
+    budget = 4096
+    msb = budget // PAGE + 2
+    desc = vb.make_desc(batch=B, num_q_heads=32, num_kv_heads=8, num_queries=G, max_blocks=pages, max_sel_blocks=msb,
+                        max_seq_len=pages * PAGE, num_pages=pages + 50, softmax_scale=0.1)
+    dev = torch.device("cuda:0")
+    sel = torch.empty((B, msb), dtype=torch.int32, device=dev)
+    ssl = torch.empty((B,), dtype=torch.int32, device=dev)
+    print(f"[case] select_long pages={pages}", flush=True)
+    vb.vegas_select_blocks(desc, torch.from_numpy(scores).to(dev), torch.from_numpy(table).to(dev),
+                           torch.from_numpy(lens).to(dev), budget, sel, ssl)
+    torch.cuda.synchronize()
+    ref_sel, ref_ssl, _ = O.select_blocks(scores, table, lens, G, budget, msb)
+    assert np.array_equal(sel.cpu().numpy(), ref_sel)
+    assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
