@@ -34,7 +34,8 @@ Readings taken where the paper is silent (each is also listed in the design note
   * a row with no visible key (only possible when seq_len < gamma+1) outputs 0 and
     contributes no weight.
 
-Pins (tests/test_oracle_*.py): closed forms for uniform weights, one-hot dominance, the
+Pins (tests/test_oracle_*.py): draft attention over 1/2/4/8-token pages against library attention
+over the listed tokens, closed forms for uniform weights, one-hot dominance, the
 library routines torch.nn.functional.scaled_dot_product_attention and scipy.special
 (softmax, logsumexp) on special cases, exhaustive subset search for the argmax of Eq. 2 on
 tiny inputs, sum-to-one invariants, page-permutation invariance, budget >= context.
@@ -63,12 +64,15 @@ def decode_bf16(bits: np.ndarray) -> np.ndarray:
 def gather_sequence(cache_bits: np.ndarray, pages: np.ndarray, n_tokens: int, kv_head: int) -> np.ndarray:
     """Tokens 0..n_tokens-1 of one sequence for one KV head as float64 [n_tokens, D].
 
-    Token i lives in physical page pages[i // 16], slot i % 16 of the NHD cache
-    [num_pages, 16, H_kv, D] (App. D)."""
-    nblk = (n_tokens + PAGE - 1) // PAGE
+    Token i lives in physical page pages[i // P], slot i % P of the NHD cache
+    [num_pages, P, H_kv, D] (App. D).  P is the cache's own page size: 16 on the
+    verify/select path; the draft step may list pages of 1, 2, 4, 8 or 16 tokens (Sec. 4 drafts
+    with one-token pages, the selected token indices serving as page indices; App. D sweeps 1..16)."""
+    P = cache_bits.shape[1]
+    nblk = (n_tokens + P - 1) // P
     phys = np.asarray(pages[:nblk], dtype=np.int64)
-    x = cache_bits[phys, :, kv_head, :]                    # [nblk, 16, D]
-    x = x.reshape(nblk * PAGE, -1)[:n_tokens]
+    x = cache_bits[phys, :, kv_head, :]                    # [nblk, P, D]
+    x = x.reshape(nblk * P, -1)[:n_tokens]
     return decode_bf16(x)
 
 
@@ -195,8 +199,9 @@ def draft_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
                     sel_table: np.ndarray, sel_seq_lens: np.ndarray, scale: float) -> np.ndarray:
     """One draft query per sequence attends over exactly the tokens of the selected pages.
 
-    q uint16 [B, H_q, D]; sel_table int32 [B, max_sel_blocks] physical page ids; sel_seq_lens[b]
-    tokens are valid (only the last listed page may be partial).  No causal mask: the draft token
+    q uint16 [B, H_q, D]; sel_table int32 [B, max_sel_blocks] physical page ids of the cache as it is
+    passed in ([num_pages, P, H_kv, D], any page size P); sel_seq_lens[b] tokens are valid (only the
+    last listed page may be partial).  No causal mask: the draft token
     is newer than everything cached.  Returns float64 [B, H_q, D]."""
     B, Hq, D = q.shape
     Hkv = k_cache.shape[2]

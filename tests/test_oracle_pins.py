@@ -359,6 +359,52 @@ def test_draft_over_hand_built_selection_matches_library_attention():
     np.testing.assert_allclose(out[0], ref, atol=1e-12)
 
 
+@pytest.mark.parametrize("P", [1, 2, 4, 8])
+def test_draft_over_small_pages_matches_library_attention(P):
+    """Page sizes below 16 (Sec. 4: one-token pages, token indices as page indices; App. D sweeps 1..16):
+    an arbitrary ascending list of P-token pages of the same pool, last page partial, against library
+    attention over the tokens those pages hold by the layout's definition."""
+    n, Hq, Hkv, D = 96, 4, 2, 32
+    c = small_case(23 + P, n, 1, Hq, Hkv, D)
+    rng = np.random.default_rng(P)
+    kc = c["k_cache"].reshape(-1, P, Hkv, D)                     # the same bytes seen as P-token pages
+    vc = c["v_cache"].reshape(-1, P, Hkv, D)
+    npg = n // P
+    logical = np.sort(rng.choice(npg, size=min(npg, 5 + 24 // P), replace=False))   # logical small pages
+    tail_tokens = max(1, P // 2)                                 # the last listed page is partial
+    tok = np.concatenate([np.arange(P * j, P * (j + 1)) for j in logical])
+    tok = tok[:len(tok) - (P - tail_tokens)]
+    # physical small-page id of logical small page j: inside 16-token page table[j*P // 16]
+    phys = c["block_table"][0, (logical * P) // PAGE].astype(np.int64) * (PAGE // P) + (logical * P % PAGE) // P
+    sel = np.full((1, len(logical) + 3), -1, dtype=np.int32)
+    sel[0, :len(logical)] = phys
+    ssl = np.array([len(tok)], dtype=np.int32)
+    out = O.draft_attention(c["q"][:, 0], kc, vc, sel, ssl, c["scale"])
+    q = torch.from_numpy(c["Q"][0]).permute(1, 0, 2)[None]
+    k = torch.from_numpy(c["Kd"][tok]).permute(1, 0, 2)[None]
+    v = torch.from_numpy(c["Vd"][tok]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, enable_gqa=True)[0, :, 0].numpy()
+    np.testing.assert_allclose(out[0], ref, atol=1e-12)
+
+
+def test_draft_result_does_not_depend_on_the_page_size_of_the_view():
+    """Listing the same tokens as 16-token pages or as their 1/2/4/8-token sub-pages gives the same bits."""
+    n, Hq, Hkv, D = 80, 4, 2, 32
+    c = small_case(29, n, 1, Hq, Hkv, D)
+    logical = np.array([0, 3, 4])
+    sel16 = np.full((1, 4), -1, dtype=np.int32)
+    sel16[0, :3] = c["block_table"][0, logical]
+    ssl = np.array([3 * PAGE], dtype=np.int32)
+    ref = O.draft_attention(c["q"][:, 0], c["k_cache"], c["v_cache"], sel16, ssl, c["scale"])
+    for P in (1, 2, 4, 8):
+        sub = PAGE // P
+        sel = np.full((1, 3 * sub + 1), -1, dtype=np.int32)
+        sel[0, :3 * sub] = (sel16[0, :3, None].astype(np.int64) * sub + np.arange(sub)[None, :]).reshape(-1)
+        out = O.draft_attention(c["q"][:, 0], c["k_cache"].reshape(-1, P, Hkv, D),
+                                c["v_cache"].reshape(-1, P, Hkv, D), sel, ssl, c["scale"])
+        assert np.array_equal(out, ref)
+
+
 # ----------------------------------------------------------------------------------------------
 # layout
 # ----------------------------------------------------------------------------------------------
