@@ -20,6 +20,8 @@ Beyond the default run:
                        CPU baseline and the counter-derived traffic belong to the default workload only
   --extras             adds per-iteration percentiles, the warm-cache figure (one cache copy) and the
                        iteration replayed from captured HIP graphs to the same JSON line
+  --sweep page_size    draft attention latency versus the page size (1..16 tokens) of the selection table in the
+                       set-up of App. D / Table 5 (batch 16, 8192 selected tokens per request, random positions)
   --sweep collect      the collection-overhead curve (Sec. 3.3, Fig. 6 analogue): the verification call
                        at G = 2..12 rows for collect_rows = none / all rows (Eq. 2) / first + bonus
                        row (Eq. 3); prints one JSON line holding the table
@@ -144,6 +146,82 @@ def sweep_collect(args, torch, vb, harness, synth) -> int:
     return 0
 
 
+PAPER_TABLE5_H100_US = {1: 197.6, 2: 197.6, 4: 197.1, 8: 198.1, 16: 198.3}   # App. D, Table 5, first row (another machine: context)
+
+
+def sweep_page_size(args, torch, vb) -> int:
+    """Sparse (draft) attention latency versus the page size of the selection table, in the set-up of
+    App. D / Table 5: batch 16, a K/V pool of 16 x 128K tokens, 8192 selected tokens per request
+    (8192 / page_size pages at random positions of the whole pool), 32 query / 8 KV heads, head_dim 128."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    B, Hq, Hkv, D, sel_tokens = 16, 32, 8, 128, 8192
+    pool_tokens = B * 131072
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7223900)
+    k_pool = torch.empty((pool_tokens, Hkv, D), dtype=torch.bfloat16, device=dev)
+    v_pool = torch.empty((pool_tokens, Hkv, D), dtype=torch.bfloat16, device=dev)
+    step = 1 << 20
+    for t0 in range(0, pool_tokens, step):                       # N(0,1)/sqrt(D), drawn on the device piece by piece
+        k_pool[t0:t0 + step].normal_(0.0, D ** -0.5, generator=gen)
+        v_pool[t0:t0 + step].normal_(0.0, D ** -0.5, generator=gen)
+    q = torch.empty((B, Hq, D), dtype=torch.bfloat16, device=dev).normal_(0.0, D ** -0.5, generator=gen)
+    out = torch.empty((B, Hq, D), dtype=torch.bfloat16, device=dev)
+    rng = np.random.default_rng(7223901)
+    K = args.steps
+    rows = []
+    bytes_per_call = B * sel_tokens * 2 * Hkv * D * 2
+    for P in (1, 2, 4, 8, 16):
+        n_sel = sel_tokens // P
+        pool_pages = pool_tokens // P
+        tables = []
+        for _ in range(3):                                       # rotate over three selections: nothing stays cached
+            ids = rng.choice(pool_pages, size=B * n_sel, replace=False).astype(np.int32).reshape(B, n_sel)
+            ids.sort(axis=1)
+            tables.append(torch.from_numpy(ids).to(dev))
+        ssl = torch.full((B,), sel_tokens, dtype=torch.int32, device=dev)
+        desc = vb.make_desc(batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=1, max_blocks=n_sel,
+                            max_sel_blocks=n_sel, max_seq_len=sel_tokens, num_pages=pool_pages,
+                            softmax_scale=D ** -0.5, page_size=P, kv_chunk_tokens=args.draft_chunk)
+        ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        addr = dict(q=q.data_ptr(), k=k_pool.data_ptr(), v=v_pool.data_ptr(), ssl=ssl.data_ptr(), out=out.data_ptr(),
+                    ws=ws.data_ptr(), t=[t.data_ptr() for t in tables])
+
+        def call(i: int) -> None:
+            vb.vegas_draft_attention(desc, addr["q"], addr["k"], addr["v"], addr["t"][i % 3], addr["ssl"], addr["out"],
+                                     addr["ws"], stream=stream, workspace_bytes=ws.numel())
+
+        def leg(stages: int) -> float:
+            desc.launch_stages = stages
+            e0, e1 = vb.HipEvent(), vb.HipEvent()
+            for i in range(5):
+                call(i)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for i in range(K):
+                call(i)
+            e1.record(stream)
+            e1.synchronize()
+            desc.launch_stages = 0
+            return e0.elapsed_ms(e1) / K * 1e3
+        call_us, stream_us = leg(0), leg(vb.STAGE_STREAM)
+        rows.append({"page_size": P, "call_us": call_us, "stream_kernel_us": stream_us,
+                     "call_gbps": bytes_per_call / (call_us * 1e-6) / 1e9,
+                     "stream_kernel_gbps": bytes_per_call / (stream_us * 1e-6) / 1e9,
+                     "stream_kernel_frac_of_peak": bytes_per_call / (stream_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                     "paper_h100_us": PAPER_TABLE5_H100_US[P]})
+        print(f"page_size={P:2d} call {call_us:7.1f} us ({rows[-1]['call_gbps']:.0f} GB/s) | streaming kernel "
+              f"{stream_us:7.1f} us ({rows[-1]['stream_kernel_gbps']:.0f} GB/s, "
+              f"{100 * rows[-1]['stream_kernel_frac_of_peak']:.1f}% of peak) | paper, H100: {PAPER_TABLE5_H100_US[P]} us",
+              file=sys.stderr, flush=True)
+    print(json.dumps({"sweep": "page_size", "steps": K, "unit": "us", "kv_bytes_per_call": bytes_per_call,
+                      "what": "vegas_draft_attention, batch 16, 8192 selected tokens per request at random pool "
+                              "positions, K/V pool of 16 x 128K tokens (App. D, Table 5 set-up)",
+                      "rows": rows}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,7 +235,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--extras", action="store_true")
-    ap.add_argument("--sweep", choices=["collect"], default=None)
+    ap.add_argument("--sweep", choices=["collect", "page_size"], default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -177,6 +255,8 @@ def main() -> int:
         return 2
     if args.sweep == "collect":
         return sweep_collect(args, torch, vb, harness, synth)
+    if args.sweep == "page_size":
+        return sweep_page_size(args, torch, vb)
 
     workload = args.workload
     spec = synth.CONFIGS[workload]

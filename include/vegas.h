@@ -66,12 +66,13 @@ typedef struct vegas_desc {
   int32_t num_q_heads;     /* H_q */
   int32_t num_kv_heads;    /* H_kv, divides H_q */
   int32_t head_dim;        /* 128 */
-  int32_t page_size;       /* 16 tokens */
+  int32_t page_size;       /* tokens per page: 16; vegas_draft_attention also takes 1, 2, 4, 8 */
   int32_t num_queries;     /* verify: G = gamma+1 rows per sequence; ignored by draft (1 row) */
   int32_t max_blocks;      /* row stride of block_table and block_scores */
   int32_t max_sel_blocks;  /* row stride of sel_table */
   int32_t max_seq_len;     /* upper bound on every seq_lens[b] (and sel_seq_lens[b]); sizes the
-                              launch grid and the workspace; <= max_blocks*page_size */
+                              launch grid and the workspace; <= max_blocks*page_size for verify
+                              and select, <= max_sel_blocks*page_size for draft */
   int32_t collect_rows;    /* VEGAS_COLLECT_* */
   int32_t kv_chunk_tokens; /* tokens of one sequence handled by one workgroup; 0 = choose */
   int32_t launch_stages;   /* profiling aid: 0 = whole call; else VEGAS_STAGE_* bits to launch only
@@ -137,6 +138,12 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores,
  *   out          bf16 [B, H_q, D]           softmax attention over exactly the first sel_seq_lens[b]
  *                                          token slots of the listed pages; no causal mask; 0 if
  *                                          sel_seq_lens[b] == 0
+ * Page size: desc->page_size may be 1, 2, 4, 8 or 16 here (Sec. 4 drafts over one-token pages, the
+ * selected token indices serving as page indices; App. D compares page sizes 1..16).  sel_table then
+ * lists physical pages of the SAME cache memory seen as [num_pages, page_size, H_kv, D], with
+ * kv_page_stride = page_size * kv_token_stride for a contiguous pool and num_pages counted in such
+ * pages; only the last listed page of a sequence may be partial.  The other two calls return
+ * VEGAS_ERR_UNSUPPORTED for page sizes other than 16.
  */
 int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                           const int32_t* sel_table, const int32_t* sel_seq_lens,

@@ -60,11 +60,17 @@ constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffe
 // NT_LOADS: K/V are read with the non-temporal hint -- right for the verification pass that streams
 // the cache once with one reader per line; wrong for draft (the next draft step re-reads the same
 // pages) and for row-block siblings (the second reader wants the L2 hit).
-template <int NW, int WPS, bool CAUSAL, bool COLLECT, bool NT_LOADS>
+// PS: log2 of the tokens per page of the table the kernel walks.  4 (16-token pages) is the path
+// described above; 0..3 (1, 2, 4, 8-token pages: Sec. 4 drafts with one-token pages, App. D sweeps
+// 1..16) is for draft calls only: a tile then spans 32 >> PS pages, every lane looks up the page of
+// its own token, and the page ids travel one tile ahead through a small per-wave LDS ring.
+template <int NW, int WPS, bool CAUSAL, bool COLLECT, bool NT_LOADS, int PS = 4>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
-  // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums]
+  static_assert(PS == 4 || (!CAUSAL && !COLLECT && !NT_LOADS), "small pages: draft calls only");
+  // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NB = 1;                      // one 32-row block per workgroup
+  constexpr int TP = 32 >> (PS < 4 ? PS : 0);   // pages per tile on the small-page path
   unsigned char* qlds = smem + p.lds_q_off;
   float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
   float* sm_l = sm_m + NW * NB * 32;
@@ -82,6 +88,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   const int split = blockIdx.x / (p.Hkv * p.row_blocks);
   const int b = blockIdx.y;
   const int row0 = rb * 32;                  // first query row (of this KV head) handled here
+  int* ids_lds = reinterpret_cast<int*>(sm_l + NW * NB * 32) + wave * 64;   // [2 tiles][32 page ids] of this wave
   const int Rl = min(32, p.R - row0);        // valid rows in this block
 
   // Physical page ids of the wave's next 32 tiles live in one register: lane (k, half) holds the id of
@@ -100,7 +107,17 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
     pagevec = static_cast<int>(ph);
   };
-  load_pagevec(0);
+  // Small pages: ids of the TP pages of this wave's tile k, lane e (mod TP) -> page e of the tile.
+  auto load_ids = [&](int k) -> int {
+    int page = (tile_first + k * NW) * TP + (lane & (TP - 1));
+    page = page < p.table_stride ? page : p.table_stride - 1;
+    int64_t ph = table[page];
+    ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
+    return static_cast<int>(ph);
+  };
+  int ids_pending = 0;
+  if constexpr (PS == 4) load_pagevec(0);
+  else ids_pending = load_ids(0);
 
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
@@ -123,7 +140,23 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     return uniform_ptr(reinterpret_cast<const unsigned char*>(cache + static_cast<int64_t>(ph) * p.page_stride + head_off));
   };
   // tile index k counts this wave's tiles: tile = tile_first + k*NW
+  // Small pages: byte address of token t (0..31) of tile k for this lane's KV head, from the ring slot of that tile.
+  typedef const __attribute__((address_space(1))) unsigned char* gbytes;
+  auto token_addr = [&](const uint16_t* cache, int k, int t) -> gbytes {
+    const int id = ids_lds[(k & 1) * 32 + (t >> (PS & 3))];
+    const int tokin = t & ((1 << (PS & 3)) - 1);
+    const int64_t el = static_cast<int64_t>(id) * p.page_stride + static_cast<int64_t>(tokin) * p.token_stride + head_off;
+    return (gbytes)cache + el * 2;
+  };
   auto issue_k = [&](int k, u32x4 (&kr)[8]) {
+    if constexpr (PS != 4) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        typedef const __attribute__((address_space(1))) u32x4* gp;
+        kr[i] = *(gp)(token_addr(p.k, k, 4 * i + k_tok) + k_chunk * 16);
+      }
+      return;
+    }
     if ((k & 31) == 0 && k > 0) load_pagevec(k);
     const int ph0 = __builtin_amdgcn_readlane(pagevec, k & 31);
     const int ph1 = __builtin_amdgcn_readlane(pagevec, 32 + (k & 31));
@@ -137,6 +170,17 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   };
   // V load (s, jj): token 16s + 8(jj/4) + 4*half + jj%4 of the tile, head dims 4*l32 .. 4*l32+3
   auto issue_v = [&](int k, u32x2 (&vr)[16]) {
+    if constexpr (PS != 4) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+          typedef const __attribute__((address_space(1))) u32x2* gp;
+          vr[s * 8 + jj] = *(gp)(token_addr(p.v, k, 16 * s + 8 * (jj >> 2) + 4 * half + (jj & 3)) + l32 * 8);
+        }
+      }
+      return;
+    }
     const int ph0 = __builtin_amdgcn_readlane(pagevec, k & 31);
     const int ph1 = __builtin_amdgcn_readlane(pagevec, 32 + (k & 31));
     const unsigned char* vb0 = page_base(p.v, ph0);
@@ -154,6 +198,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   // ---- first tile's loads go out before anything else
   u32x4 kr[8];
   u32x2 va[16], vb[16];
+  if constexpr (PS != 4) {                   // tile 0's page ids enter the ring; tile 1's are requested
+    if (lane < TP) ids_lds[lane] = ids_pending;
+    ids_pending = load_ids(1);
+    wave_lds_fence();
+  }
   if (tile_first < tile_end) {
     issue_k(0, kr);
     issue_v(0, va);
@@ -205,6 +254,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       *reinterpret_cast<u32x4*>(kst + (4 * i + k_tok) * kRowPitch + k_chunk * 16) = kr[i];
     }
     if (has_next) {
+      if constexpr (PS != 4) {               // next tile's ids -> ring; the ids after that -> on their way
+        if (lane < TP) ids_lds[((k + 1) & 1) * 32 + lane] = ids_pending;
+        ids_pending = load_ids(k + 2);
+        wave_lds_fence();
+      }
       issue_k(k + 1, kr);
       issue_v(k + 1, vnxt);
     }
@@ -385,7 +439,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 
 // Dynamic LDS bytes of attn_split_kernel<NW, ...> when a workgroup holds up to `rows` (<= 32) valid rows.
 inline size_t split_lds_tail_bytes(int NW) {
-  return static_cast<size_t>(32) * kRowPitch + 2 * static_cast<size_t>(NW) * 32 * sizeof(float);
+  return static_cast<size_t>(32) * kRowPitch + 2 * static_cast<size_t>(NW) * 32 * sizeof(float) +
+         static_cast<size_t>(NW) * 64 * sizeof(int);                 // queries, row maxima and sums, page-id ring
 }
 // lse_tokens > 0: page scores are collected and the chunk's page log-sum-exps (chunk_pages x rows floats)
 // sit right behind the K tiles.

@@ -34,14 +34,23 @@ int check_common(const vegas_desc* d) {
       d->max_seq_len <= 0 || d->num_pages <= 0)
     return VEGAS_ERR_SHAPE;
   if (d->num_q_heads % d->num_kv_heads != 0) return VEGAS_ERR_SHAPE;
-  if (static_cast<int64_t>(d->max_seq_len) > static_cast<int64_t>(d->max_blocks) * kPage) return VEGAS_ERR_SHAPE;
-  if (d->head_dim != kHeadDim || d->page_size != kPage) return VEGAS_ERR_UNSUPPORTED;
-  if (d->kv_head_stride < kHeadDim || d->kv_token_stride < kHeadDim || d->kv_page_stride < kPage * kHeadDim)
+  if (d->head_dim != kHeadDim) return VEGAS_ERR_UNSUPPORTED;
+  if (d->page_size != 1 && d->page_size != 2 && d->page_size != 4 && d->page_size != 8 && d->page_size != kPage)
+    return VEGAS_ERR_UNSUPPORTED;
+  if (d->kv_head_stride < kHeadDim || d->kv_token_stride < kHeadDim ||
+      d->kv_page_stride < static_cast<int64_t>(d->page_size) * kHeadDim)
     return VEGAS_ERR_SHAPE;
   if ((d->kv_head_stride % 8) || (d->kv_token_stride % 8) || (d->kv_page_stride % 8)) return VEGAS_ERR_ALIGN;
   if (d->kv_chunk_tokens < 0 || (d->kv_chunk_tokens % kTile) != 0) return VEGAS_ERR_SHAPE;
   if (!(d->softmax_scale > 0.f)) return VEGAS_ERR_SHAPE;
   if (d->launch_stages < 0 || d->launch_stages > (VEGAS_STAGE_STREAM | VEGAS_STAGE_MERGE)) return VEGAS_ERR_SHAPE;
+  return VEGAS_OK;
+}
+
+// Verification and selection work on 16-token pages and a block table that covers max_seq_len.
+int check_paged16(const vegas_desc* d) {
+  if (d->page_size != kPage) return VEGAS_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(d->max_seq_len) > static_cast<int64_t>(d->max_blocks) * kPage) return VEGAS_ERR_SHAPE;
   return VEGAS_OK;
 }
 
@@ -121,13 +130,22 @@ int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, con
 }
 
 template <bool CAUSAL, bool COLLECT>
-int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st) {
+int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size = kPage) {
   const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
   const int rows = pl.R < 32 ? pl.R : 32;
   const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT ? pl.chunk : 0);
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW));
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
+  if constexpr (!CAUSAL && !COLLECT) {              // draft calls may walk a table of smaller pages
+    switch (page_size) {
+      case 1: return launch_one(attn_split_kernel<4, 2, false, false, false, 0>, grid, dim3(256), lds, st, sp);
+      case 2: return launch_one(attn_split_kernel<4, 2, false, false, false, 1>, grid, dim3(256), lds, st, sp);
+      case 4: return launch_one(attn_split_kernel<4, 2, false, false, false, 2>, grid, dim3(256), lds, st, sp);
+      case 8: return launch_one(attn_split_kernel<4, 2, false, false, false, 3>, grid, dim3(256), lds, st, sp);
+      default: break;
+    }
+  }
   constexpr bool kVerify = CAUSAL;                  // the verification pass is the only causal caller
   if (kVerify && pl.NB == 1)                        // one reader per K/V line, read once: stream it
     return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(256), lds, st, sp);
@@ -202,7 +220,8 @@ size_t vegas_workspace_bytes(const vegas_desc* desc) {
   if (check_common(desc) != VEGAS_OK) return 0;
   SplitPlan pv, pd;
   size_t need = kAlign;
-  if (desc->num_queries > 0 && plan_verify(desc, &pv) == VEGAS_OK) need = pv.total > need ? pv.total : need;
+  if (desc->num_queries > 0 && check_paged16(desc) == VEGAS_OK && plan_verify(desc, &pv) == VEGAS_OK)
+    need = pv.total > need ? pv.total : need;
   if (plan_draft(desc, &pd) == VEGAS_OK) need = pd.total > need ? pd.total : need;
   return need;
 }
@@ -211,6 +230,7 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
                            const int32_t* block_table, const int32_t* seq_lens, void* out, float* block_scores,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_common(desc);
+  if (rc == VEGAS_OK) rc = check_paged16(desc);
   if (rc != VEGAS_OK) return rc;
   if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out) return VEGAS_ERR_NULL;
   SplitPlan pl;
@@ -284,6 +304,7 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const
   (void)workspace;
   (void)workspace_bytes;
   int rc = check_common(desc);
+  if (rc == VEGAS_OK) rc = check_paged16(desc);
   if (rc != VEGAS_OK) return rc;
   if (!block_scores || !block_table || !seq_lens || !sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
   if (desc->num_queries <= 0 || desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
@@ -324,7 +345,7 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
   if (rc != VEGAS_OK) return rc;
   if (!q || !k_cache || !v_cache || !sel_table || !sel_seq_lens || !out) return VEGAS_ERR_NULL;
   if (desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
-  if (static_cast<int64_t>(desc->max_seq_len) > static_cast<int64_t>(desc->max_sel_blocks) * kPage)
+  if (static_cast<int64_t>(desc->max_seq_len) > static_cast<int64_t>(desc->max_sel_blocks) * desc->page_size)
     return VEGAS_ERR_SHAPE;
   SplitPlan pl;
   rc = plan_draft(desc, &pl);
@@ -339,7 +360,7 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
   fill_split_params(desc, pl, 1, q, k_cache, v_cache, sel_table, desc->max_sel_blocks, sel_seq_lens, ws, &sp);
   if (desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM)) {
     if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-    rc = launch_split<false, false>(pl, sp, desc->batch, st);
+    rc = launch_split<false, false>(pl, sp, desc->batch, st, desc->page_size);
     if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }
