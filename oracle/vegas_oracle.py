@@ -15,6 +15,10 @@ from the product.  It is a plain float64 NumPy implementation of the *definition
   * top-k selection                   -- the argmax of Eq. 2 / Eq. 3, here over unions of
                                          16-token KV pages; "remaining tokens are kept"
                                          (Sec. 3.2, last sentence) becomes the forced tail pages
+  * the paper's own selection variant -- logits as the metric (Sec. 3.2 footnote, App. B), single
+                                         tokens as the unit (Sec. 4): token_logit_scores,
+                                         select_tokens; drafting over them is draft_attention on
+                                         the cache seen with one-token pages
   * sparse drafting                   -- Sec. 2.2 (attention over the selected entries only),
                                          realised as paged attention over the selected page
                                          list (Sec. 4, App. D)
@@ -34,7 +38,9 @@ Readings taken where the paper is silent (each is also listed in the design note
   * a row with no visible key (only possible when seq_len < gamma+1) outputs 0 and
     contributes no weight.
 
-Pins (tests/test_oracle_*.py): draft attention over 1/2/4/8-token pages against library attention
+Pins (tests/test_oracle_*.py): token logit scores against scalar loops, the closed form
+k_i . mean(q) and the single-head ranking identity of App. B; token selection against exhaustive
+subset search for Eq. 3, numpy partition and hand-worked cases; draft attention over 1/2/4/8-token pages against library attention
 over the listed tokens, closed forms for uniform weights, one-hot dominance, the
 library routines torch.nn.functional.scaled_dot_product_attention and scipy.special
 (softmax, logsumexp) on special cases, exhaustive subset search for the argmax of Eq. 2 on
@@ -192,6 +198,88 @@ def select_blocks(block_scores: np.ndarray, block_table: np.ndarray, seq_lens: n
         nblk = (n + PAGE - 1) // PAGE
         tail = n - PAGE * (nblk - 1)               # tokens in the last logical page (always selected)
         sel_seq_lens[b] = PAGE * (ids.size - 1) + tail
+    return sel_table, sel_seq_lens, logical
+
+
+# ---------------------------------------------------------------------------------------------
+# The paper's own selection variant: attention LOGITS as the metric, single tokens as the unit
+# (Sec. 3.2 Eq. 2, Sec. 3.3 Eq. 3 and its last paragraph, Sec. 4, App. B)
+# ---------------------------------------------------------------------------------------------
+
+def token_logit_scores(q: np.ndarray, k_cache: np.ndarray, block_table: np.ndarray,
+                       seq_lens: np.ndarray, scale: float, collect_rows: int = COLLECT_FIRST_LAST) -> np.ndarray:
+    """Criticality of every PREFIX token from the verification logits.
+
+    The prefix P of sequence b is tokens 0 .. p_b - 1 with p_b = max(n_b - G, 0): what the draft
+    tokens were conditioned on, all of it visible to every verification row.  score[b, i] is the
+    mean over the collected rows (all of them for Eq. 2, the first draft row and the bonus row for
+    Eq. 3) and over all query heads of the scaled logit scale * q_{t,h} . k_i -- the averaging of
+    Sec. 3.3's last paragraph; the top-k of these scores is the argmax of Eq. 2 / Eq. 3.
+    Returns float64 [B, max_blocks * 16]; entries at and beyond p_b are 0 and mean nothing."""
+    B, G, Hq, D = q.shape
+    Hkv = k_cache.shape[2]
+    g = Hq // Hkv
+    qf = decode_bf16(q)
+    R = collected_rows(G, collect_rows)
+    scores = np.zeros((B, block_table.shape[1] * PAGE), dtype=np.float64)
+    if not R:
+        return scores
+    for b in range(B):
+        n = int(seq_lens[b])
+        p_len = max(n - G, 0)
+        if p_len == 0:
+            continue
+        acc = np.zeros(p_len, dtype=np.float64)
+        for hk in range(Hkv):
+            K = gather_sequence(k_cache, block_table[b], p_len, hk)             # [p, D]
+            for j in range(g):
+                h = hk * g + j
+                logits = (qf[b, list(R), h, :] @ K.T) * scale                      # [|R|, p]
+                acc += logits.sum(axis=0)
+        scores[b, :p_len] = acc / (len(R) * Hq)
+    return scores
+
+
+def select_tokens_logical(scores_row: np.ndarray, n: int, num_queries: int, budget_tokens: int) -> np.ndarray:
+    """Selected token positions (ascending) of one sequence.
+
+    The last min(G, n) positions -- the tokens that are not part of the prefix -- are always kept
+    (Sec. 3.2, last sentence) and count towards the budget: k = min(budget, n), raised to the
+    number of kept tail tokens.  The other k - tail positions are the prefix tokens with the
+    highest scores; ties go to the lower position."""
+    if n <= 0:
+        return np.zeros(0, dtype=np.int64)
+    p_len = max(n - num_queries, 0)
+    tail = np.arange(p_len, n, dtype=np.int64)
+    k = min(max(int(budget_tokens), 0), n)
+    k = max(k, tail.size)
+    s = np.asarray(scores_row[:p_len])
+    order = np.argsort(-s, kind="stable")
+    chosen = order[:k - tail.size].astype(np.int64)
+    return np.sort(np.concatenate([chosen, tail]))
+
+
+def select_tokens(token_scores: np.ndarray, block_table: np.ndarray, seq_lens: np.ndarray,
+                  num_queries: int, budget_tokens: int, max_sel_tokens: int,
+                  budgets: Optional[Sequence[int]] = None):
+    """Top-k tokens per sequence -> (sel_table int32 [B, max_sel_tokens]: PHYSICAL token slots
+    block_table[i // 16] * 16 + i % 16 in ascending token order, i.e. page ids of the cache seen
+    with one-token pages (Sec. 4), -1 padded; sel_seq_lens int32 [B] = tokens selected; list of the
+    token positions per sequence)."""
+    B = block_table.shape[0]
+    sel_table = np.full((B, max_sel_tokens), -1, dtype=np.int32)
+    sel_seq_lens = np.zeros(B, dtype=np.int32)
+    logical = []
+    for b in range(B):
+        n = int(seq_lens[b])
+        bud = int(budgets[b]) if budgets is not None else int(budget_tokens)
+        ids = select_tokens_logical(token_scores[b], n, num_queries, bud)
+        if ids.size > max_sel_tokens:
+            raise ValueError("max_sel_tokens too small")
+        logical.append(ids)
+        if ids.size:
+            sel_table[b, :ids.size] = block_table[b, ids // PAGE].astype(np.int64) * PAGE + ids % PAGE
+            sel_seq_lens[b] = ids.size
     return sel_table, sel_seq_lens, logical
 
 

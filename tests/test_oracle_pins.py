@@ -433,3 +433,113 @@ def test_degenerate_lengths():
     sel, ssl, logical = O.select_blocks(scores, L.block_table, L.seq_lens, 4, 64, 4)
     assert ssl[0] == 0 and np.all(sel[0] == -1) and logical[0].size == 0
     assert ssl[1] == 2 and sel[1, 0] == L.block_table[1, 0]
+
+
+# ----------------------------------------------------------------------------------------------
+# the paper's own variant: logits as the metric, single tokens as the unit
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,G,collect", [(45, 3, 2), (33, 5, 1), (20, 1, 1), (64, 4, 2)])
+def test_token_logit_scores_against_scalar_loops_and_closed_form(n, G, collect):
+    Hq, Hkv, D = 4, 2, 8
+    g = Hq // Hkv
+    c = small_case(60 + n, n, G, Hq, Hkv, D, scale_q=2.0)
+    scores = O.token_logit_scores(c["q"], c["k_cache"], c["block_table"], c["seq_lens"], c["scale"], collect)
+    rows = list(range(G)) if collect == 1 else sorted({0, G - 1})
+    p_len = n - G
+    # scalar loops straight from Eq. 2 / Eq. 3: sum over rows, heads of q . k, then the averaging of Sec. 3.3
+    for i in range(p_len):
+        tot = math.fsum(float(c["Q"][0, t, h, d]) * float(c["Kd"][i, h // g, d])
+                        for t in rows for h in range(Hq) for d in range(D))
+        assert abs(scores[0, i] - c["scale"] * tot / (len(rows) * Hq)) < 1e-12
+    assert np.all(scores[0, p_len:] == 0.0)
+    # closed form: the score is linear in the query, so it is k_i . (mean collected query of the KV group)
+    qbar = c["Q"][0, rows].reshape(len(rows), Hkv, g, D).sum(axis=(0, 2))          # [Hkv, D]
+    lin = np.einsum("ihd,hd->i", c["Kd"][:p_len], qbar) * c["scale"] / (len(rows) * Hq)
+    np.testing.assert_allclose(scores[0, :p_len], lin, atol=1e-12)
+
+
+def test_single_head_logit_ranking_equals_weight_ranking():
+    """Softmax is monotone, so within one query head and one row logits and weights rank tokens alike (App. B)."""
+    n, G = 70, 1
+    c = small_case(71, n, G, 1, 1, 16, scale_q=2.0)
+    s = O.token_logit_scores(c["q"], c["k_cache"], c["block_table"], c["seq_lens"], c["scale"], 1)[0, :n - G]
+    K = O.gather_sequence(c["k_cache"], c["block_table"][0], n, 0)
+    w = O.attention_weights(c["Q"][0, :, 0, :], K, c["scale"], np.ones((1, n), dtype=bool))[0, :n - G]
+    assert np.array_equal(np.argsort(-s, kind="stable"), np.argsort(-w, kind="stable"))
+
+
+@pytest.mark.parametrize("n,G,budget", [(14, 2, 6), (12, 3, 5), (16, 1, 4)])
+def test_token_selection_is_the_exhaustive_argmax_of_eq3(n, G, budget):
+    Hq, Hkv, D = 2, 1, 8
+    c = small_case(80 + n, n, G, Hq, Hkv, D, scale_q=2.0)
+    scores = O.token_logit_scores(c["q"], c["k_cache"], c["block_table"], c["seq_lens"], c["scale"], 2)
+    rows = sorted({0, G - 1})
+    p_len = n - G
+    lsum = [math.fsum(float(c["Q"][0, t, h, d]) * float(c["Kd"][i, 0, d]) for t in rows for h in range(Hq) for d in range(D))
+            for i in range(p_len)]
+    kc = budget - G
+    best, best_set = -1e300, None
+    for T in itertools.combinations(range(p_len), kc):
+        val = math.fsum(lsum[i] for i in T)
+        if val > best:
+            best, best_set = val, T
+    ids = O.select_tokens_logical(scores[0], n, G, budget)
+    assert tuple(ids) == tuple(best_set) + tuple(range(p_len, n))
+
+
+def test_golden_token_selection_cases(golden_dir):
+    with open(os.path.join(golden_dir, "select_token_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    assert len(cases) >= 7
+    for c in cases:
+        n = c["seq_len"]
+        nblk = (n + PAGE - 1) // PAGE
+        scores = np.zeros((1, nblk * PAGE))
+        scores[0, :len(c["scores"])] = c["scores"]
+        table = (np.arange(nblk, dtype=np.int32)[::-1] * 3 + 7)[None, :].copy()
+        sel, ssl, logical = O.select_tokens(scores, table, np.array([n], dtype=np.int32), c["num_queries"],
+                                            c["budget"], max_sel_tokens=n + 2)
+        assert list(logical[0]) == c["positions"], c["name"]
+        k = len(c["positions"])
+        assert int(ssl[0]) == k, c["name"]
+        assert list(sel[0, :k]) == [int(table[0, i // PAGE]) * PAGE + i % PAGE for i in c["positions"]], c["name"]
+        assert np.all(sel[0, k:] == -1), c["name"]
+
+
+def test_token_selection_matches_numpy_partition_on_distinct_scores():
+    rng = np.random.default_rng(13)
+    for trial in range(20):
+        n = int(rng.integers(8, 3000))
+        G = int(rng.integers(1, 8))
+        budget = int(rng.integers(1, n + 50))
+        nblk = (n + PAGE - 1) // PAGE
+        scores = np.zeros((1, nblk * PAGE))
+        scores[0, :n] = rng.permutation(n) - n / 2.0                     # distinct, some negative
+        table = rng.permutation(nblk + 5)[:nblk].astype(np.int32)[None, :]
+        sel, ssl, logical = O.select_tokens(scores, table, np.array([n], dtype=np.int32), G, budget, n + 1)
+        ids = logical[0]
+        p_len = max(n - G, 0)
+        k = max(min(budget, n), n - p_len)
+        assert ids.size == k == int(ssl[0]) and np.all(np.diff(ids) > 0)
+        assert set(range(p_len, n)).issubset(ids)
+        kc = k - (n - p_len)
+        if 0 < kc < p_len:
+            thr = np.partition(scores[0, :p_len], p_len - kc)[p_len - kc]
+            assert set(ids[ids < p_len]) == set(np.nonzero(scores[0, :p_len] >= thr)[0])
+
+
+def test_draft_over_selected_tokens_equals_library_attention_over_them():
+    """End of the token-granular chain: the selected physical token slots are page ids of the one-token-page view."""
+    n, G, Hq, Hkv, D = 90, 3, 4, 2, 32
+    c = small_case(91, n, G, Hq, Hkv, D, scale_q=2.0)
+    scores = O.token_logit_scores(c["q"], c["k_cache"], c["block_table"], c["seq_lens"], c["scale"], 2)
+    sel, ssl, logical = O.select_tokens(scores, c["block_table"], c["seq_lens"], G, 20, 24)
+    qd = c["q"][:, G - 1]
+    out = O.draft_attention(qd, c["k_cache"].reshape(-1, 1, Hkv, D), c["v_cache"].reshape(-1, 1, Hkv, D), sel, ssl, c["scale"])
+    tok = logical[0]
+    q = torch.from_numpy(c["Q"][0, G - 1])[None, :, None, :]
+    k = torch.from_numpy(c["Kd"][tok]).permute(1, 0, 2)[None]
+    v = torch.from_numpy(c["Vd"][tok]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, enable_gqa=True)[0, :, 0].numpy()
+    np.testing.assert_allclose(out[0], ref, atol=1e-12)
