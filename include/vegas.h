@@ -55,6 +55,15 @@ enum {
   VEGAS_COLLECT_FIRST_LAST = 2  /* Eq. 3: first draft row and bonus row */
 };
 
+/* The criticality vegas_verify_attention collects (vegas_desc.score_metric). */
+enum {
+  VEGAS_METRIC_PAGE_WEIGHTS = 0, /* per 16-token page: summed softmax weights (App. B's weight variant);
+                                    block_scores is fp32 [B, max_blocks]; read by vegas_select_blocks */
+  VEGAS_METRIC_TOKEN_LOGITS = 1  /* per token: averaged attention logits (the paper's default metric, Sec. 3.2
+                                    footnote, Sec. 3.3 last paragraph); block_scores is fp32
+                                    [B, max_blocks * 16]; read by vegas_select_tokens */
+};
+
 /* Kernels of an attention call, for vegas_desc.launch_stages. */
 enum {
   VEGAS_STAGE_STREAM = 1,  /* the KV-streaming kernel (reads the cache, writes chunk partials) */
@@ -78,6 +87,7 @@ typedef struct vegas_desc {
   int32_t launch_stages;   /* profiling aid: 0 = whole call; else VEGAS_STAGE_* bits to launch only
                               those kernels of an attention call (outputs then incomplete) */
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
+  int32_t score_metric;    /* VEGAS_METRIC_*: what vegas_verify_attention writes to block_scores */
   int64_t num_pages;       /* pages in each cache (device-side clamp of page ids) */
   int64_t kv_page_stride;  /* elements between pages */
   int64_t kv_token_stride; /* elements between slots of a page */

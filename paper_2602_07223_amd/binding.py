@@ -25,6 +25,9 @@ COLLECT_NONE = 0
 COLLECT_ALL_ROWS = 1
 COLLECT_FIRST_LAST = 2
 
+METRIC_PAGE_WEIGHTS = 0
+METRIC_TOKEN_LOGITS = 1
+
 STAGE_STREAM = 1
 STAGE_MERGE = 2
 
@@ -48,6 +51,7 @@ class VegasDesc(ctypes.Structure):
         ("kv_chunk_tokens", ctypes.c_int32),
         ("launch_stages", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
+        ("score_metric", ctypes.c_int32),
         ("num_pages", ctypes.c_int64),
         ("kv_page_stride", ctypes.c_int64),
         ("kv_token_stride", ctypes.c_int64),
@@ -120,7 +124,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
               max_sel_blocks: int, max_seq_len: int, num_pages: int, softmax_scale: float,
               collect_rows: int = COLLECT_ALL_ROWS, head_dim: int = 128, page_size: int = 16,
               kv_chunk_tokens: int = 0, kv_page_stride: int = 0, kv_token_stride: int = 0,
-              kv_head_stride: int = 0) -> VegasDesc:
+              kv_head_stride: int = 0, score_metric: int = METRIC_PAGE_WEIGHTS) -> VegasDesc:
     """Descriptor for a contiguous NHD cache unless strides are given (elements)."""
     d = VegasDesc()
     d.batch, d.num_q_heads, d.num_kv_heads = batch, num_q_heads, num_kv_heads
@@ -128,6 +132,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
     d.max_blocks, d.max_sel_blocks, d.max_seq_len = max_blocks, max_sel_blocks, max_seq_len
     d.collect_rows, d.kv_chunk_tokens, d.softmax_scale = collect_rows, kv_chunk_tokens, softmax_scale
     d.launch_stages = 0
+    d.score_metric = score_metric
     d.num_pages = num_pages
     d.kv_head_stride = kv_head_stride or head_dim
     d.kv_token_stride = kv_token_stride or num_kv_heads * head_dim

@@ -135,7 +135,10 @@ __global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombinePa
 constexpr int kFinUnits = 6;     // (row, eighth of the chunks) units a score thread loads per batch
 constexpr int kFinPre = 8;       // page log-sum-exps a score thread keeps in registers: 4 * kFinPre rows
 
-template <int MAXS>
+// METRIC 1 (the paper's logit metric, token granularity) replaces the page-score role by workgroups
+// [nA, nA + nC) that add the H_kv per-head token sums of 1024 tokens each: score[b][i] = tok_norm *
+// sum_h partial[b][h][i] for prefix tokens i < n_b - G (Sec. 3.3, last paragraph), 0 elsewhere.
+template <int MAXS, int METRIC = 0>
 __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizeParams p) {
   extern __shared__ float smf[];              // role A (general path): [2][128] weights + [2][4]; role B: [Hkv*R] + [8][32] + [Hkv*R][8] pairs
   const int b = blockIdx.y;
@@ -204,6 +207,26 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
       const int t = r / p.g, j = r % p.g;
       p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + t128] = float_to_bf16_bits(o);
     }
+    return;
+  }
+
+  if constexpr (METRIC == 1) {
+    // ---- role C: 1024 tokens; thread = 4 consecutive tokens
+    const int i0 = (static_cast<int>(blockIdx.x) - p.nA) * 1024 + 4 * tid;
+    const int cap = p.max_blocks * kPage;
+    if (i0 >= cap) return;
+    int n = p.lens[b];
+    n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+    const int p_len = max(n - p.G, 0);
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    if (i0 < p_len) {
+      for (int h = 0; h < p.Hkv; ++h)
+        sum += *reinterpret_cast<const f32x4*>(p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + i0);
+    }
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (i0 + e < p_len) ? sum[e] * p.tok_norm : 0.f;
+    *reinterpret_cast<f32x4*>(p.block_scores + static_cast<int64_t>(b) * cap + i0) = o;
     return;
   }
 

@@ -60,13 +60,18 @@ constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffe
 // NT_LOADS: K/V are read with the non-temporal hint -- right for the verification pass that streams
 // the cache once with one reader per line; wrong for draft (the next draft step re-reads the same
 // pages) and for row-block siblings (the second reader wants the L2 hit).
+// COLLECT: 0 nothing; 1 the log-sum-exp of every (row, page) -- page criticality from softmax weights;
+// 2 the paper's own metric (Sec. 3.2 footnote, App. B): per-token sums of the collected rows' LOGITS.
+// A sum of logits is linear in the query, sum_r q_r . k = (sum_r q_r) . k, so the sum of the collected
+// query rows of this KV head rides along as two spare rows of the query tile (a bf16 high part and a
+// bf16 low part, together good to 2^-17) and the first MFMA delivers the token sums for free.
 // PS: log2 of the tokens per page of the table the kernel walks.  4 (16-token pages) is the path
 // described above; 0..3 (1, 2, 4, 8-token pages: Sec. 4 drafts with one-token pages, App. D sweeps
 // 1..16) is for draft calls only: a tile then spans 32 >> PS pages, every lane looks up the page of
 // its own token, and the page ids travel one tile ahead through a small per-wave LDS ring.
-template <int NW, int WPS, bool CAUSAL, bool COLLECT, bool NT_LOADS, int PS = 4>
+template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
-  static_assert(PS == 4 || (!CAUSAL && !COLLECT && !NT_LOADS), "small pages: draft calls only");
+  static_assert(PS == 4 || (!CAUSAL && COLLECT == 0 && !NT_LOADS), "small pages: draft calls only");
   // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NB = 1;                      // one 32-row block per workgroup
@@ -77,6 +82,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   // [pages of the chunk][Rl] page log-sum-exp (COLLECT only): behind the K tiles; the merge buffer may
   // overlap it because it is flushed (and a barrier passed) before the merge starts.
   float* lse_lds = reinterpret_cast<float*>(smem + NW * 32 * kRowPitch);
+  float* tok_lds = lse_lds;                  // COLLECT == 2: [2][chunk tokens] high-part and low-part token sums
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -209,6 +215,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   }
 
   // ---- query rows -> LDS [row][16 chunks of 16 B], padded rows; rows past R are zero
+  // COLLECT == 2: the last row block carries the sum of the collected query rows in rows Rl (high part) and Rl + 1 (low part)
+  const bool has_extra = COLLECT == 2 && rb == p.row_blocks - 1;
   for (int idx = tid; idx < NB * 32 * 16; idx += NW * 64) {
     const int row = idx >> 4, chunk = idx & 15;
     u32x4 raw = {0u, 0u, 0u, 0u};
@@ -217,6 +225,34 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       raw = *reinterpret_cast<const u32x4*>(
           p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + chunk * 8);
     }
+    if (has_extra && row == Rl) {
+      float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < p.G; ++t) {
+        if (p.collect_rows != 1 && t != 0 && t != p.G - 1) continue;       // Eq. 3: first draft row and bonus row
+        for (int j = 0; j < p.g; ++j) {
+          const u32x4 qv = *reinterpret_cast<const u32x4*>(
+              p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + chunk * 8);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] & 0xFFFFu));
+            sum[2 * e + 1] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] >> 16));
+          }
+        }
+      }
+      u32x4 hi, lo;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint16_t h0 = float_to_bf16_bits(sum[2 * e]), h1 = float_to_bf16_bits(sum[2 * e + 1]);
+        const uint16_t l0 = float_to_bf16_bits(sum[2 * e] - bf16_bits_to_float(h0));
+        const uint16_t l1 = float_to_bf16_bits(sum[2 * e + 1] - bf16_bits_to_float(h1));
+        hi[e] = static_cast<uint32_t>(h0) | (static_cast<uint32_t>(h1) << 16);
+        lo[e] = static_cast<uint32_t>(l0) | (static_cast<uint32_t>(l1) << 16);
+      }
+      *reinterpret_cast<u32x4*>(qlds + Rl * kRowPitch + chunk * 16) = hi;
+      *reinterpret_cast<u32x4*>(qlds + (Rl + 1) * kRowPitch + chunk * 16) = lo;
+      continue;
+    }
+    if (has_extra && row == Rl + 1) continue;                                // written together with row Rl
     *reinterpret_cast<u32x4*>(qlds + row * kRowPitch + chunk * 16) = raw;
   }
   int limit[NB];                             // last visible token of this lane's row
@@ -281,6 +317,18 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     }
     wave_lds_fence();
 
+    if constexpr (COLLECT == 2) {
+      // Columns Rl and Rl + 1 of S^T hold k_i . (high part) and k_i . (low part) for the tile's 32 tokens:
+      // those two lanes (of each half) park them; register i covers token 8(i/4) + 4 half + i%4.
+      if (has_extra && (l32 == Rl || l32 == Rl + 1)) {
+        float* dst = tok_lds + (l32 - Rl) * p.chunk_tokens + (tok0 - c0) + 4 * half;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+          *reinterpret_cast<f32x4*>(dst + 8 * i4) =
+              f32x4{st[0][4 * i4], st[0][4 * i4 + 1], st[0][4 * i4 + 2], st[0][4 * i4 + 3]};
+      }
+    }
+
     const bool tail = (tok0 + kTile > n) || (CAUSAL && (tok0 + kTile - 1 > n - p.G));
     bf16x8 pb[NB][2];
 #pragma unroll
@@ -307,7 +355,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       for (int i = 0; i < 8; ++i) { ps0 += pr[i]; ps1 += pr[8 + i]; }
       l_run[nb] = l_run[nb] * alpha + (ps0 + ps1);
       m_run[nb] = m_new;
-      if (COLLECT) {
+      if (COLLECT == 1) {
         const float f0 = half_sum(ps0);
         const float f1 = half_sum(ps1);
         const int page = cur * 2 + half;                 // parked in LDS, written out in bulk at the end
@@ -382,7 +430,16 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     for (int nb = 0; nb < NB; ++nb) sm_m[wave * (NB * 32) + nb * 32 + l32] = m_run[nb];
   }
   __syncthreads();                                       // also: every wave is done with its K tile
-  if (COLLECT) {
+  if constexpr (COLLECT == 2) {
+    // The chunk's token sums (high + low part) leave in one coalesced write; positions at or past the
+    // end of the sequence are never read.
+    if (has_extra) {
+      float* dst = p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0;
+      for (int e = tid; e < c1 - c0; e += NW * 64) dst[e] = tok_lds[e] + tok_lds[p.chunk_tokens + e];
+    }
+    __syncthreads();
+  }
+  if (COLLECT == 1) {
     // One contiguous, coalesced write of the chunk's page log-sum-exps (a store per tile inside the
     // streaming loop costs ~14 % of the kernel: small scattered writes disturb the read stream).
     const int pg0 = c0 / kPage;
@@ -442,11 +499,13 @@ inline size_t split_lds_tail_bytes(int NW) {
   return static_cast<size_t>(32) * kRowPitch + 2 * static_cast<size_t>(NW) * 32 * sizeof(float) +
          static_cast<size_t>(NW) * 64 * sizeof(int);                 // queries, row maxima and sums, page-id ring
 }
-// lse_tokens > 0: page scores are collected and the chunk's page log-sum-exps (chunk_pages x rows floats)
-// sit right behind the K tiles.
-inline size_t split_lds_bytes(int NW, int rows, int lse_tokens = 0) {
-  size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch +
-                 static_cast<size_t>(lse_tokens / kPage) * rows * sizeof(float);
+// collect 1: the chunk's page log-sum-exps (chunk pages x rows floats) sit right behind the K tiles;
+// collect 2: the chunk's token sums, high and low part (2 x chunk tokens floats).
+inline size_t split_lds_bytes(int NW, int rows, int collect = 0, int chunk_tokens = 0) {
+  size_t park = 0;
+  if (collect == 1) park = static_cast<size_t>(chunk_tokens / kPage) * rows * sizeof(float);
+  if (collect == 2) park = 2 * static_cast<size_t>(chunk_tokens) * sizeof(float);
+  size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch + park;
   const size_t red = static_cast<size_t>(NW) * rows * kRedPitch * sizeof(float);
   if (red > stage) stage = red;
   stage = (stage + 15) / 16 * 16;

@@ -56,7 +56,8 @@ int check_paged16(const vegas_desc* d) {
 
 // Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
 // max_len bounds the lengths the call may see; small problems get small workgroups.
-int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_lse, int wg_per_cu, SplitPlan* pl) {
+// collect: 0 nothing, 1 page log-sum-exps [pages x rows], 2 token sums [padded tokens] per (sequence, KV head)
+int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect, int wg_per_cu, SplitPlan* pl) {
   pl->R = rows_per_head;
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
   if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
@@ -79,12 +80,13 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, bool with_ls
   }
   pl->chunk = chunk;
   pl->nsplit = (max_len + chunk - 1) / chunk;
-  pl->lse_pages = with_lse ? (max_len + kPage - 1) / kPage : 0;
+  pl->lse_pages = collect == 1 ? (max_len + kPage - 1) / kPage : (collect == 2 ? pl->nsplit * chunk : 0);
   size_t off = 0;
   const size_t hs = static_cast<size_t>(heads);
   pl->off_part_o = off;  off += align_up(hs * pl->nsplit * pl->R * kHeadDim * sizeof(float));
   pl->off_part_ml = off; off += align_up(hs * pl->nsplit * pl->R * sizeof(float2));
-  pl->off_page_lse = off; off += align_up(hs * static_cast<size_t>(pl->lse_pages) * pl->R * sizeof(float));
+  pl->off_page_lse = off;
+  off += align_up(hs * static_cast<size_t>(pl->lse_pages) * (collect == 2 ? 1 : pl->R) * sizeof(float));
   pl->total = off;
   return VEGAS_OK;
 }
@@ -93,12 +95,18 @@ int plan_verify(const vegas_desc* d, SplitPlan* pl) {
   if (d->num_queries <= 0) return VEGAS_ERR_SHAPE;
   if (d->collect_rows < 0 || d->collect_rows > 2) return VEGAS_ERR_SHAPE;
   const int g = d->num_q_heads / d->num_kv_heads;
-  return plan_split(d, d->num_queries * g, d->max_seq_len, d->collect_rows != 0, 1, pl);
+  if (d->score_metric != VEGAS_METRIC_PAGE_WEIGHTS && d->score_metric != VEGAS_METRIC_TOKEN_LOGITS)
+    return VEGAS_ERR_SHAPE;
+  const int R = d->num_queries * g;
+  const int collect = d->collect_rows == 0 ? 0 : (d->score_metric == VEGAS_METRIC_TOKEN_LOGITS ? 2 : 1);
+  // the logit metric needs two spare rows in the last 32-row block of a KV head
+  if (collect == 2 && (R % 32 == 0 || R % 32 > 30)) return VEGAS_ERR_UNSUPPORTED;
+  return plan_split(d, R, d->max_seq_len, collect, 1, pl);
 }
 
 int plan_draft(const vegas_desc* d, SplitPlan* pl) {
   const int g = d->num_q_heads / d->num_kv_heads;
-  return plan_split(d, g, d->max_seq_len, false, 2, pl);
+  return plan_split(d, g, d->max_seq_len, 0, 2, pl);
 }
 
 // A kernel whose static + dynamic LDS passes the default 64 KB limit needs its limit raised first: once
@@ -129,15 +137,15 @@ int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, con
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
-template <bool CAUSAL, bool COLLECT>
+template <bool CAUSAL, int COLLECT>
 int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size = kPage) {
   const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
   const int rows = pl.R < 32 ? pl.R : 32;
-  const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT ? pl.chunk : 0);
+  const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT, pl.chunk);
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW));
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
-  if constexpr (!CAUSAL && !COLLECT) {              // draft calls may walk a table of smaller pages
+  if constexpr (!CAUSAL && COLLECT == 0) {              // draft calls may walk a table of smaller pages
     switch (page_size) {
       case 1: return launch_one(attn_split_kernel<4, 2, false, false, false, 0>, grid, dim3(256), lds, st, sp);
       case 2: return launch_one(attn_split_kernel<4, 2, false, false, false, 1>, grid, dim3(256), lds, st, sp);
@@ -172,6 +180,7 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->chunk_tokens = pl.chunk;
   sp->nsplit = pl.nsplit;
   sp->lse_pages = pl.lse_pages;
+  sp->collect_rows = d->collect_rows;
   sp->max_tokens = d->max_seq_len;
   sp->page_stride = d->kv_page_stride;
   sp->token_stride = d->kv_token_stride;
@@ -237,6 +246,7 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   rc = plan_verify(desc, &pl);
   if (rc != VEGAS_OK) return rc;
   const bool collect = desc->collect_rows != VEGAS_COLLECT_NONE;
+  const bool logits = collect && desc->score_metric == VEGAS_METRIC_TOKEN_LOGITS;
   if (collect && !block_scores) return VEGAS_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(block_table) ||
       (block_scores && !aligned16(block_scores)))
@@ -252,7 +262,8 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   const bool do_merge = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_MERGE);
   if (do_stream) {
     if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-    rc = collect ? launch_split<true, true>(pl, sp, desc->batch, st) : launch_split<true, false>(pl, sp, desc->batch, st);
+    rc = !collect ? launch_split<true, 0>(pl, sp, desc->batch, st)
+                  : (logits ? launch_split<true, 2>(pl, sp, desc->batch, st) : launch_split<true, 1>(pl, sp, desc->batch, st));
     if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }
@@ -280,8 +291,16 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   int page_groups = 1;
   (void)table_bytes;   // measured: larger page groups lose more to serialisation than the table re-reads cost
   fp.page_groups = page_groups;
-  const int nB = (groups32 + page_groups - 1) / page_groups;
-  const size_t shm = (hr + 256 + 16 * hr) * sizeof(float);   // role B needs the most; role A fits inside
+  int nB = (groups32 + page_groups - 1) / page_groups;
+  size_t shm = (hr + 256 + 16 * hr) * sizeof(float);   // role B needs the most; role A fits inside
+  fp.nC = 0;
+  fp.tok_norm = 0.f;
+  if (logits) {                                        // token sums instead of page scores: 1024 tokens per workgroup
+    fp.nC = static_cast<int>((static_cast<int64_t>(desc->max_blocks) * kPage + 1023) / 1024);
+    fp.tok_norm = desc->softmax_scale / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
+    nB = fp.nC;
+    shm = 264 * sizeof(float);
+  }
   if (shm > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
   const dim3 fgrid(fp.nA + nB, desc->batch);
   auto launch_finalize = [&](auto kern) -> int {
@@ -289,9 +308,15 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
     hipLaunchKernelGGL(kern, fgrid, dim3(256), shm, st, fp);
     return VEGAS_OK;
   };
-  if (pl.nsplit <= 16) rc = launch_finalize(verify_finalize_kernel<16>);
-  else if (pl.nsplit <= 32) rc = launch_finalize(verify_finalize_kernel<32>);
-  else rc = launch_finalize(verify_finalize_kernel<0>);
+  if (logits) {
+    if (pl.nsplit <= 16) rc = launch_finalize(verify_finalize_kernel<16, 1>);
+    else if (pl.nsplit <= 32) rc = launch_finalize(verify_finalize_kernel<32, 1>);
+    else rc = launch_finalize(verify_finalize_kernel<0, 1>);
+  } else {
+    if (pl.nsplit <= 16) rc = launch_finalize(verify_finalize_kernel<16>);
+    else if (pl.nsplit <= 32) rc = launch_finalize(verify_finalize_kernel<32>);
+    else rc = launch_finalize(verify_finalize_kernel<0>);
+  }
   if (rc != VEGAS_OK) return rc;
   if (hipGetLastError() != hipSuccess) return VEGAS_ERR_LAUNCH;
   return VEGAS_OK;
@@ -360,7 +385,7 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
   fill_split_params(desc, pl, 1, q, k_cache, v_cache, sel_table, desc->max_sel_blocks, sel_seq_lens, ws, &sp);
   if (desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM)) {
     if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-    rc = launch_split<false, false>(pl, sp, desc->batch, st, desc->page_size);
+    rc = launch_split<false, 0>(pl, sp, desc->batch, st, desc->page_size);
     if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }

@@ -70,12 +70,14 @@ struct SplitParams {
   const int32_t* lens;      // [B] valid tokens
   float* part_o;            // [B, Hkv, nsplit, R, D] un-normalised partial outputs
   float2* part_ml;          // [B, Hkv, nsplit, R]    (running max in log2 units, partial sum)
-  float* page_lse;          // [B, Hkv, lse_pages, R] log2-sum-exp2 of each page's scaled logits
+  float* page_lse;          // [B, Hkv, lse_pages, R] log2-sum-exp2 of each page's scaled logits; or, for the
+                            // logit metric, [B, Hkv, lse_pages] per-token sums of the collected rows' q . k
   int32_t table_stride;
   int32_t G, g, R, Hq, Hkv;
   int32_t chunk_tokens, nsplit, lse_pages, max_tokens;
   int32_t lds_q_off;        // byte offset of the query tile inside dynamic LDS
   int32_t row_blocks;       // ceil(R / 32): 32-row blocks of one KV head, one workgroup each
+  int32_t collect_rows;     // which verification rows are collected (1: all, 2: first and last)
   int64_t page_stride, token_stride, head_stride, num_pages;
   float scale_log2e;
 };
@@ -97,6 +99,8 @@ struct FinalizeParams {
   float* block_scores;      // [B, max_blocks]
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t max_blocks, lse_pages, collect_rows;
+  int32_t nC;               // logit metric: workgroups that sum the token partials (1024 tokens each)
+  float tok_norm;           // logit metric: softmax_scale / (collected rows * H_q)
   int32_t nA;               // workgroups that merge rows (two rows each); the rest score pages
   int32_t page_groups;      // 32-page groups scored by one workgroup (more when its row table is big)
   float inv_norm;

@@ -50,7 +50,8 @@ class VegasPath:
     def __init__(self, *, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: int, max_blocks: int,
                  max_seq_len: int, num_pages: int, budget_tokens: int, softmax_scale: float,
                  collect_rows: int = vb.COLLECT_ALL_ROWS, head_dim: int = 128, device="cuda:0",
-                 verify_chunk: int = 0, draft_chunk: int = 0, max_sel_blocks: int = 0):
+                 verify_chunk: int = 0, draft_chunk: int = 0, max_sel_blocks: int = 0,
+                 score_metric: int = vb.METRIC_PAGE_WEIGHTS):
         self.device = torch.device(device)
         self.B, self.Hq, self.Hkv, self.G, self.D = batch, num_q_heads, num_kv_heads, num_queries, head_dim
         self.budget_tokens = budget_tokens
@@ -61,7 +62,7 @@ class VegasPath:
                       max_blocks=max_blocks, max_sel_blocks=self.max_sel_blocks, num_pages=num_pages,
                       softmax_scale=softmax_scale, head_dim=head_dim)
         self.desc_verify = vb.make_desc(max_seq_len=max_seq_len, collect_rows=collect_rows,
-                                        kv_chunk_tokens=verify_chunk, **common)
+                                        kv_chunk_tokens=verify_chunk, score_metric=score_metric, **common)
         draft_len = min(self.max_sel_blocks * PAGE, max_blocks * PAGE)
         self.desc_draft = vb.make_desc(max_seq_len=draft_len, collect_rows=vb.COLLECT_NONE,
                                        kv_chunk_tokens=draft_chunk, **common)
@@ -71,7 +72,8 @@ class VegasPath:
         dev = self.device
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         self.out_verify = torch.empty((batch, num_queries, num_q_heads, head_dim), dtype=torch.bfloat16, device=dev)
-        self.block_scores = torch.empty((batch, max_blocks), dtype=torch.float32, device=dev)
+        per_page = PAGE if score_metric == vb.METRIC_TOKEN_LOGITS else 1       # token scores: one per token slot
+        self.block_scores = torch.empty((batch, max_blocks * per_page), dtype=torch.float32, device=dev)
         self.sel_table = torch.empty((batch, self.max_sel_blocks), dtype=torch.int32, device=dev)
         self.sel_seq_lens = torch.empty((batch,), dtype=torch.int32, device=dev)
         self.out_draft = torch.empty((num_queries, batch, num_q_heads, head_dim), dtype=torch.bfloat16, device=dev)
