@@ -141,6 +141,34 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Selection of single tokens from averaged logits: the paper's own granularity and metric
+ * (Sec. 3.3 Eq. 3 and its last paragraph; Sec. 4).  For each sequence b with n_b = seq_lens[b]:
+ * the last min(G, n_b) tokens (those after the prefix) are always kept and count towards the
+ * budget; k_b = min(budget_b, n_b), raised to the number of kept tail tokens; the other k_b - tail
+ * tokens are the prefix tokens (positions < n_b - G) with the highest scores, ties to the lower
+ * position.
+ *   token_scores fp32 [B, max_blocks*16]    as written by vegas_verify_attention with
+ *                                           score_metric = VEGAS_METRIC_TOKEN_LOGITS (only positions
+ *                                           below n_b - G are read)
+ *   block_table  int32 [B, max_blocks]      16-token pages, as for verification
+ *   budget_tokens / budgets                 as for vegas_select_blocks (tokens)
+ *   sel_table    int32 [B, max_sel_blocks]  PHYSICAL token slots block_table[i/16]*16 + i%16 in
+ *                                           ascending token order, then -1: the page list of
+ *                                           vegas_draft_attention with page_size = 1
+ *   sel_seq_lens int32 [B]                  k_b
+ * desc->page_size is 16 here (it describes block_table); desc->max_sel_blocks counts tokens.
+ * Integer work: for identical fp32 scores the result is defined bit for bit.  Seven short kernels
+ * (histogram passes meet in global memory); workspace from vegas_workspace_bytes.
+ * Returns VEGAS_ERR_SHAPE if max_sel_blocks < max(min(budget_tokens, max_seq_len), min(G, max_seq_len))
+ * (checked when budgets == NULL; per-sequence budgets are clamped on the device).
+ */
+int vegas_select_tokens(const vegas_desc* desc, const float* token_scores,
+                        const int32_t* block_table, const int32_t* seq_lens,
+                        int32_t budget_tokens, const int32_t* budgets,
+                        int32_t* sel_table, int32_t* sel_seq_lens,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Sparse draft attention (Sec. 2.2 last paragraph; Sec. 4: the selection is the page list).
  *   q            bf16 [B, H_q, D]           one draft token per sequence
  *   sel_table    int32 [B, max_sel_blocks]  as written by vegas_select_blocks

@@ -31,7 +31,7 @@ METRIC_TOKEN_LOGITS = 1
 STAGE_STREAM = 1
 STAGE_MERGE = 2
 
-EXPORTS = ("vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
+EXPORTS = ("vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks", "vegas_select_tokens",
            "vegas_draft_attention", "vegas_strerror")
 
 
@@ -88,6 +88,8 @@ def load_library(path: Optional[str] = None):
     lib.vegas_verify_attention.argtypes = [D, P, P, P, P, P, P, P, P, ctypes.c_size_t, P]
     lib.vegas_select_blocks.restype = ctypes.c_int
     lib.vegas_select_blocks.argtypes = [D, P, P, P, ctypes.c_int32, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_select_tokens.restype = ctypes.c_int
+    lib.vegas_select_tokens.argtypes = [D, P, P, P, ctypes.c_int32, P, P, P, P, ctypes.c_size_t, P]
     lib.vegas_draft_attention.restype = ctypes.c_int
     lib.vegas_draft_attention.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P]
     lib.vegas_strerror.restype = ctypes.c_char_p
@@ -164,6 +166,16 @@ def vegas_select_blocks(desc: VegasDesc, block_scores, block_table, seq_lens, bu
                                             _ptr(sel_seq_lens), _ptr(workspace), wb, _stream(stream))
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_select_blocks")
+
+
+def vegas_select_tokens(desc: VegasDesc, token_scores, block_table, seq_lens, budget_tokens: int, sel_table,
+                        sel_seq_lens, workspace, budgets=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
+    rc = load_library().vegas_select_tokens(ctypes.byref(desc), _ptr(token_scores), _ptr(block_table),
+                                            _ptr(seq_lens), int(budget_tokens), _ptr(budgets), _ptr(sel_table),
+                                            _ptr(sel_seq_lens), _ptr(workspace), wb, _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_select_tokens")
 
 
 def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace,

@@ -1,0 +1,289 @@
+// Top-k selection over single tokens (the paper's own granularity: Sec. 3.3 last paragraph, Sec. 4).
+//
+// A sequence has up to a few hundred thousand prefix tokens, too many for one workgroup, so the
+// radix select of the page version is spread over workgroups that own 4096-token slices and meet in
+// global histograms between launches:
+//   token_select_zero      clears the digit histograms
+//   token_select_hist x 4  pass q: every workgroup re-derives the key prefix fixed by passes < q from
+//                          their (complete) histograms, counts digit q of its slice's matching keys
+//                          in LDS and adds its 256 counts to the global histogram of pass q
+//   token_select_count     with the k-th key T known: keys > T and keys == T per slice
+//   token_select_write     exclusive prefix over the slices' counts, then an order-preserving
+//                          compaction of the slice; physical slot = table[i / 16] * 16 + i % 16
+// The last min(G, n) tokens are not part of the prefix and are always kept (Sec. 3.2, last sentence).
+// Integer work on the score bits: defined bit for bit, ties go to the lower position.
+#pragma once
+#include "select_blocks.hpp"
+#include "vegas_common.hpp"
+
+namespace vegas {
+
+constexpr int kTokSlice = 4096;       // prefix tokens per workgroup
+constexpr int kTokThreads = 1024;
+
+struct TokenSelectParams {
+  const float* scores;        // [B, max_blocks * 16]
+  const int32_t* block_table; // [B, max_blocks]
+  const int32_t* seq_lens;
+  const int32_t* budgets;     // or nullptr
+  int32_t* sel_table;         // [B, max_sel] physical token slots
+  int32_t* sel_seq_lens;
+  uint32_t* hist;             // [B, 4, 256]
+  uint32_t* counts;           // [B, slices, 2] (keys > T, keys == T) of every slice
+  int32_t budget_tokens, G, max_blocks, max_sel, max_tokens, slices;
+};
+
+// What one sequence asks for.
+struct TokenPlan {
+  int n, p_len, tail, k, kc;
+  bool need_search, take_all;
+};
+
+__device__ __forceinline__ TokenPlan token_plan(const TokenSelectParams& p, int b) {
+  TokenPlan t;
+  int n = p.seq_lens[b];
+  t.n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
+  t.p_len = max(t.n - p.G, 0);
+  t.tail = t.n - t.p_len;
+  int budget = p.budgets ? p.budgets[b] : p.budget_tokens;
+  budget = budget < 0 ? 0 : budget;
+  int k = min(budget, t.n);
+  k = max(k, t.tail);
+  t.k = min(k, p.max_sel);                           // device-side clamp; the host rejects this case
+  t.kc = max(t.k - t.tail, 0);
+  t.need_search = t.kc > 0 && t.kc < t.p_len;
+  t.take_all = t.kc >= t.p_len;
+  return t;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS).
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
+  int v = static_cast<int>(x);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return static_cast<uint32_t>(v);
+}
+
+// Executed by ONE full wave: walks the finished histograms of passes 0 .. passes-1 of sequence b and
+// returns, in every lane, the key prefix they fix and how many keys are still wanted inside it.
+__device__ __forceinline__ void token_prefix(const TokenSelectParams& p, int b, int passes, uint32_t kc,
+                                             uint32_t* prefix_out, uint32_t* need_out) {
+  const int lane = threadIdx.x & 63;
+  uint32_t prefix = 0u, need = kc;
+  for (int q = 0; q < passes; ++q) {
+    const int shift = 24 - 8 * q;
+    const uint32_t* h = p.hist + (static_cast<int64_t>(b) * 4 + q) * 256;
+    // lane l owns bins 255-4l .. 252-4l, so an inclusive prefix sum over lanes counts from the top bin down
+    uint32_t c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c[i] = h[255 - 4 * lane - i];
+    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+    uint32_t above = wave_prefix_sum(mine) - mine;
+    uint32_t found = 0u, digit = 0u, rest = 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (above < need && need <= above + c[i]) {
+        found = 1u;
+        digit = static_cast<uint32_t>(255 - 4 * lane - i);
+        rest = need - above;
+      }
+      above += c[i];
+    }
+    const uint64_t who = __builtin_amdgcn_ballot_w64(found != 0u);   // exactly one lane when need <= matching keys
+    const int src = who ? __builtin_ctzll(who) : 0;
+    digit = __builtin_amdgcn_readlane(digit, src);
+    rest = __builtin_amdgcn_readlane(rest, src);
+    prefix |= digit << shift;
+    need = rest;
+  }
+  *prefix_out = prefix;
+  *need_out = need;
+}
+
+__global__ __launch_bounds__(256) void token_select_zero(const TokenSelectParams p, int total) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) p.hist[i] = 0u;
+}
+
+__global__ __launch_bounds__(kTokThreads) void token_select_hist(const TokenSelectParams p, int pass) {
+  __shared__ uint32_t hist[kTokThreads / 64][256];
+  __shared__ uint32_t sh_prefix;
+  const int b = blockIdx.y, s = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const TokenPlan t = token_plan(p, b);
+  const int base = s * kTokSlice;
+  if (!t.need_search || base >= t.p_len) return;
+  if (wave == 0) {
+    uint32_t prefix, need;
+    token_prefix(p, b, pass, static_cast<uint32_t>(t.kc), &prefix, &need);
+    if (lane == 0) sh_prefix = prefix;
+  }
+  uint32_t* h = hist[wave];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) h[lane + 64 * i] = 0u;
+  __syncthreads();
+  const uint32_t prefix = sh_prefix;
+  const uint32_t mask = pass == 0 ? 0u : (0xFFFFFFFFu << (32 - 8 * pass));
+  const int shift = 24 - 8 * pass;
+  const float* scores = p.scores + static_cast<int64_t>(b) * p.max_blocks * kPage;
+#pragma unroll
+  for (int it = 0; it < kTokSlice / kTokThreads; ++it) {
+    const int j = base + it * kTokThreads + tid;
+    uint32_t key = 0u;
+    bool act = false;
+    if (j < t.p_len) {
+      key = score_key(scores[j]);
+      act = (key & mask) == prefix;
+    }
+    const uint32_t d = (key >> shift) & 255u;
+    // lanes that share the leader's digit are counted by one atomic; what is left after two rounds adds itself
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+      const uint64_t am = __builtin_amdgcn_ballot_w64(act);
+      const int leader = am ? __builtin_ctzll(am) : 0;
+      const uint32_t dl = __builtin_amdgcn_readlane(d, leader);
+      const bool hit = act && d == dl;
+      const uint64_t same = __builtin_amdgcn_ballot_w64(hit);
+      if (hit && lane == leader) atomicAdd(&h[dl], static_cast<uint32_t>(__popcll(same)));
+      act = act && !hit;
+    }
+    if (act) atomicAdd(&h[d], 1u);
+  }
+  __syncthreads();
+  if (tid < 256) {
+    uint32_t c = 0u;
+#pragma unroll
+    for (int w = 0; w < kTokThreads / 64; ++w) c += hist[w][tid];
+    if (c) atomicAdd(p.hist + (static_cast<int64_t>(b) * 4 + pass) * 256 + tid, c);
+  }
+}
+
+__global__ __launch_bounds__(kTokThreads) void token_select_count(const TokenSelectParams p) {
+  __shared__ uint32_t sh_T;
+  __shared__ uint32_t wgt[kTokThreads / 64], weq[kTokThreads / 64];
+  const int b = blockIdx.y, s = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const TokenPlan t = token_plan(p, b);
+  const int base = s * kTokSlice;
+  if (!t.need_search || base >= t.p_len) return;
+  if (wave == 0) {
+    uint32_t T, need_eq;
+    token_prefix(p, b, 4, static_cast<uint32_t>(t.kc), &T, &need_eq);
+    if (lane == 0) sh_T = T;
+  }
+  __syncthreads();
+  const uint32_t T = sh_T;
+  const float* scores = p.scores + static_cast<int64_t>(b) * p.max_blocks * kPage;
+  uint32_t gt = 0u, eq = 0u;
+#pragma unroll
+  for (int it = 0; it < kTokSlice / kTokThreads; ++it) {
+    const int j = base + it * kTokThreads + tid;
+    bool g = false, e = false;
+    if (j < t.p_len) {
+      const uint32_t key = score_key(scores[j]);
+      g = key > T;
+      e = key == T;
+    }
+    gt += __popcll(__builtin_amdgcn_ballot_w64(g));
+    eq += __popcll(__builtin_amdgcn_ballot_w64(e));
+  }
+  if (lane == 0) { wgt[wave] = gt; weq[wave] = eq; }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t G = 0u, E = 0u;
+    for (int w = 0; w < kTokThreads / 64; ++w) { G += wgt[w]; E += weq[w]; }
+    uint32_t* c = p.counts + (static_cast<int64_t>(b) * p.slices + s) * 2;
+    c[0] = G;
+    c[1] = E;
+  }
+}
+
+__global__ __launch_bounds__(kTokThreads) void token_select_write(const TokenSelectParams p) {
+  __shared__ uint32_t sh_T, sh_need_eq, sh_eq_before, sh_pos_before;
+  __shared__ uint32_t wave_take[kTokThreads / 64], wave_eq[kTokThreads / 64];
+  const int b = blockIdx.y, s = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const TokenPlan t = token_plan(p, b);
+  int32_t* sel = p.sel_table + static_cast<int64_t>(b) * p.max_sel;
+  const int32_t* table = p.block_table + static_cast<int64_t>(b) * p.max_blocks;
+  const float* scores = p.scores + static_cast<int64_t>(b) * p.max_blocks * kPage;
+  auto slot_of = [&](int i) -> int32_t { return table[i >> 4] * kPage + (i & 15); };
+
+  // ---- the kept tail, the padding and the length: spread over the sequence's workgroups
+  const int stride = gridDim.x * kTokThreads;
+  for (int i = s * kTokThreads + tid; i < t.tail; i += stride)
+    if (t.kc + i < p.max_sel) sel[t.kc + i] = slot_of(t.p_len + i);
+  for (int i = t.k + s * kTokThreads + tid; i < p.max_sel; i += stride) sel[i] = -1;
+  if (s == 0 && tid == 0) p.sel_seq_lens[b] = t.k;
+
+  const int base = s * kTokSlice;
+  if (t.kc == 0 || base >= t.p_len) return;
+  if (wave == 0 && t.need_search) {
+    uint32_t T, need_eq;
+    token_prefix(p, b, 4, static_cast<uint32_t>(t.kc), &T, &need_eq);
+    // exclusive prefix over the slices before this one: ties seen, and tokens taken
+    uint32_t eq_before = 0u, pos_before = 0u;
+    const uint32_t* c = p.counts + static_cast<int64_t>(b) * p.slices * 2;
+    for (int q = 0; q < s; ++q) {
+      const uint32_t g = c[2 * q], e = c[2 * q + 1];
+      const uint32_t room = need_eq > eq_before ? need_eq - eq_before : 0u;
+      pos_before += g + min(e, room);
+      eq_before += e;
+    }
+    if (lane == 0) { sh_T = T; sh_need_eq = need_eq; sh_eq_before = eq_before; sh_pos_before = pos_before; }
+  }
+  __syncthreads();
+  const bool all = t.take_all;
+  const uint32_t T = all ? 0u : sh_T, need_eq = all ? 0u : sh_need_eq;
+  const uint32_t slice_eq_before = all ? 0u : sh_eq_before;
+  const uint32_t slice_pos_before = all ? static_cast<uint32_t>(base) : sh_pos_before;
+
+  // ---- ordered compaction: wave w owns tokens [base + 256 w, base + 256 (w + 1)), 64 per step (lane = token)
+  constexpr int kSteps = kTokSlice / kTokThreads;
+  const int w0 = base + wave * (64 * kSteps);
+  const uint64_t lt = (1ull << lane) - 1ull;
+  uint32_t key[kSteps];
+  bool valid[kSteps];
+#pragma unroll
+  for (int st = 0; st < kSteps; ++st) {
+    const int j = w0 + 64 * st + lane;
+    valid[st] = j < t.p_len;
+    key[st] = (valid[st] && !all) ? score_key(scores[j]) : 0u;
+  }
+  uint32_t eq_wave = 0u;
+#pragma unroll
+  for (int st = 0; st < kSteps; ++st) eq_wave += __popcll(__builtin_amdgcn_ballot_w64(valid[st] && !all && key[st] == T));
+  if (lane == 0) wave_eq[wave] = eq_wave;
+  __syncthreads();
+  uint32_t eq_before = slice_eq_before;
+  for (int w = 0; w < wave; ++w) eq_before += wave_eq[w];
+  uint32_t take_wave = 0u, eq_run = eq_before;
+  bool take[kSteps];
+#pragma unroll
+  for (int st = 0; st < kSteps; ++st) {
+    const bool eq = valid[st] && !all && key[st] == T;
+    const bool gt = valid[st] && !all && key[st] > T;
+    const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
+    take[st] = all ? valid[st] : (gt || (eq && eq_run + __popcll(beq & lt) < need_eq));
+    eq_run += __popcll(beq);
+    take_wave += __popcll(__builtin_amdgcn_ballot_w64(take[st]));
+  }
+  if (lane == 0) wave_take[wave] = take_wave;
+  __syncthreads();
+  uint32_t pos_run = slice_pos_before;
+  for (int w = 0; w < wave; ++w) pos_run += wave_take[w];
+#pragma unroll
+  for (int st = 0; st < kSteps; ++st) {
+    const uint64_t btk = __builtin_amdgcn_ballot_w64(take[st]);
+    if (take[st]) {
+      const uint32_t pos = pos_run + __popcll(btk & lt);
+      if (pos < static_cast<uint32_t>(p.max_sel)) sel[pos] = slot_of(w0 + 64 * st + lane);
+    }
+    pos_run += __popcll(btk);
+  }
+}
+
+}  // namespace vegas

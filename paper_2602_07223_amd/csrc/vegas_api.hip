@@ -11,6 +11,7 @@
 #include "attn_finalize.hpp"
 #include "attn_split.hpp"
 #include "select_blocks.hpp"
+#include "select_tokens.hpp"
 #include "vegas_common.hpp"
 
 namespace {
@@ -189,6 +190,15 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->scale_log2e = d->softmax_scale * 1.4426950408889634f;
 }
 
+// Scratch of vegas_select_tokens: digit histograms [B, 4, 256] and per-slice counts [B, slices, 2].
+int token_slices(const vegas_desc* d) {
+  return static_cast<int>((static_cast<int64_t>(d->max_blocks) * kPage + kTokSlice - 1) / kTokSlice);
+}
+size_t token_select_bytes(const vegas_desc* d) {
+  return align_up(static_cast<size_t>(d->batch) * 4 * 256 * sizeof(uint32_t)) +
+         align_up(static_cast<size_t>(d->batch) * token_slices(d) * 2 * sizeof(uint32_t));
+}
+
 int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& sp, void* out, hipStream_t st) {
   CombineParams cp;
   cp.part_o = sp.part_o;
@@ -232,6 +242,10 @@ size_t vegas_workspace_bytes(const vegas_desc* desc) {
   if (desc->num_queries > 0 && check_paged16(desc) == VEGAS_OK && plan_verify(desc, &pv) == VEGAS_OK)
     need = pv.total > need ? pv.total : need;
   if (plan_draft(desc, &pd) == VEGAS_OK) need = pd.total > need ? pd.total : need;
+  if (check_paged16(desc) == VEGAS_OK) {
+    const size_t ts = token_select_bytes(desc);
+    need = ts > need ? ts : need;
+  }
   return need;
 }
 
@@ -360,6 +374,52 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(select_blocks_kernel), shm)) return rc;
   hipLaunchKernelGGL(select_blocks_kernel, dim3(desc->batch), dim3(kSelectThreads), shm,
                      static_cast<hipStream_t>(hip_stream), sp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+int vegas_select_tokens(const vegas_desc* desc, const float* token_scores, const int32_t* block_table,
+                        const int32_t* seq_lens, int32_t budget_tokens, const int32_t* budgets,
+                        int32_t* sel_table, int32_t* sel_seq_lens, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc == VEGAS_OK) rc = check_paged16(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (!token_scores || !block_table || !seq_lens || !sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
+  if (desc->num_queries <= 0 || desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
+  if (!budgets) {
+    if (budget_tokens <= 0) return VEGAS_ERR_SHAPE;
+    int64_t kmax = budget_tokens < desc->max_seq_len ? budget_tokens : desc->max_seq_len;
+    const int64_t tail = desc->num_queries < desc->max_seq_len ? desc->num_queries : desc->max_seq_len;
+    if (kmax < tail) kmax = tail;
+    if (desc->max_sel_blocks < kmax) return VEGAS_ERR_SHAPE;
+  }
+  const size_t need = token_select_bytes(desc);
+  if (!workspace || workspace_bytes < need) return VEGAS_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return VEGAS_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  TokenSelectParams tp;
+  tp.scores = token_scores;
+  tp.block_table = block_table;
+  tp.seq_lens = seq_lens;
+  tp.budgets = budgets;
+  tp.sel_table = sel_table;
+  tp.sel_seq_lens = sel_seq_lens;
+  tp.hist = reinterpret_cast<uint32_t*>(ws);
+  tp.counts = reinterpret_cast<uint32_t*>(ws + align_up(static_cast<size_t>(desc->batch) * 4 * 256 * sizeof(uint32_t)));
+  tp.budget_tokens = budget_tokens;
+  tp.G = desc->num_queries;
+  tp.max_blocks = desc->max_blocks;
+  tp.max_sel = desc->max_sel_blocks;
+  tp.max_tokens = desc->max_seq_len;
+  tp.slices = token_slices(desc);
+  const int total = desc->batch * 4 * 256;
+  const dim3 grid(tp.slices, desc->batch);
+  hipLaunchKernelGGL(token_select_zero, dim3((total + 255) / 256 < 64 ? (total + 255) / 256 : 64), dim3(256), 0, st, tp, total);
+  for (int pass = 0; pass < 4; ++pass)
+    hipLaunchKernelGGL(token_select_hist, grid, dim3(kTokThreads), 0, st, tp, pass);
+  hipLaunchKernelGGL(token_select_count, grid, dim3(kTokThreads), 0, st, tp);
+  hipLaunchKernelGGL(token_select_write, grid, dim3(kTokThreads), 0, st, tp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 

@@ -106,3 +106,150 @@ def test_rows_without_spare_columns_are_refused():
     with pytest.raises(vb.VegasError) as e:
         vb.vegas_verify_attention(desc, z, z, z, z, z, z, z.view(torch.float32), z)
     assert e.value.status == vb.VEGAS_ERR_UNSUPPORTED
+
+
+# ----------------------------------------------------------------------------------------------
+# token selection (integer work: bit-exact on identical fp32 scores)
+# ----------------------------------------------------------------------------------------------
+
+def gpu_select_tokens(scores32, table, lens, G, budget, max_sel, budgets=None):
+    dev = torch.device("cuda:0")
+    B, mb = table.shape
+    desc = vb.make_desc(batch=B, num_q_heads=32, num_kv_heads=8, num_queries=G, max_blocks=mb, max_sel_blocks=max_sel,
+                        max_seq_len=max(int(lens.max()), 1), num_pages=int(table.max()) + 1, softmax_scale=0.1)
+    ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    ws.fill_(0xFF)
+    sel = torch.full((B, max_sel), -7, dtype=torch.int32, device=dev)
+    ssl = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    vb.vegas_select_tokens(desc, torch.from_numpy(scores32).to(dev), torch.from_numpy(table).to(dev),
+                           torch.from_numpy(lens).to(dev), budget, sel, ssl, ws,
+                           budgets=None if budgets is None else torch.from_numpy(budgets).to(dev))
+    torch.cuda.synchronize()
+    return sel.cpu().numpy(), ssl.cpu().numpy()
+
+
+@pytest.mark.parametrize("kind", ["distinct", "ties", "logit_like"])
+def test_select_tokens_bit_exact(kind):
+    rng = np.random.default_rng({"distinct": 1, "ties": 2, "logit_like": 3}[kind])
+    lens = np.array([20000, 4096 + 5, 0, 3, 140001, 4101, 17], dtype=np.int32)
+    B = len(lens)
+    mb = (int(lens.max()) + PAGE - 1) // PAGE + 3
+    scores = np.zeros((B, mb * PAGE), dtype=np.float32)
+    for b in range(B):
+        n = int(lens[b])
+        if kind == "distinct":
+            scores[b, :n] = (rng.permutation(n) - n / 3.0).astype(np.float32)
+        elif kind == "ties":
+            scores[b, :n] = rng.integers(-3, 4, size=n).astype(np.float32) / 4.0
+        else:
+            x = rng.standard_normal(n).astype(np.float32) * 0.05
+            x[rng.integers(0, max(n, 1), size=n // 50)] += 3.0
+            scores[b, :n] = x
+    scores[:, :] += 0.0
+    table = np.stack([rng.permutation(mb + 11)[:mb] for _ in range(B)]).astype(np.int32)
+    G = 5
+    budgets = np.array([1400, 100000, 64, 1, 9800, 4100, 9], dtype=np.int32)
+    max_sel = 10000
+    for use_per_seq, budget in ((False, 2048), (True, 2048), (False, 7)):
+        print(f"[case] select_tokens {kind} per_seq={use_per_seq} budget={budget}", flush=True)
+        bud = budgets if use_per_seq else None
+        sel, ssl = gpu_select_tokens(scores, table, lens, G, budget, max_sel, bud)
+        ref_sel, ref_ssl, _ = O.select_tokens(scores, table, lens, G, budget, max_sel,
+                                              None if bud is None else np.minimum(bud, max_sel))
+        assert np.array_equal(ssl, ref_ssl)
+        assert np.array_equal(sel, ref_sel)
+
+
+def test_select_tokens_golden_cases():
+    import json, os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "select_token_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        n = c["seq_len"]
+        nblk = (n + PAGE - 1) // PAGE
+        scores = np.zeros((1, nblk * PAGE), dtype=np.float32)
+        scores[0, :len(c["scores"])] = c["scores"]
+        table = (np.arange(nblk, dtype=np.int32)[::-1] * 3 + 7)[None, :].copy()
+        sel, ssl = gpu_select_tokens(scores, table, np.array([n], dtype=np.int32), c["num_queries"], c["budget"], n + 2)
+        k = len(c["positions"])
+        assert int(ssl[0]) == k, c["name"]
+        assert list(sel[0, :k]) == [int(table[0, i // PAGE]) * PAGE + i % PAGE for i in c["positions"]], c["name"]
+        assert np.all(sel[0, k:] == -1), c["name"]
+
+
+# ----------------------------------------------------------------------------------------------
+# the whole token-granular chain: verify (token logits) -> select tokens -> draft over one-token pages
+# ----------------------------------------------------------------------------------------------
+
+def run_token_chain(L, budget, collect=vb.COLLECT_FIRST_LAST, name="case"):
+    s = L.spec
+    G = s.num_queries
+    dev = torch.device("cuda:0")
+    dl, path = verify_token_scores(L, collect)
+    ref_scores, got = check_token_scores(name, L, path, collect)
+    max_sel = min(max(budget, G), int(L.seq_lens.max())) + 2
+    desc_sel = vb.make_desc(batch=s.batch, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads, num_queries=G,
+                            max_blocks=L.max_blocks, max_sel_blocks=max_sel, max_seq_len=max(int(L.seq_lens.max()), 1),
+                            num_pages=L.num_pages, softmax_scale=L.softmax_scale)
+    ws = torch.empty(vb.vegas_workspace_bytes(desc_sel), dtype=torch.uint8, device=dev)
+    sel = torch.empty((s.batch, max_sel), dtype=torch.int32, device=dev)
+    ssl = torch.empty((s.batch,), dtype=torch.int32, device=dev)
+    vb.vegas_select_tokens(desc_sel, path.block_scores, dl.block_table, dl.seq_lens, budget, sel, ssl, ws)
+    torch.cuda.synchronize()
+    sel_h, ssl_h = sel.cpu().numpy(), ssl.cpu().numpy()
+    # (1) on the GPU's own fp32 scores the selection is exactly the oracle's
+    sel_same, ssl_same, _ = O.select_tokens(path.block_scores.cpu().numpy(), L.block_table, L.seq_lens, G, budget, max_sel)
+    assert np.array_equal(sel_h, sel_same) and np.array_equal(ssl_h, ssl_same)
+    # (2) against the selection from the oracle's float64 scores: identical outside the band the score error allows
+    _, ref_ssl, ref_pos = O.select_tokens(ref_scores, L.block_table, L.seq_lens, G, budget, max_sel)
+    assert np.array_equal(ssl_h, ref_ssl)
+    bound = token_score_bound(L, collect)
+    exact = 0
+    for b in range(s.batch):
+        n = int(L.seq_lens[b])
+        p_len = max(n - G, 0)
+        inv = {int(L.block_table[b, i // PAGE]) * PAGE + i % PAGE: i for i in range(n)}
+        got_pos = np.array(sorted(inv[int(x)] for x in sel_h[b, :ssl_h[b]]), dtype=np.int64)
+        assert len(set(got_pos)) == len(got_pos) == ssl_h[b]
+        assert set(range(p_len, n)).issubset(set(got_pos))
+        kc = int(ssl_h[b]) - (n - p_len)
+        if 0 < kc < p_len:
+            sc = ref_scores[b, :p_len]
+            kth = np.sort(sc)[p_len - kc]
+            band = 2 * TOKEN_SCORE_REL * float(bound[b, :p_len].max()) + 1e-12
+            chosen = got_pos[got_pos < p_len]
+            assert np.all(sc[chosen] >= kth - band), name + ": a selected token lies below the k-th score"
+            must = np.nonzero(sc > kth + band)[0]
+            assert set(must).issubset(set(chosen)), name + ": a token above the k-th score is missing"
+        exact += int(np.array_equal(got_pos, ref_pos[b]))
+    print(f"[info] {name}: {exact}/{s.batch} sequences select exactly the oracle's token set", flush=True)
+    # (3) draft over the GPU's selection, one-token pages
+    desc_d = vb.make_desc(batch=s.batch, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads, num_queries=1,
+                          max_blocks=max_sel, max_sel_blocks=max_sel, max_seq_len=max(int(ssl_h.max()), 1),
+                          num_pages=L.num_pages * PAGE, softmax_scale=L.softmax_scale, page_size=1)
+    wsd = torch.empty(vb.vegas_workspace_bytes(desc_d), dtype=torch.uint8, device=dev)
+    kc1 = L.k_cache.reshape(-1, 1, s.num_kv_heads, s.head_dim)
+    vc1 = L.v_cache.reshape(-1, 1, s.num_kv_heads, s.head_dim)
+    for step in (0, G - 1):
+        out = torch.empty((s.batch, s.num_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+        vb.vegas_draft_attention(desc_d, dl.q_draft[step], dl.k_cache, dl.v_cache, sel, ssl, out, wsd)
+        torch.cuda.synchronize()
+        ref = O.draft_attention(L.q_draft[step], kc1, vc1, sel_h, ssl_h, L.softmax_scale)
+        U.check_out(f"{name}.draft{step}", out, ref, U.vmax_visible(L))
+
+
+def test_token_chain_small_ragged():
+    L = synth.make_random_case(seed=611, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[5000, 4, 1300], logit_std=1.5, value_std=1.0, outliers=3, outlier_logit=20.0)
+    run_token_chain(L, 400, name="token_chain_ragged")
+
+
+def test_token_chain_ctx32k_full():
+    """The 32K workload at the paper's operating point: 7 % of the tokens (App. C), Eq. 3 rows."""
+    L = synth.make_layer(synth.CONFIGS["ctx32k"])
+    run_token_chain(L, int(0.07 * 32768), name="token_chain_ctx32k")
+
+
+def test_token_chain_ctx128k_full():
+    L = synth.make_layer(synth.CONFIGS["ctx128k_drift"])
+    run_token_chain(L, int(0.07 * 131072), name="token_chain_ctx128k")
