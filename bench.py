@@ -235,6 +235,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--extras", action="store_true")
+    ap.add_argument("--variant", choices=["page", "token"], default="page",
+                    help="page: 16-token pages scored by softmax weights (the default path); token: the paper's own "
+                         "variant -- averaged logits per token (Eq. 3 rows), top-k over tokens, one-token pages")
+    ap.add_argument("--budget", type=int, default=0, help="KV budget in tokens (0: the workload's)")
     ap.add_argument("--sweep", choices=["collect", "page_size"], default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -264,7 +268,11 @@ def main() -> int:
     dev = torch.device("cuda:0")
     base = harness.DeviceLayer.upload(L, dev)
     copies = device_copies(harness, base, copies_for(base, args.copies))
-    path = harness.VegasPath.for_layer(L, verify_chunk=args.verify_chunk, draft_chunk=args.draft_chunk)
+    token = args.variant == "token"
+    budget = args.budget or spec.budget_tokens
+    path = harness.VegasPath.for_layer(L, budget_tokens=budget, verify_chunk=args.verify_chunk,
+                                       draft_chunk=args.draft_chunk, token_granular=token,
+                                       collect_rows=vb.COLLECT_FIRST_LAST if token else vb.COLLECT_ALL_ROWS)
     G = spec.num_queries
     stream = int(torch.cuda.current_stream(dev).cuda_stream)
 
@@ -305,7 +313,7 @@ def main() -> int:
         desc.launch_stages = 0
         return e0.elapsed_ms(e1) / reps * 1e3
 
-    traffic = VERIFY_TRAFFIC_BYTES if workload == DEFAULT_WORKLOAD and args.verify_chunk == 0 else None
+    traffic = VERIFY_TRAFFIC_BYTES if workload == DEFAULT_WORKLOAD and args.verify_chunk == 0 and not token else None
     roofline = {"bound": "hbm", "kernel": "attn_split_kernel<causal, collect> (KV-streaming kernel of vegas_verify_attention)",
                 "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": traffic,
                 "bytes_per_launch": verify_bytes}
@@ -330,7 +338,7 @@ def main() -> int:
                    "context_tokens_total": n_tokens, "layer": args.layer,
                    "num_q_heads": spec.num_q_heads, "num_kv_heads": spec.num_kv_heads,
                    "head_dim": spec.head_dim, "page_size": 16, "gamma": spec.gamma,
-                   "kv_budget_tokens": spec.budget_tokens, "draft_steps": G,
+                   "kv_budget_tokens": budget, "draft_steps": G, "variant": args.variant,
                    "kv_cache_copies_rotated": len(copies)},
         "iteration_kv_bytes": iter_bytes,
         "iteration_gbps": iter_bytes / (us_per_step * 1e-6) / 1e9,
@@ -384,7 +392,7 @@ def main() -> int:
                          "iteration_us_p90": percentile(per, 0.9), "iteration_us_warm_cache": warm_us,
                          "iteration_us_hip_graph": graph_us}
 
-    if not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0:
+    if not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0 and not token and not args.budget:
         out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens, workload)
     print(json.dumps(out), flush=True)
     return 0

@@ -157,8 +157,8 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores,
  *                                           vegas_draft_attention with page_size = 1
  *   sel_seq_lens int32 [B]                  k_b
  * desc->page_size is 16 here (it describes block_table); desc->max_sel_blocks counts tokens.
- * Integer work: for identical fp32 scores the result is defined bit for bit.  Seven short kernels
- * (histogram passes meet in global memory); workspace from vegas_workspace_bytes.
+ * Integer work: for identical fp32 scores the result is defined bit for bit.  Five short kernels
+ * (four digit-histogram passes that meet in global memory, one ordered compaction); workspace from vegas_workspace_bytes.
  * Returns VEGAS_ERR_SHAPE if max_sel_blocks < max(min(budget_tokens, max_seq_len), min(G, max_seq_len))
  * (checked when budgets == NULL; per-sequence budgets are clamped on the device).
  */

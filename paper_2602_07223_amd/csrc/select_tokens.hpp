@@ -2,14 +2,14 @@
 //
 // A sequence has up to a few hundred thousand prefix tokens, too many for one workgroup, so the
 // radix select of the page version is spread over workgroups that own 4096-token slices and meet in
-// global histograms between launches:
-//   token_select_zero      clears the digit histograms
-//   token_select_hist x 4  pass q: every workgroup re-derives the key prefix fixed by passes < q from
-//                          their (complete) histograms, counts digit q of its slice's matching keys
-//                          in LDS and adds its 256 counts to the global histogram of pass q
-//   token_select_count     with the k-th key T known: keys > T and keys == T per slice
-//   token_select_write     exclusive prefix over the slices' counts, then an order-preserving
-//                          compaction of the slice; physical slot = table[i / 16] * 16 + i % 16
+// per-slice digit histograms between launches (plain stores, nothing to clear, no global atomics):
+//   token_select_hist x 4  pass q: every workgroup sums the slices' histograms of passes < q, derives
+//                          the key prefix they fix, counts digit q of its own slice's matching keys
+//                          in LDS and stores its 256 counts
+//   token_select_write     derives the k-th key T the same way; the keys > T and == T in the slices
+//                          before its own follow from those slices' histograms, so it knows where its
+//                          output starts; then an order-preserving compaction of the slice;
+//                          physical slot = table[i / 16] * 16 + i % 16
 // The last min(G, n) tokens are not part of the prefix and are always kept (Sec. 3.2, last sentence).
 // Integer work on the score bits: defined bit for bit, ties go to the lower position.
 #pragma once
@@ -28,8 +28,7 @@ struct TokenSelectParams {
   const int32_t* budgets;     // or nullptr
   int32_t* sel_table;         // [B, max_sel] physical token slots
   int32_t* sel_seq_lens;
-  uint32_t* hist;             // [B, 4, 256]
-  uint32_t* counts;           // [B, slices, 2] (keys > T, keys == T) of every slice
+  uint32_t* hist;             // [B, 4, slices, 256] digit histogram of every (pass, slice)
   int32_t budget_tokens, G, max_blocks, max_sel, max_tokens, slices;
 };
 
@@ -68,19 +67,42 @@ __device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
   return static_cast<uint32_t>(v);
 }
 
-// Executed by ONE full wave: walks the finished histograms of passes 0 .. passes-1 of sequence b and
-// returns, in every lane, the key prefix they fix and how many keys are still wanted inside it.
-__device__ __forceinline__ void token_prefix(const TokenSelectParams& p, int b, int passes, uint32_t kc,
+// All threads: sh_tot[q][bin] = sum over the sequence's slices of histogram (pass q, bin) for q < passes,
+// and, if sh_bef is given, the same sum over the slices before `upto` only.  Followed by a barrier.
+__device__ __forceinline__ void token_sum_hists(const TokenSelectParams& p, int b, int passes, int nslices, int upto,
+                                                uint32_t (*sh_tot)[256], uint32_t (*sh_bef)[256]) {
+  const int q = threadIdx.x >> 8, bin = threadIdx.x & 255;          // 1024 threads = 4 passes x 256 bins
+  if (q < passes) {
+    const uint32_t* h = p.hist + ((static_cast<int64_t>(b) * 4 + q) * p.slices) * 256 + bin;
+    uint32_t tot = 0u, bef = 0u;
+    for (int sl0 = 0; sl0 < nslices; sl0 += 8) {          // eight independent loads in flight per round trip
+      uint32_t c[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) c[u] = h[static_cast<int64_t>(min(sl0 + u, nslices - 1)) * 256];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        tot += sl0 + u < nslices ? c[u] : 0u;
+        bef += sl0 + u < upto ? c[u] : 0u;
+      }
+    }
+    sh_tot[q][bin] = tot;
+    if (sh_bef) sh_bef[q][bin] = bef;
+  }
+  __syncthreads();
+}
+
+// Executed by ONE full wave: walks the summed histograms of passes 0 .. passes-1 and returns, in every
+// lane, the key prefix they fix and how many keys are still wanted inside it.
+__device__ __forceinline__ void token_prefix(const uint32_t (*sh_tot)[256], int passes, uint32_t kc,
                                              uint32_t* prefix_out, uint32_t* need_out) {
   const int lane = threadIdx.x & 63;
   uint32_t prefix = 0u, need = kc;
   for (int q = 0; q < passes; ++q) {
     const int shift = 24 - 8 * q;
-    const uint32_t* h = p.hist + (static_cast<int64_t>(b) * 4 + q) * 256;
     // lane l owns bins 255-4l .. 252-4l, so an inclusive prefix sum over lanes counts from the top bin down
     uint32_t c[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) c[i] = h[255 - 4 * lane - i];
+    for (int i = 0; i < 4; ++i) c[i] = sh_tot[q][255 - 4 * lane - i];
     const uint32_t mine = c[0] + c[1] + c[2] + c[3];
     uint32_t above = wave_prefix_sum(mine) - mine;
     uint32_t found = 0u, digit = 0u, rest = 0u;
@@ -104,26 +126,25 @@ __device__ __forceinline__ void token_prefix(const TokenSelectParams& p, int b, 
   *need_out = need;
 }
 
-__global__ __launch_bounds__(256) void token_select_zero(const TokenSelectParams p, int total) {
-  for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) p.hist[i] = 0u;
-}
-
 __global__ __launch_bounds__(kTokThreads) void token_select_hist(const TokenSelectParams p, int pass) {
   __shared__ uint32_t hist[kTokThreads / 64][256];
+  __shared__ uint32_t sh_tot[4][256];
   __shared__ uint32_t sh_prefix;
   const int b = blockIdx.y, s = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const TokenPlan t = token_plan(p, b);
   const int base = s * kTokSlice;
   if (!t.need_search || base >= t.p_len) return;
-  if (wave == 0) {
-    uint32_t prefix, need;
-    token_prefix(p, b, pass, static_cast<uint32_t>(t.kc), &prefix, &need);
-    if (lane == 0) sh_prefix = prefix;
-  }
+  const int nslices = (t.p_len + kTokSlice - 1) / kTokSlice;
   uint32_t* h = hist[wave];
 #pragma unroll
   for (int i = 0; i < 4; ++i) h[lane + 64 * i] = 0u;
+  token_sum_hists(p, b, pass, nslices, 0, sh_tot, nullptr);
+  if (wave == 0) {
+    uint32_t prefix, need;
+    token_prefix(sh_tot, pass, static_cast<uint32_t>(t.kc), &prefix, &need);
+    if (lane == 0) sh_prefix = prefix;
+  }
   __syncthreads();
   const uint32_t prefix = sh_prefix;
   const uint32_t mask = pass == 0 ? 0u : (0xFFFFFFFFu << (32 - 8 * pass));
@@ -157,51 +178,12 @@ __global__ __launch_bounds__(kTokThreads) void token_select_hist(const TokenSele
     uint32_t c = 0u;
 #pragma unroll
     for (int w = 0; w < kTokThreads / 64; ++w) c += hist[w][tid];
-    if (c) atomicAdd(p.hist + (static_cast<int64_t>(b) * 4 + pass) * 256 + tid, c);
-  }
-}
-
-__global__ __launch_bounds__(kTokThreads) void token_select_count(const TokenSelectParams p) {
-  __shared__ uint32_t sh_T;
-  __shared__ uint32_t wgt[kTokThreads / 64], weq[kTokThreads / 64];
-  const int b = blockIdx.y, s = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const TokenPlan t = token_plan(p, b);
-  const int base = s * kTokSlice;
-  if (!t.need_search || base >= t.p_len) return;
-  if (wave == 0) {
-    uint32_t T, need_eq;
-    token_prefix(p, b, 4, static_cast<uint32_t>(t.kc), &T, &need_eq);
-    if (lane == 0) sh_T = T;
-  }
-  __syncthreads();
-  const uint32_t T = sh_T;
-  const float* scores = p.scores + static_cast<int64_t>(b) * p.max_blocks * kPage;
-  uint32_t gt = 0u, eq = 0u;
-#pragma unroll
-  for (int it = 0; it < kTokSlice / kTokThreads; ++it) {
-    const int j = base + it * kTokThreads + tid;
-    bool g = false, e = false;
-    if (j < t.p_len) {
-      const uint32_t key = score_key(scores[j]);
-      g = key > T;
-      e = key == T;
-    }
-    gt += __popcll(__builtin_amdgcn_ballot_w64(g));
-    eq += __popcll(__builtin_amdgcn_ballot_w64(e));
-  }
-  if (lane == 0) { wgt[wave] = gt; weq[wave] = eq; }
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t G = 0u, E = 0u;
-    for (int w = 0; w < kTokThreads / 64; ++w) { G += wgt[w]; E += weq[w]; }
-    uint32_t* c = p.counts + (static_cast<int64_t>(b) * p.slices + s) * 2;
-    c[0] = G;
-    c[1] = E;
+    p.hist[((static_cast<int64_t>(b) * 4 + pass) * p.slices + s) * 256 + tid] = c;
   }
 }
 
 __global__ __launch_bounds__(kTokThreads) void token_select_write(const TokenSelectParams p) {
+  __shared__ uint32_t sh_tot[4][256], sh_bef[4][256];
   __shared__ uint32_t sh_T, sh_need_eq, sh_eq_before, sh_pos_before;
   __shared__ uint32_t wave_take[kTokThreads / 64], wave_eq[kTokThreads / 64];
   const int b = blockIdx.y, s = blockIdx.x;
@@ -221,19 +203,33 @@ __global__ __launch_bounds__(kTokThreads) void token_select_write(const TokenSel
 
   const int base = s * kTokSlice;
   if (t.kc == 0 || base >= t.p_len) return;
-  if (wave == 0 && t.need_search) {
-    uint32_t T, need_eq;
-    token_prefix(p, b, 4, static_cast<uint32_t>(t.kc), &T, &need_eq);
-    // exclusive prefix over the slices before this one: ties seen, and tokens taken
-    uint32_t eq_before = 0u, pos_before = 0u;
-    const uint32_t* c = p.counts + static_cast<int64_t>(b) * p.slices * 2;
-    for (int q = 0; q < s; ++q) {
-      const uint32_t g = c[2 * q], e = c[2 * q + 1];
-      const uint32_t room = need_eq > eq_before ? need_eq - eq_before : 0u;
-      pos_before += g + min(e, room);
-      eq_before += e;
+  if (t.need_search) {
+    const int nslices = (t.p_len + kTokSlice - 1) / kTokSlice;
+    token_sum_hists(p, b, 4, nslices, s, sh_tot, sh_bef);
+    if (wave == 0) {
+      uint32_t T, need_eq;
+      token_prefix(sh_tot, 4, static_cast<uint32_t>(t.kc), &T, &need_eq);
+      // In the slices before this one: keys > T are, pass by pass, the keys that match T's prefix so far and
+      // have a larger digit; keys == T are the last pass's count of T's low digit.
+      uint32_t gt = 0u;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t digit = (T >> (24 - 8 * q)) & 255u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t bin = static_cast<uint32_t>(4 * lane + i);
+          gt += bin > digit ? sh_bef[q][bin] : 0u;
+        }
+      }
+      gt = __builtin_amdgcn_readlane(wave_prefix_sum(gt), 63);
+      const uint32_t eq_before = sh_bef[3][T & 255u];
+      if (lane == 0) {
+        sh_T = T;
+        sh_need_eq = need_eq;
+        sh_eq_before = eq_before;
+        sh_pos_before = gt + min(eq_before, need_eq);        // ties are taken in order until need_eq are found
+      }
     }
-    if (lane == 0) { sh_T = T; sh_need_eq = need_eq; sh_eq_before = eq_before; sh_pos_before = pos_before; }
   }
   __syncthreads();
   const bool all = t.take_all;

@@ -190,13 +190,12 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->scale_log2e = d->softmax_scale * 1.4426950408889634f;
 }
 
-// Scratch of vegas_select_tokens: digit histograms [B, 4, 256] and per-slice counts [B, slices, 2].
+// Scratch of vegas_select_tokens: digit histograms [B, 4 passes, slices, 256].
 int token_slices(const vegas_desc* d) {
   return static_cast<int>((static_cast<int64_t>(d->max_blocks) * kPage + kTokSlice - 1) / kTokSlice);
 }
 size_t token_select_bytes(const vegas_desc* d) {
-  return align_up(static_cast<size_t>(d->batch) * 4 * 256 * sizeof(uint32_t)) +
-         align_up(static_cast<size_t>(d->batch) * token_slices(d) * 2 * sizeof(uint32_t));
+  return align_up(static_cast<size_t>(d->batch) * 4 * token_slices(d) * 256 * sizeof(uint32_t));
 }
 
 int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& sp, void* out, hipStream_t st) {
@@ -406,19 +405,15 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores, const
   tp.sel_table = sel_table;
   tp.sel_seq_lens = sel_seq_lens;
   tp.hist = reinterpret_cast<uint32_t*>(ws);
-  tp.counts = reinterpret_cast<uint32_t*>(ws + align_up(static_cast<size_t>(desc->batch) * 4 * 256 * sizeof(uint32_t)));
   tp.budget_tokens = budget_tokens;
   tp.G = desc->num_queries;
   tp.max_blocks = desc->max_blocks;
   tp.max_sel = desc->max_sel_blocks;
   tp.max_tokens = desc->max_seq_len;
   tp.slices = token_slices(desc);
-  const int total = desc->batch * 4 * 256;
   const dim3 grid(tp.slices, desc->batch);
-  hipLaunchKernelGGL(token_select_zero, dim3((total + 255) / 256 < 64 ? (total + 255) / 256 : 64), dim3(256), 0, st, tp, total);
   for (int pass = 0; pass < 4; ++pass)
     hipLaunchKernelGGL(token_select_hist, grid, dim3(kTokThreads), 0, st, tp, pass);
-  hipLaunchKernelGGL(token_select_count, grid, dim3(kTokThreads), 0, st, tp);
   hipLaunchKernelGGL(token_select_write, grid, dim3(kTokThreads), 0, st, tp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }

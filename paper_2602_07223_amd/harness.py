@@ -51,21 +51,33 @@ class VegasPath:
                  max_seq_len: int, num_pages: int, budget_tokens: int, softmax_scale: float,
                  collect_rows: int = vb.COLLECT_ALL_ROWS, head_dim: int = 128, device="cuda:0",
                  verify_chunk: int = 0, draft_chunk: int = 0, max_sel_blocks: int = 0,
-                 score_metric: int = vb.METRIC_PAGE_WEIGHTS):
+                 score_metric: int = vb.METRIC_PAGE_WEIGHTS, token_granular: bool = False):
+        """token_granular: the paper's own variant -- verification collects averaged logits per token,
+        selection picks single tokens, drafting walks one-token pages (Sec. 3.3, Sec. 4)."""
         self.device = torch.device(device)
+        self.token_granular = token_granular
+        if token_granular:
+            score_metric = vb.METRIC_TOKEN_LOGITS
         self.B, self.Hq, self.Hkv, self.G, self.D = batch, num_q_heads, num_kv_heads, num_queries, head_dim
         self.budget_tokens = budget_tokens
         max_pages = (max_seq_len + PAGE - 1) // PAGE
         want = max(min((budget_tokens + PAGE - 1) // PAGE, max_pages), (num_queries + PAGE - 2) // PAGE + 1)
+        if token_granular:                                   # sel_table rows hold token slots
+            want = min(max(budget_tokens, num_queries), max_seq_len)
         self.max_sel_blocks = max_sel_blocks or (want + 2)
         common = dict(batch=batch, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, num_queries=num_queries,
                       max_blocks=max_blocks, max_sel_blocks=self.max_sel_blocks, num_pages=num_pages,
                       softmax_scale=softmax_scale, head_dim=head_dim)
         self.desc_verify = vb.make_desc(max_seq_len=max_seq_len, collect_rows=collect_rows,
                                         kv_chunk_tokens=verify_chunk, score_metric=score_metric, **common)
-        draft_len = min(self.max_sel_blocks * PAGE, max_blocks * PAGE)
-        self.desc_draft = vb.make_desc(max_seq_len=draft_len, collect_rows=vb.COLLECT_NONE,
-                                       kv_chunk_tokens=draft_chunk, **common)
+        if token_granular:
+            draft_common = dict(common, max_blocks=self.max_sel_blocks, num_pages=num_pages * PAGE)
+            self.desc_draft = vb.make_desc(max_seq_len=min(self.max_sel_blocks, max_seq_len), collect_rows=vb.COLLECT_NONE,
+                                           kv_chunk_tokens=draft_chunk, page_size=1, **draft_common)
+        else:
+            draft_len = min(self.max_sel_blocks * PAGE, max_blocks * PAGE)
+            self.desc_draft = vb.make_desc(max_seq_len=draft_len, collect_rows=vb.COLLECT_NONE,
+                                           kv_chunk_tokens=draft_chunk, **common)
         nbytes = max(vb.vegas_workspace_bytes(self.desc_verify), vb.vegas_workspace_bytes(self.desc_draft))
         if nbytes == 0:
             raise ValueError("descriptor rejected by vegas_workspace_bytes")
@@ -120,6 +132,11 @@ class VegasPath:
 
     def select(self, dl: DeviceLayer, block_scores: Optional[torch.Tensor] = None, budgets=None, stream=None) -> None:
         a, o = self._addrs(dl), self._own()
+        if self.token_granular:
+            vb.vegas_select_tokens(self.desc_verify, o["bs"] if block_scores is None else block_scores,
+                                   a["bt"], a["sl"], self.budget_tokens, o["st"], o["ssl"], o["ws"], budgets=budgets,
+                                   stream=self.stream() if stream is None else stream, workspace_bytes=o["wsn"])
+            return
         vb.vegas_select_blocks(self.desc_verify, o["bs"] if block_scores is None else block_scores,
                                a["bt"], a["sl"], self.budget_tokens, o["st"], o["ssl"], budgets=budgets,
                                stream=self.stream() if stream is None else stream)
