@@ -125,7 +125,7 @@ __global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombinePa
 // Verification epilogue in ONE launch (a kernel boundary costs ~3 us on this GPU): workgroups
 // [0, nA) merge the chunk partials of two query rows each (as the combine kernels do) and write
 // the bf16 output rows (Eq. 1); workgroups [nA, nA + nB) turn the per-(row, page) log-sum-exps of
-// page_groups x 32 pages into page criticalities (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the
+// 32 pages into page criticalities (Eq. 2 / Eq. 3 with weights, averaged over rows and heads as in the
 // last paragraph of Sec. 3.3): score[b][j] = inv_norm * sum_h sum_{rows in R} 2^(page_lse - row_lse).
 // A score workgroup derives the global row log-sum-exps itself from the chunks' (max, sum) pairs,
 // so it does not depend on the merge workgroups.  Pages at or beyond the sequence's page count get 0.
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
 
   // ---- role B: 32 pages; thread = (page, head slot)
   const int pg = tid & 31, slot = tid >> 5;
-  const int jbase = (blockIdx.x - p.nA) * 32 * p.page_groups;       // page_groups x 32 pages per workgroup
+  const int jbase = (blockIdx.x - p.nA) * 32;
   float* out_row = p.block_scores + static_cast<int64_t>(b) * p.max_blocks;
   float* sm_row = smf;                        // [HR] global row lse; -inf for rows that do not count
   float* sm_sum = smf + HR;                   // [8][32]
@@ -257,9 +257,9 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
       }
     }
   };
-  // The first batch, and (with one 32-page group and few rows) this thread's page log-sum-exps, are
+  // The first batch, and (with few rows) this thread's page log-sum-exps, are
   // requested before the sequence length is needed.
-  const bool pre_ok = p.page_groups == 1 && (p.R & 3) == 0 && p.R <= 4 * kFinPre && p.Hkv <= 8;
+  const bool pre_ok = (p.R & 3) == 0 && p.R <= 4 * kFinPre && p.Hkv <= 8;
   f32x4 pre[kFinPre];
   const int jpre = min(jbase + pg, p.lse_pages - 1);
   if (pre_ok && slot < p.Hkv) {
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const int nblk = (n + kPage - 1) / kPage;
   if (jbase >= nblk) {                                             // whole workgroup past the sequence
-    for (int j = jbase + tid; j < jbase + 32 * p.page_groups && j < p.max_blocks; j += 256) out_row[j] = 0.f;
+    if (tid < 32 && jbase + tid < p.max_blocks) out_row[jbase + tid] = 0.f;
     return;
   }
   bool loaded = true;
@@ -321,8 +321,8 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     sm_row[i] = (use && L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
   }
   __syncthreads();
-  for (int grp = 0; grp < p.page_groups; ++grp) {
-    const int j = jbase + grp * 32 + pg;
+  {
+    const int j = jbase + pg;
     float sc = 0.f;
     if (j < nblk) {
       if (pre_ok) {
@@ -363,7 +363,6 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
       for (int q = 0; q < 8; ++q) tot += sm_sum[q * 32 + pg];
       out_row[j] = (j < nblk) ? tot * p.inv_norm : 0.f;
     }
-    __syncthreads();
   }
 }
 

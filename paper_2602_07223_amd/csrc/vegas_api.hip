@@ -296,15 +296,10 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
                                                                    : (desc->num_queries > 1 ? 2 : 1);
   fp.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
-  // Every score workgroup rebuilds the (rows x chunks) table of (max, sum) pairs; when that table is
-  // big, give each workgroup more pages so the redundant reads stay within a few MB per sequence.
+  // Every score workgroup (32 pages) rebuilds the row log-sum-exps from the (rows x chunks) table of
+  // (max, sum) pairs; giving a workgroup more pages to amortise that was measured slower.
   const size_t hr = static_cast<size_t>(sp.Hkv) * pl.R;
-  const size_t table_bytes = hr * pl.nsplit * sizeof(float2);
-  const int groups32 = (desc->max_blocks + 31) / 32;
-  int page_groups = 1;
-  (void)table_bytes;   // measured: larger page groups lose more to serialisation than the table re-reads cost
-  fp.page_groups = page_groups;
-  int nB = (groups32 + page_groups - 1) / page_groups;
+  int nB = (desc->max_blocks + 31) / 32;
   size_t shm = (hr + 256 + 16 * hr) * sizeof(float);   // role B needs the most; role A fits inside
   fp.nC = 0;
   fp.tok_norm = 0.f;

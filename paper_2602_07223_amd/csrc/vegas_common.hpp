@@ -102,7 +102,6 @@ struct FinalizeParams {
   int32_t nC;               // logit metric: workgroups that sum the token partials (1024 tokens each)
   float tok_norm;           // logit metric: softmax_scale / (collected rows * H_q)
   int32_t nA;               // workgroups that merge rows (two rows each); the rest score pages
-  int32_t page_groups;      // 32-page groups scored by one workgroup (more when its row table is big)
   float inv_norm;
 };
 

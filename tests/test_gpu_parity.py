@@ -69,6 +69,7 @@ SMALL = [
     ("gamma11_g4", 1, 32, 8, 12, [2000], {}),
     ("mha_like", 1, 8, 8, 3, [900], {}),
     ("rows96", 2, 64, 8, 12, [1100, 300], {}),
+    ("rows96_big_table", 2, 64, 8, 12, [2000, 77], dict(verify_chunk=128)),   # scores finalised in two launches
 ]
 
 
