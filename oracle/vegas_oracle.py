@@ -283,6 +283,40 @@ def select_tokens(token_scores: np.ndarray, block_table: np.ndarray, seq_lens: n
     return sel_table, sel_seq_lens, logical
 
 
+def ratio_budgets(seq_lens: np.ndarray, ratio: float) -> np.ndarray:
+    """Per-sequence token budgets from a sparsity ratio (App. C): ceil(ratio * n_b), with the product
+    taken in float32 so that the budget is one well-defined integer on every implementation."""
+    n = np.asarray(seq_lens).astype(np.float32)
+    return np.ceil(np.float32(ratio) * n).astype(np.int64)
+
+
+def extend_selection(sel_table: np.ndarray, sel_seq_lens: np.ndarray, block_table: np.ndarray,
+                     seq_lens_after: np.ndarray, num_new: int, page_size: int):
+    """Selection after num_new freshly appended tokens per sequence were added to it (Sec. 3.2, last
+    sentence: only the prefix is sparsified; later tokens are kept).  Positions
+    [n' - num_new, n') join the selection: a new table entry whenever a position starts a page of the
+    selection's page size (16: the physical page block_table[i // 16]; 1: the physical slot
+    block_table[i // 16] * 16 + i % 16), and num_new more covered tokens.  Sequences whose row is
+    full or whose selection is empty are left unchanged.  Returns new copies."""
+    sel = np.array(sel_table, copy=True)
+    ssl = np.array(sel_seq_lens, copy=True)
+    P = int(page_size)
+    for b in range(sel.shape[0]):
+        if ssl[b] <= 0:
+            continue
+        n_new = int(seq_lens_after[b])
+        count = (int(ssl[b]) + P - 1) // P
+        entries = []
+        for i in range(n_new - num_new, n_new):
+            if i % P == 0:
+                entries.append(int(block_table[b, i // PAGE]) * (PAGE // P) + (i % PAGE) // P)
+        if count + len(entries) > sel.shape[1]:
+            continue
+        sel[b, count:count + len(entries)] = entries
+        ssl[b] += num_new
+    return sel, ssl
+
+
 def draft_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
                     sel_table: np.ndarray, sel_seq_lens: np.ndarray, scale: float) -> np.ndarray:
     """One draft query per sequence attends over exactly the tokens of the selected pages.

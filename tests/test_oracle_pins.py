@@ -543,3 +543,53 @@ def test_draft_over_selected_tokens_equals_library_attention_over_them():
     v = torch.from_numpy(c["Vd"][tok]).permute(1, 0, 2)[None]
     ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, enable_gqa=True)[0, :, 0].numpy()
     np.testing.assert_allclose(out[0], ref, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------------
+# ratio budgets (App. C) and growth of the selection while drafting (Sec. 3.2, last sentence)
+# ----------------------------------------------------------------------------------------------
+
+def test_ratio_budgets_closed_cases():
+    # exactly representable products: 0.5 * n, 0.25 * n, and the ceiling of a non-integer product
+    assert list(O.ratio_budgets(np.array([0, 1, 2, 3, 100, 131072]), 0.5)) == [0, 1, 1, 2, 50, 65536]
+    assert list(O.ratio_budgets(np.array([4, 5, 7]), 0.25)) == [1, 2, 2]
+    # 7 % of 32768 = 2293.76 -> 2294; of 131072 = 9175.04 -> 9176 (the paper's operating point, App. C / Table 6)
+    assert list(O.ratio_budgets(np.array([32768, 131072]), 0.07)) == [2294, 9176]
+
+
+@pytest.mark.parametrize("P", [1, 16])
+@pytest.mark.parametrize("n_old,num_new", [(70, 1), (79, 3), (80, 1), (64, 17)])
+def test_extended_selection_covers_old_selection_and_new_tokens(P, n_old, num_new):
+    """After appending tokens, drafting over the extended selection equals library attention over the old
+    selection's tokens plus the new positions."""
+    Hq, Hkv, D, G = 4, 2, 32, 2
+    n_new = n_old + num_new
+    c = small_case(140 + n_old + num_new, n_new, 1, Hq, Hkv, D)       # cache already holds the appended tokens
+    rng = np.random.default_rng(n_old)
+    if P == 16:
+        scores = rng.random((1, c["nblk"]))
+        sel, ssl, logical = O.select_blocks(scores, c["block_table"], np.array([n_old], dtype=np.int32), G, 32, 12)
+        tok_old = np.concatenate([np.arange(16 * j, min(16 * (j + 1), n_old)) for j in logical[0]])
+        kc, vc = c["k_cache"], c["v_cache"]
+    else:
+        scores = rng.standard_normal((1, c["nblk"] * PAGE))
+        sel, ssl, logical = O.select_tokens(scores, c["block_table"], np.array([n_old], dtype=np.int32), G, 20, 48)
+        tok_old = logical[0]
+        kc, vc = c["k_cache"].reshape(-1, 1, Hkv, D), c["v_cache"].reshape(-1, 1, Hkv, D)
+    sel2, ssl2 = O.extend_selection(sel, ssl, c["block_table"], np.array([n_new], dtype=np.int32), num_new, P)
+    assert int(ssl2[0]) == int(ssl[0]) + num_new
+    out = O.draft_attention(c["q"][:, 0], kc, vc, sel2, ssl2, c["scale"])
+    tok = np.concatenate([tok_old, np.arange(n_old, n_new)])
+    q = torch.from_numpy(c["Q"][0]).permute(1, 0, 2)[None]
+    k = torch.from_numpy(c["Kd"][tok]).permute(1, 0, 2)[None]
+    v = torch.from_numpy(c["Vd"][tok]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, enable_gqa=True)[0, :, 0].numpy()
+    np.testing.assert_allclose(out[0], ref, atol=1e-12)
+
+
+def test_extend_selection_leaves_full_rows_and_empty_selections_alone():
+    table = np.arange(8, dtype=np.int32)[None, :].repeat(2, axis=0)
+    sel = np.array([[0, 1, 2, 3], [-1, -1, -1, -1]], dtype=np.int32)
+    ssl = np.array([64, 0], dtype=np.int32)
+    sel2, ssl2 = O.extend_selection(sel, ssl, table, np.array([65, 1], dtype=np.int32), 1, 16)
+    assert np.array_equal(sel2, sel) and np.array_equal(ssl2, ssl)
