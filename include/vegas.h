@@ -88,6 +88,9 @@ typedef struct vegas_desc {
                               those kernels of an attention call (outputs then incomplete) */
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
   int32_t score_metric;    /* VEGAS_METRIC_*: what vegas_verify_attention writes to block_scores */
+  float   budget_ratio;    /* selection calls: if > 0 and no per-sequence budgets are passed, sequence b's budget
+                              is ceil(budget_ratio * seq_lens[b]) tokens (fp32 arithmetic) instead of
+                              budget_tokens: a sparsity ratio adapts the budget to the context (App. C) */
   int64_t num_pages;       /* pages in each cache (device-side clamp of page ids) */
   int64_t kv_page_stride;  /* elements between pages */
   int64_t kv_token_stride; /* elements between slots of a page */
@@ -167,6 +170,26 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores,
                         int32_t budget_tokens, const int32_t* budgets,
                         int32_t* sel_table, int32_t* sel_seq_lens,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Growth of a selection while drafting (Sec. 3.2, last sentence: tokens after the prefix are kept).
+ * Each draft step appends one token's K/V to the cache; the next draft step must see it.  Call this
+ * after the caller has written the new K/V and increased seq_lens: for every sequence it adds the
+ * num_new newest token positions [seq_lens[b] - num_new, seq_lens[b]) to the selection -- a new entry
+ * of sel_table whenever such a position starts a page of the selection's page size, and num_new more
+ * tokens in sel_seq_lens[b].
+ *   desc->page_size        page size of sel_table: 16 (from vegas_select_blocks; entries are
+ *                          block_table[i/16]) or 1 (from vegas_select_tokens; entries are
+ *                          block_table[i/16]*16 + i%16)
+ *   block_table  int32 [B, max_blocks]   16-token pages of the cache, covering the new positions
+ *   seq_lens     int32 [B]               lengths AFTER the append
+ *   sel_table / sel_seq_lens             updated in place; a sequence whose row of sel_table is full
+ *                                        (max_sel_blocks entries) or whose selection is empty is left as is
+ * Precondition: the selection ends with the sequence's last page (every selection of this library does).
+ * One tiny kernel; no workspace.
+ */
+int vegas_extend_selection(const vegas_desc* desc, const int32_t* block_table, const int32_t* seq_lens,
+                           int32_t num_new, int32_t* sel_table, int32_t* sel_seq_lens, void* hip_stream);
 
 /*
  * Sparse draft attention (Sec. 2.2 last paragraph; Sec. 4: the selection is the page list).

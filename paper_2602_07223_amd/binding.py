@@ -32,7 +32,7 @@ STAGE_STREAM = 1
 STAGE_MERGE = 2
 
 EXPORTS = ("vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks", "vegas_select_tokens",
-           "vegas_draft_attention", "vegas_strerror")
+           "vegas_extend_selection", "vegas_draft_attention", "vegas_strerror")
 
 
 class VegasDesc(ctypes.Structure):
@@ -52,6 +52,7 @@ class VegasDesc(ctypes.Structure):
         ("launch_stages", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
         ("score_metric", ctypes.c_int32),
+        ("budget_ratio", ctypes.c_float),
         ("num_pages", ctypes.c_int64),
         ("kv_page_stride", ctypes.c_int64),
         ("kv_token_stride", ctypes.c_int64),
@@ -90,6 +91,8 @@ def load_library(path: Optional[str] = None):
     lib.vegas_select_blocks.argtypes = [D, P, P, P, ctypes.c_int32, P, P, P, P, ctypes.c_size_t, P]
     lib.vegas_select_tokens.restype = ctypes.c_int
     lib.vegas_select_tokens.argtypes = [D, P, P, P, ctypes.c_int32, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_extend_selection.restype = ctypes.c_int
+    lib.vegas_extend_selection.argtypes = [D, P, P, ctypes.c_int32, P, P, P]
     lib.vegas_draft_attention.restype = ctypes.c_int
     lib.vegas_draft_attention.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P]
     lib.vegas_strerror.restype = ctypes.c_char_p
@@ -126,7 +129,8 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
               max_sel_blocks: int, max_seq_len: int, num_pages: int, softmax_scale: float,
               collect_rows: int = COLLECT_ALL_ROWS, head_dim: int = 128, page_size: int = 16,
               kv_chunk_tokens: int = 0, kv_page_stride: int = 0, kv_token_stride: int = 0,
-              kv_head_stride: int = 0, score_metric: int = METRIC_PAGE_WEIGHTS) -> VegasDesc:
+              kv_head_stride: int = 0, score_metric: int = METRIC_PAGE_WEIGHTS,
+              budget_ratio: float = 0.0) -> VegasDesc:
     """Descriptor for a contiguous NHD cache unless strides are given (elements)."""
     d = VegasDesc()
     d.batch, d.num_q_heads, d.num_kv_heads = batch, num_q_heads, num_kv_heads
@@ -135,6 +139,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
     d.collect_rows, d.kv_chunk_tokens, d.softmax_scale = collect_rows, kv_chunk_tokens, softmax_scale
     d.launch_stages = 0
     d.score_metric = score_metric
+    d.budget_ratio = budget_ratio
     d.num_pages = num_pages
     d.kv_head_stride = kv_head_stride or head_dim
     d.kv_token_stride = kv_token_stride or num_kv_heads * head_dim
@@ -176,6 +181,14 @@ def vegas_select_tokens(desc: VegasDesc, token_scores, block_table, seq_lens, bu
                                             _ptr(sel_seq_lens), _ptr(workspace), wb, _stream(stream))
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_select_tokens")
+
+
+def vegas_extend_selection(desc: VegasDesc, block_table, seq_lens, num_new: int, sel_table, sel_seq_lens,
+                           stream=None) -> None:
+    rc = load_library().vegas_extend_selection(ctypes.byref(desc), _ptr(block_table), _ptr(seq_lens), int(num_new),
+                                               _ptr(sel_table), _ptr(sel_seq_lens), _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_extend_selection")
 
 
 def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace,

@@ -41,8 +41,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     if (tid == 0) p.sel_seq_lens[b] = 0;
     return;
   }
-  int budget = p.budgets ? p.budgets[b] : p.budget_tokens;
-  budget = budget < 0 ? 0 : budget;
+  const int budget = sequence_budget(p.budgets, p.budget_ratio, p.budget_tokens, b, n);
   const int f0 = max(n - p.G, 0) / kPage;            // first forced page
   int nF = nblk - f0;                                // forced pages (1 or 2 for G <= 17)
   int k = min((budget + kPage - 1) / kPage, nblk);
@@ -199,6 +198,30 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
   for (int i = tid; i < nF; i += kSelectThreads) sel[kc + i] = table[nblk - nF + i];
   for (int i = k + tid; i < p.max_sel_blocks; i += kSelectThreads) sel[i] = -1;
   if (tid == 0) p.sel_seq_lens[b] = kPage * (k - 1) + (n - kPage * (nblk - 1));
+}
+
+// Adds the num_new newest token positions of every sequence to its selection (one thread per sequence):
+// a new table entry whenever a position starts a page of the selection's page size.
+__global__ void extend_selection_kernel(const ExtendParams p) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= p.batch) return;
+  const int covered = p.sel_seq_lens[b];
+  if (covered <= 0) return;
+  const int P = p.page_size;
+  const int n_new = p.seq_lens[b];
+  int32_t* sel = p.sel_table + static_cast<int64_t>(b) * p.max_sel_blocks;
+  const int32_t* table = p.block_table + static_cast<int64_t>(b) * p.max_blocks;
+  int count = (covered + P - 1) / P;
+  int added = 0;
+  for (int i = n_new - p.num_new; i < n_new; ++i) added += (i >= 0 && i % P == 0) ? 1 : 0;
+  if (count + added > p.max_sel_blocks) return;            // row full: left as it is
+  for (int i = n_new - p.num_new; i < n_new; ++i) {
+    if (i >= 0 && i % P == 0) {
+      const int page16 = min(i / kPage, p.max_blocks - 1);
+      sel[count++] = table[page16] * (kPage / P) + (i % kPage) / P;
+    }
+  }
+  p.sel_seq_lens[b] = covered + p.num_new;
 }
 
 }  // namespace vegas

@@ -30,6 +30,7 @@ struct TokenSelectParams {
   int32_t* sel_seq_lens;
   uint32_t* hist;             // [B, 4, slices, 256] digit histogram of every (pass, slice)
   int32_t budget_tokens, G, max_blocks, max_sel, max_tokens, slices;
+  float budget_ratio;         // > 0: budget = ceil(ratio * seq_len) unless per-sequence budgets are given
 };
 
 // What one sequence asks for.
@@ -44,8 +45,7 @@ __device__ __forceinline__ TokenPlan token_plan(const TokenSelectParams& p, int 
   t.n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   t.p_len = max(t.n - p.G, 0);
   t.tail = t.n - t.p_len;
-  int budget = p.budgets ? p.budgets[b] : p.budget_tokens;
-  budget = budget < 0 ? 0 : budget;
+  const int budget = sequence_budget(p.budgets, p.budget_ratio, p.budget_tokens, b, t.n);
   int k = min(budget, t.n);
   k = max(k, t.tail);
   t.k = min(k, p.max_sel);                           // device-side clamp; the host rejects this case

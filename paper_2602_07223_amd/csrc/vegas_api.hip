@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <mutex>
 #include <set>
 #include <utility>
@@ -198,6 +199,13 @@ size_t token_select_bytes(const vegas_desc* d) {
   return align_up(static_cast<size_t>(d->batch) * 4 * token_slices(d) * 256 * sizeof(uint32_t));
 }
 
+// Largest token budget a selection call can meet when no per-sequence budgets are passed: the constant,
+// or (budget_ratio > 0) the ratio applied to the longest allowed sequence, in the kernels' fp32 arithmetic.
+int64_t ratio_or_constant_budget(const vegas_desc* d, int32_t budget_tokens) {
+  if (d->budget_ratio > 0.f) return static_cast<int64_t>(std::ceil(d->budget_ratio * static_cast<float>(d->max_seq_len)));
+  return budget_tokens;
+}
+
 int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& sp, void* out, hipStream_t st) {
   CombineParams cp;
   cp.part_o = sp.part_o;
@@ -342,9 +350,10 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const
   if (!block_scores || !block_table || !seq_lens || !sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
   if (desc->num_queries <= 0 || desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
   if (!budgets) {
-    if (budget_tokens <= 0) return VEGAS_ERR_SHAPE;
+    const int64_t bt = ratio_or_constant_budget(desc, budget_tokens);
+    if (bt <= 0) return VEGAS_ERR_SHAPE;
     const int64_t max_pages = (static_cast<int64_t>(desc->max_seq_len) + kPage - 1) / kPage;
-    int64_t kmax = (static_cast<int64_t>(budget_tokens) + kPage - 1) / kPage;
+    int64_t kmax = (bt + kPage - 1) / kPage;
     const int64_t forced = (desc->num_queries + kPage - 2) / kPage + 1;   // pages G positions can touch
     if (kmax < forced) kmax = forced;
     if (kmax > max_pages) kmax = max_pages;
@@ -362,6 +371,7 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores, const
   sp.max_blocks = desc->max_blocks;
   sp.max_sel_blocks = desc->max_sel_blocks;
   sp.max_tokens = desc->max_seq_len;
+  sp.budget_ratio = desc->budget_ratio;
   const int64_t max_pages = (static_cast<int64_t>(desc->max_seq_len) + kPage - 1) / kPage;
   sp.key_cap = static_cast<int32_t>(max_pages < kSelectKeyCap ? max_pages : kSelectKeyCap);
   const size_t shm = static_cast<size_t>(sp.key_cap) * sizeof(uint32_t);
@@ -381,8 +391,9 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores, const
   if (!token_scores || !block_table || !seq_lens || !sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
   if (desc->num_queries <= 0 || desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
   if (!budgets) {
-    if (budget_tokens <= 0) return VEGAS_ERR_SHAPE;
-    int64_t kmax = budget_tokens < desc->max_seq_len ? budget_tokens : desc->max_seq_len;
+    const int64_t bt = ratio_or_constant_budget(desc, budget_tokens);
+    if (bt <= 0) return VEGAS_ERR_SHAPE;
+    int64_t kmax = bt < desc->max_seq_len ? bt : desc->max_seq_len;
     const int64_t tail = desc->num_queries < desc->max_seq_len ? desc->num_queries : desc->max_seq_len;
     if (kmax < tail) kmax = tail;
     if (desc->max_sel_blocks < kmax) return VEGAS_ERR_SHAPE;
@@ -406,10 +417,33 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores, const
   tp.max_sel = desc->max_sel_blocks;
   tp.max_tokens = desc->max_seq_len;
   tp.slices = token_slices(desc);
+  tp.budget_ratio = desc->budget_ratio;
   const dim3 grid(tp.slices, desc->batch);
   for (int pass = 0; pass < 4; ++pass)
     hipLaunchKernelGGL(token_select_hist, grid, dim3(kTokThreads), 0, st, tp, pass);
   hipLaunchKernelGGL(token_select_write, grid, dim3(kTokThreads), 0, st, tp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+int vegas_extend_selection(const vegas_desc* desc, const int32_t* block_table, const int32_t* seq_lens,
+                           int32_t num_new, int32_t* sel_table, int32_t* sel_seq_lens, void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (desc->page_size != kPage && desc->page_size != 1) return VEGAS_ERR_UNSUPPORTED;
+  if (!block_table || !seq_lens || !sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
+  if (num_new <= 0 || desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
+  ExtendParams ep;
+  ep.block_table = block_table;
+  ep.seq_lens = seq_lens;
+  ep.sel_table = sel_table;
+  ep.sel_seq_lens = sel_seq_lens;
+  ep.batch = desc->batch;
+  ep.num_new = num_new;
+  ep.max_blocks = desc->max_blocks;
+  ep.max_sel_blocks = desc->max_sel_blocks;
+  ep.page_size = desc->page_size;
+  hipLaunchKernelGGL(extend_selection_kernel, dim3((desc->batch + 63) / 64), dim3(64), 0,
+                     static_cast<hipStream_t>(hip_stream), ep);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 

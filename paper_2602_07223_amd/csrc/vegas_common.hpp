@@ -114,6 +114,21 @@ struct SelectParams {
   int32_t* sel_seq_lens;
   int32_t budget_tokens, G, max_blocks, max_sel_blocks, max_tokens;
   int32_t key_cap;          // score keys that fit the kernel's dynamic LDS
+  float budget_ratio;       // > 0: budget = ceil(ratio * seq_len) unless per-sequence budgets are given
+};
+
+// Token budget of one sequence: per-sequence value, or a sparsity ratio of its length (App. C), or the call's constant.
+__device__ __forceinline__ int sequence_budget(const int32_t* budgets, float ratio, int constant, int b, int n) {
+  int budget = budgets ? budgets[b] : (ratio > 0.f ? static_cast<int>(ceilf(ratio * static_cast<float>(n))) : constant);
+  return budget < 0 ? 0 : budget;
+}
+
+struct ExtendParams {
+  const int32_t* block_table;
+  const int32_t* seq_lens;   // lengths after the append
+  int32_t* sel_table;
+  int32_t* sel_seq_lens;
+  int32_t batch, num_new, max_blocks, max_sel_blocks, page_size;
 };
 
 }  // namespace vegas
