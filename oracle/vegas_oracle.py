@@ -107,13 +107,15 @@ def attention_weights(q_rows: np.ndarray, keys: np.ndarray, scale: float,
 
 def verify_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
                      block_table: np.ndarray, seq_lens: np.ndarray, scale: float,
-                     collect_rows: int = COLLECT_ALL_ROWS):
+                     collect_rows: int = COLLECT_ALL_ROWS, window: int = 0):
     """Full attention of the G = gamma+1 verify rows over the paged cache + page criticality.
 
     q uint16 [B, G, H_q, D]; caches uint16 [P, 16, H_kv, D]; block_table int32 [B, max_blocks];
     seq_lens int32 [B].  Returns (out float64 [B, G, H_q, D], block_scores float64 [B, max_blocks]).
     block_scores[b, j] = 1/(|R| H_q) * sum_{t in R} sum_h sum_{i in page j} w[t, h, i]; entries
-    j >= ceil(n_b/16) are 0.  With COLLECT_NONE the scores are all 0."""
+    j >= ceil(n_b/16) are 0.  With COLLECT_NONE the scores are all 0.
+    window > 0: local ("sliding window") masking for banded layers (Sec. 4 collects "after causal or
+    local masking"): the row at position pos sees keys pos - window + 1 .. pos only."""
     B, G, Hq, D = q.shape
     Hkv = k_cache.shape[2]
     g = Hq // Hkv
@@ -131,6 +133,8 @@ def verify_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
         # row t of the G verify tokens sees keys 0 .. n-G+t
         last_visible = n - G + np.arange(G)
         vis_t = pos[None, :] <= last_visible[:, None]                     # [G, n]
+        if window > 0:
+            vis_t &= pos[None, :] > (last_visible[:, None] - window)
         for hk in range(Hkv):
             K = gather_sequence(k_cache, block_table[b], n, hk)
             V = gather_sequence(v_cache, block_table[b], n, hk)

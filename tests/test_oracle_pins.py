@@ -593,3 +593,35 @@ def test_extend_selection_leaves_full_rows_and_empty_selections_alone():
     ssl = np.array([64, 0], dtype=np.int32)
     sel2, ssl2 = O.extend_selection(sel, ssl, table, np.array([65, 1], dtype=np.int32), 1, 16)
     assert np.array_equal(sel2, sel) and np.array_equal(ssl2, ssl)
+
+
+# ----------------------------------------------------------------------------------------------
+# local (sliding-window) masking of banded layers
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,G,W", [(50, 3, 8), (37, 5, 16), (64, 1, 5), (20, 4, 100)])
+def test_windowed_verify_rows_match_library_attention_with_a_band_mask(n, G, W):
+    Hq, Hkv, D = 4, 2, 32
+    c = small_case(170 + n + W, n, G, Hq, Hkv, D, scale_q=2.0)
+    out, _ = O.verify_attention(c["q"], c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"], c["scale"],
+                                O.COLLECT_NONE, window=W)
+    qpos = np.arange(n - G, n)
+    kpos = np.arange(n)
+    band = (kpos[None, :] <= qpos[:, None]) & (kpos[None, :] > qpos[:, None] - W)           # [G, n]
+    q = torch.from_numpy(c["Q"][0]).permute(1, 0, 2)[None]                                  # [1, Hq, G, D]
+    k = torch.from_numpy(c["Kd"]).permute(1, 0, 2)[None]
+    v = torch.from_numpy(c["Vd"]).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=torch.from_numpy(band), enable_gqa=True)
+    np.testing.assert_allclose(out[0], ref[0].permute(1, 0, 2).numpy(), atol=1e-12)
+    if W >= n:                                                                              # a window wider than the context is no window
+        full, _ = O.verify_attention(c["q"], c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"], c["scale"], 0)
+        assert np.array_equal(out, full)
+
+
+def test_window_of_one_returns_the_rows_own_value():
+    n, G, Hq, Hkv, D = 40, 4, 4, 2, 16
+    c = small_case(181, n, G, Hq, Hkv, D)
+    out, _ = O.verify_attention(c["q"], c["k_cache"], c["v_cache"], c["block_table"], c["seq_lens"], c["scale"], 0, window=1)
+    for t in range(G):
+        for h in range(Hq):
+            np.testing.assert_allclose(out[0, t, h], c["Vd"][n - G + t, h // (Hq // Hkv)], atol=1e-15)
