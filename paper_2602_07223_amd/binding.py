@@ -52,6 +52,7 @@ class VegasDesc(ctypes.Structure):
         ("launch_stages", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
         ("score_metric", ctypes.c_int32),
+        ("window", ctypes.c_int32),
         ("budget_ratio", ctypes.c_float),
         ("num_pages", ctypes.c_int64),
         ("kv_page_stride", ctypes.c_int64),
@@ -130,7 +131,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
               collect_rows: int = COLLECT_ALL_ROWS, head_dim: int = 128, page_size: int = 16,
               kv_chunk_tokens: int = 0, kv_page_stride: int = 0, kv_token_stride: int = 0,
               kv_head_stride: int = 0, score_metric: int = METRIC_PAGE_WEIGHTS,
-              budget_ratio: float = 0.0) -> VegasDesc:
+              budget_ratio: float = 0.0, window: int = 0) -> VegasDesc:
     """Descriptor for a contiguous NHD cache unless strides are given (elements)."""
     d = VegasDesc()
     d.batch, d.num_q_heads, d.num_kv_heads = batch, num_q_heads, num_kv_heads
@@ -140,6 +141,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
     d.launch_stages = 0
     d.score_metric = score_metric
     d.budget_ratio = budget_ratio
+    d.window = window
     d.num_pages = num_pages
     d.kv_head_stride = kv_head_stride or head_dim
     d.kv_token_stride = kv_token_stride or num_kv_heads * head_dim

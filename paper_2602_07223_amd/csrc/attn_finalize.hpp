@@ -22,9 +22,10 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
   const float* po = p.part_o + (pbase * p.R + r) * kHeadDim + tid; // stride R*128 between chunks
   const int64_t ostride = static_cast<int64_t>(p.R) * kHeadDim;
 
+  const int s_lo = first_live_chunk(n, p.G, p.window, p.chunk_tokens);   // earlier chunks were skipped (local masking)
   // pass 1: global max over chunks
   float m = -INFINITY;
-  for (int s = tid; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
+  for (int s = s_lo + tid; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
   if ((tid & 63) == 0) sred[wave] = m;
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
 
   // pass 2: weights of up to 128 chunks at a time, then the weighted sum of the partial rows
   float accv = 0.f, L = 0.f;
-  for (int s0 = 0; s0 < ns; s0 += 128) {
+  for (int s0 = s_lo; s0 < ns; s0 += 128) {
     const int cnt = min(128, ns - s0);
     float wl = 0.f;
     if (tid < cnt) {
@@ -86,22 +87,24 @@ struct RowMerge {
     __builtin_amdgcn_sched_barrier(0);     // every request leaves before the first use
   }
   // Output element: sum_s 2^(m_s - m) x_s / sum_s 2^(m_s - m) l_s over the first ns chunks; 0 if no key was visible.
-  __device__ __forceinline__ float finish(int ns) const {
+  // Chunks before s_lo were skipped by a call with local masking and hold nothing either.
+  __device__ __forceinline__ float finish(int ns, int s_lo = 0) const {
     const int lane = threadIdx.x & 63;
-    const float ms = lane < ns ? mine[0] : -INFINITY;
+    const bool live = lane >= s_lo && lane < ns;
+    const float ms = live ? mine[0] : -INFINITY;
     float m = ms;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
     const float m_use = (m == -INFINITY) ? 0.f : m;
     const float w = fast_exp2(ms - m_use);              // 0 for lanes at or past ns
-    float L = lane < ns ? w * mine[1] : 0.f;
+    float L = live ? w * mine[1] : 0.f;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) L += __shfl_xor(L, off, 64);
     float acc = 0.f;
 #pragma unroll
     for (int s = 0; s < MAXS; ++s) {
       const float ws = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), s));
-      acc += (s < ns) ? ws * x[s] : 0.f;
+      acc += (s >= s_lo && s < ns) ? ws * x[s] : 0.f;
     }
     return (L > 0.f) ? acc / L : 0.f;
   }
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombinePa
   rm.issue(p.part_ml + pbase * p.R + r, p.part_o + (pbase * p.R + r) * kHeadDim, tid, p.R, p.nsplit);
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
-  const float o = rm.finish(ns);
+  const float o = rm.finish(ns, first_live_chunk(n, p.G, p.window, p.chunk_tokens));
   const int t = r / p.g, j = r % p.g;
   p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
 }

@@ -69,9 +69,12 @@ constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffe
 // described above; 0..3 (1, 2, 4, 8-token pages: Sec. 4 drafts with one-token pages, App. D sweeps
 // 1..16) is for draft calls only: a tile then spans 32 >> PS pages, every lane looks up the page of
 // its own token, and the page ids travel one tile ahead through a small per-wave LDS ring.
-template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4>
+// LOCAL: local ("sliding window") masking of a banded layer on top of the causal mask (verification without
+// collection only); a separate instantiation so that the other variants keep their register budget.
+template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4, bool LOCAL = false>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
   static_assert(PS == 4 || (!CAUSAL && COLLECT == 0 && !NT_LOADS), "small pages: draft calls only");
+  static_assert(!LOCAL || (CAUSAL && COLLECT == 0), "local masking: verification without collection only");
   // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NB = 1;                      // one 32-row block per workgroup
@@ -129,6 +132,9 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   if (c0 >= n) return;                       // whole workgroup: nothing to do, no partial is read
   const int c1 = min(c0 + p.chunk_tokens, n);
+  // Local masking: no row sees a token before lo_min; chunks and tiles wholly before it are skipped.
+  const int lo_min = LOCAL ? max(n - p.G - p.window + 1, 0) : 0;
+  if (LOCAL && c0 / p.chunk_tokens < first_live_chunk(n, p.G, p.window, p.chunk_tokens)) return;
   const int nblk = (n + kPage - 1) / kPage;
 
   // ---- per-lane constants
@@ -329,7 +335,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       }
     }
 
-    const bool tail = (tok0 + kTile > n) || (CAUSAL && (tok0 + kTile - 1 > n - p.G));
+    const bool tail = (tok0 + kTile > n) || (CAUSAL && (tok0 + kTile - 1 > n - p.G)) ||
+                      (LOCAL && tok0 < n - p.window);               // tiles the largest lower bound cuts into
     bf16x8 pb[NB][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -337,7 +344,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int tok = tok0 + 8 * (i >> 2) + 4 * half + (i & 3);
-          if (tok > limit[nb]) st[nb][i] = -INFINITY;
+          if (tok > limit[nb] || (LOCAL && tok <= limit[nb] - p.window)) st[nb][i] = -INFINITY;
         }
       }
       float tmax = st[nb][0];
@@ -409,6 +416,15 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     int k = 0;
+    if constexpr (LOCAL) {                   // this wave's first tile that reaches lo_min
+      const int first_tile = lo_min / kTile;
+      if (first_tile > tile_first) k = (first_tile - tile_first + NW - 1) / NW;
+      if (k > 0 && k < ntiles) {             // the preloaded tile 0 is not the first one: fetch the right one
+        if (k >= 32) load_pagevec(k & ~31);
+        issue_k(k, kr);
+        issue_v(k, va);
+      }
+    }
     while (k + 2 < ntiles) {
       step(k, va, vb, yes{});
       step(k + 1, vb, va, yes{});
@@ -417,7 +433,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     if (k + 1 < ntiles) {
       step(k, va, vb, yes{});
       step(k + 1, vb, va, no{});
-    } else {
+    } else if (!LOCAL || k < ntiles) {       // (local masking may leave this wave without a tile)
       step(k, va, vb, no{});
     }
   }

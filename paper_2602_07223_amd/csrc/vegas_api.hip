@@ -156,6 +156,12 @@ int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st,
       default: break;
     }
   }
+  if constexpr (CAUSAL && COLLECT == 0) {           // banded layer: local masking on top of the causal mask
+    if (sp.window > 0) {
+      if (pl.NB == 1) return launch_one(attn_split_kernel<4, 2, true, 0, true, 4, true>, grid, dim3(256), lds, st, sp);
+      return launch_one(attn_split_kernel<4, 2, true, 0, false, 4, true>, grid, dim3(256), lds, st, sp);
+    }
+  }
   constexpr bool kVerify = CAUSAL;                  // the verification pass is the only causal caller
   if (kVerify && pl.NB == 1)                        // one reader per K/V line, read once: stream it
     return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(256), lds, st, sp);
@@ -183,6 +189,7 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->nsplit = pl.nsplit;
   sp->lse_pages = pl.lse_pages;
   sp->collect_rows = d->collect_rows;
+  sp->window = 0;
   sp->max_tokens = d->max_seq_len;
   sp->page_stride = d->kv_page_stride;
   sp->token_stride = d->kv_token_stride;
@@ -214,6 +221,7 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   cp.out = static_cast<uint16_t*>(out);
   cp.G = sp.G; cp.g = sp.g; cp.R = sp.R; cp.Hq = sp.Hq; cp.Hkv = sp.Hkv;
   cp.chunk_tokens = pl.chunk; cp.nsplit = pl.nsplit; cp.max_tokens = d->max_seq_len;
+  cp.window = sp.window;
   const dim3 grid(pl.R, sp.Hkv, d->batch);
   if (pl.nsplit <= 8)
     hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(128), 0, st, cp);
@@ -279,6 +287,9 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
 
   SplitParams sp;
   fill_split_params(desc, pl, desc->num_queries, q, k_cache, v_cache, block_table, desc->max_blocks, seq_lens, ws, &sp);
+  if (desc->window < 0) return VEGAS_ERR_SHAPE;
+  if (desc->window > 0 && collect) return VEGAS_ERR_UNSUPPORTED;   // banded layers are not sparsified: nothing to score
+  sp.window = desc->window;
   const bool do_stream = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM);
   const bool do_merge = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_MERGE);
   if (do_stream) {

@@ -78,6 +78,7 @@ struct SplitParams {
   int32_t lds_q_off;        // byte offset of the query tile inside dynamic LDS
   int32_t row_blocks;       // ceil(R / 32): 32-row blocks of one KV head, one workgroup each
   int32_t collect_rows;     // which verification rows are collected (1: all, 2: first and last)
+  int32_t window;           // > 0: local masking, a row at position pos sees keys pos - window + 1 .. pos (causal calls)
   int64_t page_stride, token_stride, head_stride, num_pages;
   float scale_log2e;
 };
@@ -88,7 +89,15 @@ struct CombineParams {
   const int32_t* lens;
   uint16_t* out;            // bf16 [B, G, Hq, D]
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
+  int32_t window;           // > 0: chunks wholly before token n - G - window + 1 were skipped and hold nothing
 };
+
+// First chunk that any row of a (windowed) verification call can see.
+__device__ __forceinline__ int first_live_chunk(int n, int G, int window, int chunk_tokens) {
+  if (window <= 0) return 0;
+  const int lo = n - G - window + 1;
+  return lo > 0 ? lo / chunk_tokens : 0;
+}
 
 struct FinalizeParams {
   const float* part_o;

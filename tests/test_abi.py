@@ -34,7 +34,7 @@ def test_desc_layout_matches_header():
     body = header[header.index("typedef struct vegas_desc {"):header.index("} vegas_desc;")]
     fields = re.findall(r"^\s*(?:int32_t|int64_t|float|void\*)\s+(\w+);", body, flags=re.M)
     assert fields == [f[0] for f in vb.VegasDesc._fields_]
-    assert ctypes.sizeof(vb.VegasDesc) == 16 * 4 + 4 * 8 + 2 * 8   # 15 x 4-byte fields + 4 bytes of padding
+    assert ctypes.sizeof(vb.VegasDesc) == 16 * 4 + 4 * 8 + 2 * 8   # 16 x 4-byte fields
 
 
 def test_workspace_bytes_is_a_pure_host_function():

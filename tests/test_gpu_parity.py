@@ -69,7 +69,7 @@ SMALL = [
     ("gamma11_g4", 1, 32, 8, 12, [2000], {}),
     ("mha_like", 1, 8, 8, 3, [900], {}),
     ("rows96", 2, 64, 8, 12, [1100, 300], {}),
-    ("rows96_big_table", 2, 64, 8, 12, [2000, 77], dict(verify_chunk=128)),   # scores finalised in two launches
+    ("rows96_big_table", 2, 64, 8, 12, [2000, 77], dict(verify_chunk=128)),   # a big (rows x chunks) table in the score role
 ]
 
 
@@ -349,3 +349,44 @@ def test_select_long_sequences(pages):
     ref_sel, ref_ssl, _ = O.select_blocks(scores, table, lens, G, budget, msb)
     assert np.array_equal(sel.cpu().numpy(), ref_sel)
     assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
+
+
+WINDOW_CASES = [
+    # name, B, Hq, Hkv, G, lens, window, verify_chunk
+    ("w128_multi_chunk", 1, 32, 8, 5, [5000], 128, 0),
+    ("w100_ragged", 3, 32, 8, 5, [700, 2049, 3], 100, 256),
+    ("w_wider_than_context", 1, 32, 8, 5, [900], 4096, 0),
+    ("w1", 1, 32, 8, 3, [333], 1, 0),
+    ("w128_group8_many_chunks", 2, 64, 8, 5, [9000, 130], 128, 128),
+    ("w37_single_row", 1, 32, 8, 1, [2100], 37, 0),
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,window,chunk", WINDOW_CASES, ids=[c[0] for c in WINDOW_CASES])
+def test_verify_with_local_masking(name, B, Hq, Hkv, G, lens, window, chunk):
+    """Banded layers (Sec. 4: logits are taken "after causal or local masking"): the row at position pos sees
+    keys pos - window + 1 .. pos; chunks and tiles before the band are skipped, so their stale partials
+    (poisoned here) must never be read."""
+    L = synth.make_random_case(seed=700 + len(name), batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=G,
+                               seq_lens=lens, logit_std=1.5, value_std=1.0, outliers=2, outlier_logit=20.0)
+    print(f"[case] window {name} W={window}", flush=True)
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=64, collect_rows=vb.COLLECT_NONE, verify_chunk=chunk)
+    path.desc_verify.window = window
+    path.workspace.fill_(0xFF)                                    # NaN bit patterns in every partial
+    path.out_verify.fill_(float("nan"))
+    path.verify(dl)
+    torch.cuda.synchronize()
+    ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale,
+                                    0, window=window)
+    U.check_out(name, path.out_verify, ref_out, U.vmax_visible(L))
+
+
+def test_local_masking_refuses_score_collection():
+    desc = vb.make_desc(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, max_blocks=64, max_sel_blocks=64,
+                        max_seq_len=1024, num_pages=64, softmax_scale=0.1, window=128)
+    z = torch.zeros(1 << 16, dtype=torch.int32, device="cuda:0")
+    ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_verify_attention(desc, z, z, z, z, z, z, z.view(torch.float32), ws)
+    assert e.value.status == vb.VEGAS_ERR_UNSUPPORTED
