@@ -16,7 +16,8 @@ launches of that kernel alone over the same rotating caches, bracketed by two HI
 launch stream) and the CPU oracle timed on the host cores as a reported baseline.
 
 Beyond the default run:
-  --workload NAME      another synthetic workload (ctx4k, ctx128k_drift, ragged16, stack32); the
+  --workload NAME      another synthetic workload (ctx4k, ctx128k_drift, ragged16, stack32, or hd64_ctx32k: the
+                       head-dimension-64 shape at 32K context); the
                        CPU baseline and the counter-derived traffic belong to the default workload only
   --extras             adds per-iteration percentiles, the warm-cache figure (one cache copy) and the
                        iteration replayed from captured HIP graphs to the same JSON line
@@ -44,6 +45,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 VERIFY_TRAFFIC_BYTES = 138_511_360   # (131385 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
 DEFAULT_WORKLOAD = "ctx32k"
 ROTATE_BYTES = 1.2e9           # rotate cache copies up to about this much K+V in total
+
+
+def all_workloads(synth):
+    return {**synth.CONFIGS, **synth.EXTRA_CONFIGS}
 
 
 def cpu_baseline(L, budget: int, workload: str, target_seconds: float = 12.0):
@@ -97,7 +102,7 @@ def sweep_collect(args, torch, vb, harness, synth) -> int:
     rows G and what is collected.  Sec. 3.3 measures that cost for an instrumented dense kernel
     (all rows against two rows); this is the same question asked of the kernel here."""
     dev = torch.device("cuda:0")
-    base_spec = synth.CONFIGS[args.workload]
+    base_spec = all_workloads(synth)[args.workload]
     stream = int(torch.cuda.current_stream(dev).cuda_stream)
     K = args.steps
     rows = []
@@ -254,8 +259,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     vb.load_library()                                   # fail loudly if the HIP library is not built
-    if args.workload not in synth.CONFIGS:
-        print(f"bench.py: unknown workload {args.workload!r}; one of {sorted(synth.CONFIGS)}", file=sys.stderr)
+    if args.workload not in all_workloads(synth):
+        print(f"bench.py: unknown workload {args.workload!r}; one of {sorted(all_workloads(synth))}", file=sys.stderr)
         return 2
     if args.sweep == "collect":
         return sweep_collect(args, torch, vb, harness, synth)
@@ -263,7 +268,7 @@ def main() -> int:
         return sweep_page_size(args, torch, vb)
 
     workload = args.workload
-    spec = synth.CONFIGS[workload]
+    spec = all_workloads(synth)[workload]
     L = synth.make_layer(spec, args.layer)
     dev = torch.device("cuda:0")
     base = harness.DeviceLayer.upload(L, dev)

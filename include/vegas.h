@@ -74,7 +74,7 @@ typedef struct vegas_desc {
   int32_t batch;           /* B: sequences */
   int32_t num_q_heads;     /* H_q */
   int32_t num_kv_heads;    /* H_kv, divides H_q */
-  int32_t head_dim;        /* 128 */
+  int32_t head_dim;        /* 128, or 64 (the 2 KB-per-token shape of App. D); anything else: VEGAS_ERR_UNSUPPORTED */
   int32_t page_size;       /* tokens per page: 16; vegas_draft_attention also takes 1, 2, 4, 8 */
   int32_t num_queries;     /* verify: G = gamma+1 rows per sequence; ignored by draft (1 row) */
   int32_t max_blocks;      /* row stride of block_table and block_scores */

@@ -4,7 +4,7 @@
 
 namespace vegas {
 
-// One workgroup of 128 threads (= head dims) per (query row, KV head, sequence): merges the
+// One workgroup of D threads (= head dims; 128 or 64) per (query row, KV head, sequence): merges the
 // chunk partials of that row with the usual max/sum bookkeeping (all in log2 units), writes the
 // bf16 output row (Eq. 1).  The per-chunk (max, sum) pairs are
 // fetched by one thread each, so the whole merge costs two dependent memory round trips.
@@ -14,29 +14,30 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
   const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
+  const int T = p.D;                                              // threads of this workgroup = head dims
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
   const float2* ml = p.part_ml + pbase * p.R + r;                 // stride R between chunks
-  const float* po = p.part_o + (pbase * p.R + r) * kHeadDim + tid; // stride R*128 between chunks
-  const int64_t ostride = static_cast<int64_t>(p.R) * kHeadDim;
+  const float* po = p.part_o + (pbase * p.R + r) * T + tid;       // stride R*D between chunks
+  const int64_t ostride = static_cast<int64_t>(p.R) * T;
 
   const int s_lo = first_live_chunk(n, p.G, p.window, p.chunk_tokens);   // earlier chunks were skipped (local masking)
   // pass 1: global max over chunks
   float m = -INFINITY;
-  for (int s = s_lo + tid; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
+  for (int s = s_lo + tid; s < ns; s += T) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
   if ((tid & 63) == 0) sred[wave] = m;
   __syncthreads();
-  m = fmaxf(sred[0], sred[1]);
+  m = T > 64 ? fmaxf(sred[0], sred[1]) : sred[0];
   const float m_use = (m == -INFINITY) ? 0.f : m;
 
-  // pass 2: weights of up to 128 chunks at a time, then the weighted sum of the partial rows
+  // pass 2: weights of up to D chunks at a time, then the weighted sum of the partial rows
   float accv = 0.f, L = 0.f;
-  for (int s0 = s_lo; s0 < ns; s0 += 128) {
-    const int cnt = min(128, ns - s0);
+  for (int s0 = s_lo; s0 < ns; s0 += T) {
+    const int cnt = min(T, ns - s0);
     float wl = 0.f;
     if (tid < cnt) {
       const float2 v = ml[static_cast<int64_t>(s0 + tid) * p.R];
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
     for (int off = 32; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 64);
     if ((tid & 63) == 0) sred[2 + wave] = wl;
     __syncthreads();
-    L += sred[2] + sred[3];
+    L += T > 64 ? sred[2] + sred[3] : sred[2];
     int s = 0;
     for (; s + 4 <= cnt; s += 4) {
       const float x0 = po[(s0 + s) * ostride], x1 = po[(s0 + s + 1) * ostride];
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
   }
   const float o = (L > 0.f) ? accv / L : 0.f;
   const int t = r / p.g, j = r % p.g;
-  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
+  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * T + tid] = float_to_bf16_bits(o);
 }
 
 // The same merge for at most MAXS (<= 64) chunks, in ONE memory round trip: the sequence length, the
@@ -74,13 +75,13 @@ struct RowMerge {
   f32x2 mine;        // (max, sum) of chunk `lane`
   float x[MAXS];     // this thread's head dim of every chunk's partial row
   // ml, po: the row's first chunk (wave-uniform); d: head dim of this thread
-  __device__ __forceinline__ void issue(const float2* ml, const float* po, int d, int R, int nsplit) {
+  __device__ __forceinline__ void issue(const float2* ml, const float* po, int d, int R, int nsplit, int D) {
     const int lane = threadIdx.x & 63;
     const unsigned char* mlb = uniform_ptr(reinterpret_cast<const unsigned char*>(ml));
     const unsigned char* pob = uniform_ptr(reinterpret_cast<const unsigned char*>(po));
     const uint32_t last = static_cast<uint32_t>(nsplit - 1);
     mine = gload<f32x2, false>(mlb, min(static_cast<uint32_t>(lane), last) * static_cast<uint32_t>(R) * 8u);
-    const uint32_t stride = static_cast<uint32_t>(R) * kHeadDim * 4u;
+    const uint32_t stride = static_cast<uint32_t>(R) * static_cast<uint32_t>(D) * 4u;
     const uint32_t off = static_cast<uint32_t>(d) * 4u;
 #pragma unroll
     for (int s = 0; s < MAXS; ++s) x[s] = gload<float, false>(pob, off + min(static_cast<uint32_t>(s), last) * stride);
@@ -111,18 +112,18 @@ struct RowMerge {
 };
 
 template <int MAXS>
-__global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombineParams p) {
+__global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombineParams p) {   // launched with D threads
   const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
   int n = p.lens[b];
   RowMerge<MAXS> rm;
-  rm.issue(p.part_ml + pbase * p.R + r, p.part_o + (pbase * p.R + r) * kHeadDim, tid, p.R, p.nsplit);
+  rm.issue(p.part_ml + pbase * p.R + r, p.part_o + (pbase * p.R + r) * p.D, tid, p.R, p.nsplit, p.D);
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const float o = rm.finish(ns, first_live_chunk(n, p.G, p.window, p.chunk_tokens));
   const int t = r / p.g, j = r % p.g;
-  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + tid] = float_to_bf16_bits(o);
+  p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * p.D + tid] = float_to_bf16_bits(o);
 }
 
 // Verification epilogue in ONE launch (a kernel boundary costs ~3 us on this GPU): workgroups
@@ -143,15 +144,16 @@ constexpr int kFinPre = 8;       // page log-sum-exps a score thread keeps in re
 // sum_h partial[b][h][i] for prefix tokens i < n_b - G (Sec. 3.3, last paragraph), 0 elsewhere.
 template <int MAXS, int METRIC = 0>
 __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizeParams p) {
-  extern __shared__ float smf[];              // role A (general path): [2][128] weights + [2][4]; role B: [Hkv*R] + [8][32] + [Hkv*R][8] pairs
+  extern __shared__ float smf[];              // role A (general path): [256 / D][D] weights + [256 / D][4]; role B: [Hkv*R] + [8][32] + [Hkv*R][8] pairs
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
   const int HR = p.Hkv * p.R;
 
   if (static_cast<int>(blockIdx.x) < p.nA) {
-    // ---- role A: rows 2*bx and 2*bx+1 of the Hkv*R rows, 128 threads (= head dims) each
-    const int sub = tid >> 7, t128 = tid & 127, wv = (tid >> 6) & 1;
-    const int rr_raw = 2 * blockIdx.x + sub;
+    // ---- role A: 256 / D consecutive rows of the Hkv*R rows, D threads (= head dims) each
+    const int T = p.D;
+    const int sub = tid / T, t128 = tid % T, wv = (tid >> 6) % (T >> 6);
+    const int rr_raw = (256 / T) * blockIdx.x + sub;
     const bool valid = rr_raw < HR;
     const int rr = valid ? rr_raw : HR - 1;
     const int h = rr / p.R, r = rr % p.R;
@@ -161,28 +163,28 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     if constexpr (MAXS > 0) {
       int n = p.lens[b];
       RowMerge<MAXS> rm;
-      rm.issue(ml, p.part_o + (pbase * p.R + r) * kHeadDim, t128, p.R, p.nsplit);
+      rm.issue(ml, p.part_o + (pbase * p.R + r) * T, t128, p.R, p.nsplit, T);
       n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
       o = rm.finish((n + p.chunk_tokens - 1) / p.chunk_tokens);
     } else {
       int n = p.lens[b];
       n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
       const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
-      const float* po = p.part_o + (pbase * p.R + r) * kHeadDim + t128;
-      float* sw = smf + sub * 128;
+      const float* po = p.part_o + (pbase * p.R + r) * T + t128;
+      float* sw = smf + sub * T;
       float* sred = smf + 256 + sub * 4;
-      const int64_t ostride = static_cast<int64_t>(p.R) * kHeadDim;
+      const int64_t ostride = static_cast<int64_t>(p.R) * T;
       float m = -INFINITY;
-      for (int s = t128; s < ns; s += 128) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
+      for (int s = t128; s < ns; s += T) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
 #pragma unroll
       for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
       if ((tid & 63) == 0) sred[wv] = m;
       __syncthreads();
-      m = fmaxf(sred[0], sred[1]);
+      m = T > 64 ? fmaxf(sred[0], sred[1]) : sred[0];
       const float m_use = (m == -INFINITY) ? 0.f : m;
       float accv = 0.f, L = 0.f;
-      for (int s0 = 0; s0 < ns; s0 += 128) {
-        const int cnt = min(128, ns - s0);
+      for (int s0 = 0; s0 < ns; s0 += T) {
+        const int cnt = min(T, ns - s0);
         float wl = 0.f;
         if (t128 < cnt) {
           const float2 v = ml[static_cast<int64_t>(s0 + t128) * p.R];
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
         for (int off = 32; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 64);
         if ((tid & 63) == 0) sred[2 + wv] = wl;
         __syncthreads();
-        L += sred[2] + sred[3];
+        L += T > 64 ? sred[2] + sred[3] : sred[2];
         int s = 0;
         for (; s + 4 <= cnt; s += 4) {
           const float x0 = po[(s0 + s) * ostride], x1 = po[(s0 + s + 1) * ostride];
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     }
     if (valid) {
       const int t = r / p.g, j = r % p.g;
-      p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + t128] = float_to_bf16_bits(o);
+      p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * T + t128] = float_to_bf16_bits(o);
     }
     return;
   }

@@ -51,9 +51,10 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-constexpr int kRowPitch = 272;   // LDS bytes per 256-byte K/Q row: the 16-byte pad spreads rows over banks
-
-constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffer (128 + pad)
+// Per head dimension D (128, or 64 for the 2 KB/token shape of App. D): a K/Q row is 2 D bytes, padded by 16 bytes in
+// LDS so that rows spread over the banks; the cross-wave merge buffer pads its rows by 4 floats.
+constexpr int row_pitch(int D) { return 2 * D + 16; }
+constexpr int red_pitch(int D) { return D + 4; }
 
 // NW: waves per workgroup; WPS: waves per SIMD the register budget is sized for (2 -> at most
 // 256 registers per lane).  One workgroup handles up to 32 query rows of one KV head.
@@ -71,13 +72,23 @@ constexpr int kRedPitch = 132;   // floats per row of the cross-wave merge buffe
 // its own token, and the page ids travel one tile ahead through a small per-wave LDS ring.
 // LOCAL: local ("sliding window") masking of a banded layer on top of the causal mask (verification without
 // collection only); a separate instantiation so that the other variants keep their register budget.
-template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4, bool LOCAL = false>
+// D: head dimension.  64 halves everything that scales with it: a 16-byte K load covers 8 token rows instead of
+// 4, the first contraction has 4 steps, the output has 2 blocks of 32, a V load is 4 bytes (2 head dims).
+template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4, bool LOCAL = false, int D = 128>
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
   static_assert(PS == 4 || (!CAUSAL && COLLECT == 0 && !NT_LOADS), "small pages: draft calls only");
   static_assert(!LOCAL || (CAUSAL && COLLECT == 0), "local masking: verification without collection only");
   // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  static_assert(D == 128 || D == 64, "head dimension");
   constexpr int NB = 1;                      // one 32-row block per workgroup
+  constexpr int CH = D / 8;                  // 16-byte chunks of a K/Q row
+  constexpr int TPI = 64 / CH;               // token rows one K load instruction covers
+  constexpr int NK = 32 / TPI;               // K load instructions per tile
+  constexpr int NBLK = D / 32;               // 32-wide blocks of the output's head dimension
+  constexpr int kRowPitch = row_pitch(D);
+  constexpr int kRedPitch = red_pitch(D);
+  using VReg = typename std::conditional<D == 128, u32x2, uint32_t>::type;   // NBLK head dims of one token
   constexpr int TP = 32 >> (PS < 4 ? PS : 0);   // pages per tile on the small-page path
   unsigned char* qlds = smem + p.lds_q_off;
   float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
@@ -139,14 +150,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 
   // ---- per-lane constants
   const int64_t head_off = static_cast<int64_t>(h) * p.head_stride;
-  const int k_tok = lane >> 4;               // K load i: token 4i + lane/16 of the tile ...
-  const int k_chunk = lane & 15;             // ... 16-byte chunk lane%16
+  const int k_tok = lane / CH;               // K load i: token TPI*i + lane/CH of the tile ...
+  const int k_chunk = lane % CH;             // ... 16-byte chunk lane%CH
   unsigned char* kst = smem + wave * (32 * kRowPitch);
 
   // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit per-lane byte offset.
   const uint32_t ts_bytes = static_cast<uint32_t>(p.token_stride) * 2u;
   const uint32_t k_lane_off = static_cast<uint32_t>(k_tok) * ts_bytes + static_cast<uint32_t>(k_chunk) * 16u;
-  const uint32_t v_lane_off = static_cast<uint32_t>(4 * half) * ts_bytes + static_cast<uint32_t>(l32) * 8u;
+  const uint32_t v_lane_off = static_cast<uint32_t>(4 * half) * ts_bytes + static_cast<uint32_t>(l32) * (2u * NBLK);
   const int tile_end = (c1 + kTile - 1) / kTile;
   auto page_base = [&](const uint16_t* cache, int ph) -> const unsigned char* {
     return uniform_ptr(reinterpret_cast<const unsigned char*>(cache + static_cast<int64_t>(ph) * p.page_stride + head_off));
@@ -160,12 +171,12 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     const int64_t el = static_cast<int64_t>(id) * p.page_stride + static_cast<int64_t>(tokin) * p.token_stride + head_off;
     return (gbytes)cache + el * 2;
   };
-  auto issue_k = [&](int k, u32x4 (&kr)[8]) {
+  auto issue_k = [&](int k, u32x4 (&kr)[NK]) {
     if constexpr (PS != 4) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
+      for (int i = 0; i < NK; ++i) {
         typedef const __attribute__((address_space(1))) u32x4* gp;
-        kr[i] = *(gp)(token_addr(p.k, k, 4 * i + k_tok) + k_chunk * 16);
+        kr[i] = *(gp)(token_addr(p.k, k, TPI * i + k_tok) + k_chunk * 16);
       }
       return;
     }
@@ -175,20 +186,20 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     const unsigned char* kb0 = page_base(p.k, ph0);
     const unsigned char* kb1 = page_base(p.k, ph1);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const unsigned char* base = ((i < 4) ? kb0 : kb1) + static_cast<uint32_t>(4 * (i & 3)) * ts_bytes;
+    for (int i = 0; i < NK; ++i) {
+      const unsigned char* base = ((TPI * i < kPage) ? kb0 : kb1) + static_cast<uint32_t>((TPI * i) & (kPage - 1)) * ts_bytes;
       kr[i] = gload<u32x4, NT_LOADS>(base, k_lane_off);
     }
   };
-  // V load (s, jj): token 16s + 8(jj/4) + 4*half + jj%4 of the tile, head dims 4*l32 .. 4*l32+3
-  auto issue_v = [&](int k, u32x2 (&vr)[16]) {
+  // V load (s, jj): token 16s + 8(jj/4) + 4*half + jj%4 of the tile, head dims NBLK*l32 .. NBLK*l32 + NBLK-1
+  auto issue_v = [&](int k, VReg (&vr)[16]) {
     if constexpr (PS != 4) {
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
-          typedef const __attribute__((address_space(1))) u32x2* gp;
-          vr[s * 8 + jj] = *(gp)(token_addr(p.v, k, 16 * s + 8 * (jj >> 2) + 4 * half + (jj & 3)) + l32 * 8);
+          typedef const __attribute__((address_space(1))) VReg* gp;
+          vr[s * 8 + jj] = *(gp)(token_addr(p.v, k, 16 * s + 8 * (jj >> 2) + 4 * half + (jj & 3)) + l32 * (2 * NBLK));
         }
       }
       return;
@@ -202,14 +213,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
         const unsigned char* base = (s ? vb1 : vb0) + static_cast<uint32_t>(8 * (jj >> 2) + (jj & 3)) * ts_bytes;
-        vr[s * 8 + jj] = gload<u32x2, NT_LOADS>(base, v_lane_off);
+        vr[s * 8 + jj] = gload<VReg, NT_LOADS>(base, v_lane_off);
       }
     }
   };
 
   // ---- first tile's loads go out before anything else
-  u32x4 kr[8];
-  u32x2 va[16], vb[16];
+  u32x4 kr[NK];
+  VReg va[16], vb[16];
   if constexpr (PS != 4) {                   // tile 0's page ids enter the ring; tile 1's are requested
     if (lane < TP) ids_lds[lane] = ids_pending;
     ids_pending = load_ids(1);
@@ -220,16 +231,16 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     issue_v(0, va);
   }
 
-  // ---- query rows -> LDS [row][16 chunks of 16 B], padded rows; rows past R are zero
+  // ---- query rows -> LDS [row][CH chunks of 16 B], padded rows; rows past R are zero
   // COLLECT == 2: the last row block carries the sum of the collected query rows in rows Rl (high part) and Rl + 1 (low part)
   const bool has_extra = COLLECT == 2 && rb == p.row_blocks - 1;
-  for (int idx = tid; idx < NB * 32 * 16; idx += NW * 64) {
-    const int row = idx >> 4, chunk = idx & 15;
+  for (int idx = tid; idx < NB * 32 * CH; idx += NW * 64) {
+    const int row = idx / CH, chunk = idx % CH;
     u32x4 raw = {0u, 0u, 0u, 0u};
     if (row < Rl) {
       const int t = (row0 + row) / p.g, j = (row0 + row) % p.g;
       raw = *reinterpret_cast<const u32x4*>(
-          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + chunk * 8);
+          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
     }
     if (has_extra && row == Rl) {
       float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -237,7 +248,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
         if (p.collect_rows != 1 && t != 0 && t != p.G - 1) continue;       // Eq. 3: first draft row and bonus row
         for (int j = 0; j < p.g; ++j) {
           const u32x4 qv = *reinterpret_cast<const u32x4*>(
-              p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * kHeadDim + chunk * 8);
+              p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] & 0xFFFFu));
@@ -270,15 +281,15 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   __syncthreads();
 
   // ---- running state: lane (row, half) keeps the row max m (same in both halves), its half's
-  //      partial sum l, and O^T accumulators acc[nb][blk][i] = O[row][4*(8(i/4) + 4half + i%4) + blk]
+  //      partial sum l, and O^T accumulators acc[nb][blk][i] = O[row][NBLK*(8(i/4) + 4half + i%4) + blk]
   float m_run[NB], l_run[NB];
-  f32x16 acc[NB][4];
+  f32x16 acc[NB][NBLK];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     m_run[nb] = -INFINITY;
     l_run[nb] = 0.f;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
+    for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[nb][blk][i] = 0.f;
   }
@@ -286,14 +297,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   // One tile: vcur holds this tile's V, vnxt receives the next tile's.
   // (has_next is a compile-time property of the call site: a prefetch under a run-time branch would
   // make the compiler's load-counter waits assume the worst case and drain the prefetch early.)
-  auto step = [&](int k, u32x2 (&vcur)[16], u32x2 (&vnxt)[16], auto has_next_tag) {
+  auto step = [&](int k, VReg (&vcur)[16], VReg (&vnxt)[16], auto has_next_tag) {
     constexpr bool has_next = decltype(has_next_tag)::value;
     const int cur = tile_first + k * NW;
     const int tok0 = cur * kTile;
-    // K: registers -> LDS tile [32 tokens][16 chunks of 16 B]; then refill the registers
+    // K: registers -> LDS tile [32 tokens][CH chunks of 16 B]; then refill the registers
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<u32x4*>(kst + (4 * i + k_tok) * kRowPitch + k_chunk * 16) = kr[i];
+    for (int i = 0; i < NK; ++i) {
+      *reinterpret_cast<u32x4*>(kst + (TPI * i + k_tok) * kRowPitch + k_chunk * 16) = kr[i];
     }
     if (has_next) {
       if constexpr (PS != 4) {               // next tile's ids -> ring; the ids after that -> on their way
@@ -311,7 +322,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 #pragma unroll
       for (int i = 0; i < 16; ++i) st[nb][i] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
+    for (int kk = 0; kk < D / 16; ++kk) {
       const int off = l32 * kRowPitch + half * 16 + kk * 32;
       const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kst + off));
 #pragma unroll
@@ -370,7 +381,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       }
       if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
+        for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc[nb][blk][i] *= alpha;
       }
@@ -386,20 +397,24 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
           const int tok = tok0 + 16 * s2 + 8 * (jj >> 2) + 4 * half + (jj & 3);
-          if (tok >= n) vcur[s2 * 8 + jj] = u32x2{0u, 0u};
+          if (tok >= n) vcur[s2 * 8 + jj] = VReg{};
         }
     }
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
 #pragma unroll
-      for (int blk = 0; blk < 4; ++blk) {
+      for (int blk = 0; blk < NBLK; ++blk) {
         u32x4 raw;
 #pragma unroll
         for (int pp = 0; pp < 4; ++pp) {
-          const u32x2 ev = vcur[s2 * 8 + 2 * pp];
-          const u32x2 od = vcur[s2 * 8 + 2 * pp + 1];
-          const unsigned lo = (blk < 2) ? ev[0] : ev[1];
-          const unsigned hi = (blk < 2) ? od[0] : od[1];
+          unsigned lo, hi;                     // the dword that holds head dim blk of two consecutive tokens
+          if constexpr (D == 128) {
+            lo = (blk < 2) ? vcur[s2 * 8 + 2 * pp][0] : vcur[s2 * 8 + 2 * pp][1];
+            hi = (blk < 2) ? vcur[s2 * 8 + 2 * pp + 1][0] : vcur[s2 * 8 + 2 * pp + 1][1];
+          } else {
+            lo = vcur[s2 * 8 + 2 * pp];
+            hi = vcur[s2 * 8 + 2 * pp + 1];
+          }
           raw[pp] = __builtin_amdgcn_perm(hi, lo, (blk & 1) ? 0x07060302u : 0x05040100u);
         }
         const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
@@ -483,17 +498,21 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       float* dst = red + (wave * Rl + row) * kRedPitch;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int d0 = 4 * (8 * (i >> 2) + 4 * half + (i & 3));
-        *reinterpret_cast<f32x4*>(dst + d0) =
-            f32x4{acc[nb][0][i] * sc, acc[nb][1][i] * sc, acc[nb][2][i] * sc, acc[nb][3][i] * sc};
+        const int d0 = NBLK * (8 * (i >> 2) + 4 * half + (i & 3));
+        if constexpr (D == 128) {
+          *reinterpret_cast<f32x4*>(dst + d0) =
+              f32x4{acc[nb][0][i] * sc, acc[nb][1][i] * sc, acc[nb][2][i] * sc, acc[nb][3][i] * sc};
+        } else {
+          *reinterpret_cast<f32x2*>(dst + d0) = f32x2{acc[nb][0][i] * sc, acc[nb][1][i] * sc};
+        }
       }
     }
   }
   __syncthreads();
   const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
-  float* po = p.part_o + (pbase * p.R + row0) * kHeadDim;
-  for (int e = tid; e < Rl * kHeadDim; e += NW * 64) {
-    const int row = e >> 7, d = e & 127;
+  float* po = p.part_o + (pbase * p.R + row0) * D;
+  for (int e = tid; e < Rl * D; e += NW * 64) {
+    const int row = e / D, d = e % D;
     float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) sum += red[(w * Rl + row) * kRedPitch + d];
@@ -511,21 +530,21 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
 }
 
 // Dynamic LDS bytes of attn_split_kernel<NW, ...> when a workgroup holds up to `rows` (<= 32) valid rows.
-inline size_t split_lds_tail_bytes(int NW) {
-  return static_cast<size_t>(32) * kRowPitch + 2 * static_cast<size_t>(NW) * 32 * sizeof(float) +
+inline size_t split_lds_tail_bytes(int NW, int D = 128) {
+  return static_cast<size_t>(32) * row_pitch(D) + 2 * static_cast<size_t>(NW) * 32 * sizeof(float) +
          static_cast<size_t>(NW) * 64 * sizeof(int);                 // queries, row maxima and sums, page-id ring
 }
 // collect 1: the chunk's page log-sum-exps (chunk pages x rows floats) sit right behind the K tiles;
 // collect 2: the chunk's token sums, high and low part (2 x chunk tokens floats).
-inline size_t split_lds_bytes(int NW, int rows, int collect = 0, int chunk_tokens = 0) {
+inline size_t split_lds_bytes(int NW, int rows, int collect = 0, int chunk_tokens = 0, int D = 128) {
   size_t park = 0;
   if (collect == 1) park = static_cast<size_t>(chunk_tokens / kPage) * rows * sizeof(float);
   if (collect == 2) park = 2 * static_cast<size_t>(chunk_tokens) * sizeof(float);
-  size_t stage = static_cast<size_t>(NW) * 32 * kRowPitch + park;
-  const size_t red = static_cast<size_t>(NW) * rows * kRedPitch * sizeof(float);
+  size_t stage = static_cast<size_t>(NW) * 32 * row_pitch(D) + park;
+  const size_t red = static_cast<size_t>(NW) * rows * red_pitch(D) * sizeof(float);
   if (red > stage) stage = red;
   stage = (stage + 15) / 16 * 16;
-  return stage + split_lds_tail_bytes(NW);
+  return stage + split_lds_tail_bytes(NW, D);
 }
 
 }  // namespace vegas

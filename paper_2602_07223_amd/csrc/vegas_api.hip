@@ -36,11 +36,11 @@ int check_common(const vegas_desc* d) {
       d->max_seq_len <= 0 || d->num_pages <= 0)
     return VEGAS_ERR_SHAPE;
   if (d->num_q_heads % d->num_kv_heads != 0) return VEGAS_ERR_SHAPE;
-  if (d->head_dim != kHeadDim) return VEGAS_ERR_UNSUPPORTED;
+  if (d->head_dim != 128 && d->head_dim != 64) return VEGAS_ERR_UNSUPPORTED;
   if (d->page_size != 1 && d->page_size != 2 && d->page_size != 4 && d->page_size != 8 && d->page_size != kPage)
     return VEGAS_ERR_UNSUPPORTED;
-  if (d->kv_head_stride < kHeadDim || d->kv_token_stride < kHeadDim ||
-      d->kv_page_stride < static_cast<int64_t>(d->page_size) * kHeadDim)
+  if (d->kv_head_stride < d->head_dim || d->kv_token_stride < d->head_dim ||
+      d->kv_page_stride < static_cast<int64_t>(d->page_size) * d->head_dim)
     return VEGAS_ERR_SHAPE;
   if ((d->kv_head_stride % 8) || (d->kv_token_stride % 8) || (d->kv_page_stride % 8)) return VEGAS_ERR_ALIGN;
   if (d->kv_chunk_tokens < 0 || (d->kv_chunk_tokens % kTile) != 0) return VEGAS_ERR_SHAPE;
@@ -85,7 +85,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   pl->lse_pages = collect == 1 ? (max_len + kPage - 1) / kPage : (collect == 2 ? pl->nsplit * chunk : 0);
   size_t off = 0;
   const size_t hs = static_cast<size_t>(heads);
-  pl->off_part_o = off;  off += align_up(hs * pl->nsplit * pl->R * kHeadDim * sizeof(float));
+  pl->off_part_o = off;  off += align_up(hs * pl->nsplit * pl->R * d->head_dim * sizeof(float));
   pl->off_part_ml = off; off += align_up(hs * pl->nsplit * pl->R * sizeof(float2));
   pl->off_page_lse = off;
   off += align_up(hs * static_cast<size_t>(pl->lse_pages) * (collect == 2 ? 1 : pl->R) * sizeof(float));
@@ -139,33 +139,39 @@ int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, con
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
-template <bool CAUSAL, int COLLECT>
-int launch_split(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size = kPage) {
+template <bool CAUSAL, int COLLECT, int D>
+int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size) {
   const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
   const int rows = pl.R < 32 ? pl.R : 32;
-  const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT, pl.chunk);
-  sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW));
+  const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT, pl.chunk, D);
+  sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW, D));
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
   if constexpr (!CAUSAL && COLLECT == 0) {              // draft calls may walk a table of smaller pages
     switch (page_size) {
-      case 1: return launch_one(attn_split_kernel<4, 2, false, false, false, 0>, grid, dim3(256), lds, st, sp);
-      case 2: return launch_one(attn_split_kernel<4, 2, false, false, false, 1>, grid, dim3(256), lds, st, sp);
-      case 4: return launch_one(attn_split_kernel<4, 2, false, false, false, 2>, grid, dim3(256), lds, st, sp);
-      case 8: return launch_one(attn_split_kernel<4, 2, false, false, false, 3>, grid, dim3(256), lds, st, sp);
+      case 1: return launch_one(attn_split_kernel<4, 2, false, 0, false, 0, false, D>, grid, dim3(256), lds, st, sp);
+      case 2: return launch_one(attn_split_kernel<4, 2, false, 0, false, 1, false, D>, grid, dim3(256), lds, st, sp);
+      case 4: return launch_one(attn_split_kernel<4, 2, false, 0, false, 2, false, D>, grid, dim3(256), lds, st, sp);
+      case 8: return launch_one(attn_split_kernel<4, 2, false, 0, false, 3, false, D>, grid, dim3(256), lds, st, sp);
       default: break;
     }
   }
   if constexpr (CAUSAL && COLLECT == 0) {           // banded layer: local masking on top of the causal mask
     if (sp.window > 0) {
-      if (pl.NB == 1) return launch_one(attn_split_kernel<4, 2, true, 0, true, 4, true>, grid, dim3(256), lds, st, sp);
-      return launch_one(attn_split_kernel<4, 2, true, 0, false, 4, true>, grid, dim3(256), lds, st, sp);
+      if (pl.NB == 1) return launch_one(attn_split_kernel<4, 2, true, 0, true, 4, true, D>, grid, dim3(256), lds, st, sp);
+      return launch_one(attn_split_kernel<4, 2, true, 0, false, 4, true, D>, grid, dim3(256), lds, st, sp);
     }
   }
   constexpr bool kVerify = CAUSAL;                  // the verification pass is the only causal caller
   if (kVerify && pl.NB == 1)                        // one reader per K/V line, read once: stream it
-    return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify>, grid, dim3(256), lds, st, sp);
-  return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, false>, grid, dim3(256), lds, st, sp);
+    return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, kVerify, 4, false, D>, grid, dim3(256), lds, st, sp);
+  return launch_one(attn_split_kernel<4, 2, CAUSAL, COLLECT, false, 4, false, D>, grid, dim3(256), lds, st, sp);
+}
+
+template <bool CAUSAL, int COLLECT>
+int launch_split(const SplitPlan& pl, const SplitParams& sp, int batch, hipStream_t st, int head_dim, int page_size = kPage) {
+  if (head_dim == 64) return launch_split_d<CAUSAL, COLLECT, 64>(pl, sp, batch, st, page_size);
+  return launch_split_d<CAUSAL, COLLECT, 128>(pl, sp, batch, st, page_size);
 }
 
 void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const void* q, const void* k,
@@ -222,27 +228,28 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   cp.G = sp.G; cp.g = sp.g; cp.R = sp.R; cp.Hq = sp.Hq; cp.Hkv = sp.Hkv;
   cp.chunk_tokens = pl.chunk; cp.nsplit = pl.nsplit; cp.max_tokens = d->max_seq_len;
   cp.window = sp.window;
+  cp.D = d->head_dim;
   const dim3 grid(pl.R, sp.Hkv, d->batch);
   if (pl.nsplit <= 8)
-    hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 12)
-    hipLaunchKernelGGL(attn_combine_small_kernel<12>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<12>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 16)
-    hipLaunchKernelGGL(attn_combine_small_kernel<16>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<16>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 20)
-    hipLaunchKernelGGL(attn_combine_small_kernel<20>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<20>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 24)
-    hipLaunchKernelGGL(attn_combine_small_kernel<24>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<24>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 32)
-    hipLaunchKernelGGL(attn_combine_small_kernel<32>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<32>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 40)
-    hipLaunchKernelGGL(attn_combine_small_kernel<40>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<40>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 48)
-    hipLaunchKernelGGL(attn_combine_small_kernel<48>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<48>, grid, dim3(cp.D), 0, st, cp);
   else if (pl.nsplit <= 64)
-    hipLaunchKernelGGL(attn_combine_small_kernel<64>, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<64>, grid, dim3(cp.D), 0, st, cp);
   else
-    hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(128), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(cp.D), 0, st, cp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
@@ -294,8 +301,10 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   const bool do_merge = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_MERGE);
   if (do_stream) {
     if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-    rc = !collect ? launch_split<true, 0>(pl, sp, desc->batch, st)
-                  : (logits ? launch_split<true, 2>(pl, sp, desc->batch, st) : launch_split<true, 1>(pl, sp, desc->batch, st));
+    const int hd = desc->head_dim;
+    rc = !collect ? launch_split<true, 0>(pl, sp, desc->batch, st, hd)
+                  : (logits ? launch_split<true, 2>(pl, sp, desc->batch, st, hd)
+                            : launch_split<true, 1>(pl, sp, desc->batch, st, hd));
     if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }
@@ -311,7 +320,9 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   fp.G = desc->num_queries; fp.g = sp.g; fp.R = pl.R; fp.Hq = sp.Hq; fp.Hkv = sp.Hkv;
   fp.chunk_tokens = pl.chunk; fp.nsplit = pl.nsplit; fp.max_tokens = desc->max_seq_len;
   fp.max_blocks = desc->max_blocks; fp.lse_pages = pl.lse_pages; fp.collect_rows = desc->collect_rows;
-  fp.nA = (sp.Hkv * pl.R + 1) / 2;
+  fp.D = desc->head_dim;
+  const int rows_per_wg = 256 / fp.D;                  // merge workgroups: 256 threads, D per row
+  fp.nA = (sp.Hkv * pl.R + rows_per_wg - 1) / rows_per_wg;
   const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries
                                                                    : (desc->num_queries > 1 ? 2 : 1);
   fp.inv_norm = 1.0f / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
@@ -326,7 +337,7 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
     fp.nC = static_cast<int>((static_cast<int64_t>(desc->max_blocks) * kPage + 1023) / 1024);
     fp.tok_norm = desc->softmax_scale / (static_cast<float>(nrows) * static_cast<float>(desc->num_q_heads));
     nB = fp.nC;
-    shm = 264 * sizeof(float);
+    shm = 272 * sizeof(float);
   }
   if (shm > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
   const dim3 fgrid(fp.nA + nB, desc->batch);
@@ -480,7 +491,7 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
   fill_split_params(desc, pl, 1, q, k_cache, v_cache, sel_table, desc->max_sel_blocks, sel_seq_lens, ws, &sp);
   if (desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM)) {
     if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
-    rc = launch_split<false, 0>(pl, sp, desc->batch, st, desc->page_size);
+    rc = launch_split<false, 0>(pl, sp, desc->batch, st, desc->head_dim, desc->page_size);
     if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }

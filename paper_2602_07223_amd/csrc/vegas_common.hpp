@@ -6,7 +6,7 @@
 namespace vegas {
 
 constexpr int kPage = 16;       // tokens per KV page
-constexpr int kHeadDim = 128;   // head dimension the kernels are written for
+constexpr int kHeadDim = 128;   // the larger of the two head dimensions (128, 64) the kernels are written for
 constexpr int kTile = 32;       // tokens per MFMA tile (two pages)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -90,6 +90,7 @@ struct CombineParams {
   uint16_t* out;            // bf16 [B, G, Hq, D]
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t window;           // > 0: chunks wholly before token n - G - window + 1 were skipped and hold nothing
+  int32_t D;                // head dimension (128 or 64) = threads per row
 };
 
 // First chunk that any row of a (windowed) verification call can see.
@@ -108,6 +109,7 @@ struct FinalizeParams {
   float* block_scores;      // [B, max_blocks]
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t max_blocks, lse_pages, collect_rows;
+  int32_t D;                // head dimension (128 or 64)
   int32_t nC;               // logit metric: workgroups that sum the token partials (1024 tokens each)
   float tok_norm;           // logit metric: softmax_scale / (collected rows * H_q)
   int32_t nA;               // workgroups that merge rows (two rows each); the rest score pages

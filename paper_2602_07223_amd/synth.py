@@ -107,6 +107,14 @@ CONFIGS: Dict[str, WorkloadSpec] = {
 }
 
 
+# Beyond the five: the second attention shape the paper evaluates (App. D: 2 KB of K+V per token; a
+# gpt-oss-20b-like layer with 64 query / 8 KV heads of dimension 64), at the context of "ctx32k".
+EXTRA_CONFIGS: Dict[str, WorkloadSpec] = {
+    "hd64_ctx32k": WorkloadSpec("hd64_ctx32k", 6, batch=1, num_q_heads=64, num_kv_heads=8, gamma=4,
+                                budget_tokens=2048, seq_len=32768, hitters=128, hitter_run=16, head_dim=64),
+}
+
+
 def scaled(spec: WorkloadSpec, **changes) -> WorkloadSpec:
     """A copy of ``spec`` with some fields replaced (reduced-size parity cases)."""
     return dataclasses.replace(spec, **changes)

@@ -41,7 +41,8 @@ def test_workspace_bytes_is_a_pure_host_function():
     n = vb.vegas_workspace_bytes(good_desc())
     assert n > 0 and n % 256 == 0
     assert vb.vegas_workspace_bytes(good_desc(max_seq_len=65536, max_blocks=4096)) > n
-    assert vb.vegas_workspace_bytes(good_desc(head_dim=64)) == 0
+    assert 0 < vb.vegas_workspace_bytes(good_desc(head_dim=64)) < n     # partial rows are half as long
+    assert vb.vegas_workspace_bytes(good_desc(head_dim=96)) == 0
     assert vb.vegas_workspace_bytes(good_desc(num_q_heads=30)) == 0
 
 
@@ -57,7 +58,7 @@ A = 4096  # a 16-byte aligned fake device address: never dereferenced because va
 @pytest.mark.parametrize("over,status", [
     (dict(batch=0), vb.VEGAS_ERR_SHAPE),
     (dict(num_q_heads=30), vb.VEGAS_ERR_SHAPE),
-    (dict(head_dim=64), vb.VEGAS_ERR_UNSUPPORTED),
+    (dict(head_dim=96), vb.VEGAS_ERR_UNSUPPORTED),
     (dict(page_size=32), vb.VEGAS_ERR_UNSUPPORTED),
     (dict(max_seq_len=32769), vb.VEGAS_ERR_SHAPE),
     (dict(num_queries=0), vb.VEGAS_ERR_SHAPE),

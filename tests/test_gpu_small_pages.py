@@ -21,7 +21,7 @@ def draft_small_pages(L, P, sel, ssl, step=0, chunk=0):
     desc = vb.make_desc(batch=B, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads, num_queries=1,
                         max_blocks=msb, max_sel_blocks=msb, max_seq_len=max(int(ssl.max()), 1),
                         num_pages=L.num_pages * (PAGE // P), softmax_scale=L.softmax_scale, page_size=P,
-                        kv_chunk_tokens=chunk)
+                        kv_chunk_tokens=chunk, head_dim=s.head_dim)
     ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     ws.fill_(0xFF)
     out = torch.full((B, s.num_q_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=dev)
