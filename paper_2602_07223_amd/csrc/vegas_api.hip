@@ -10,6 +10,7 @@
 #include <utility>
 
 #include "attn_finalize.hpp"
+#include "attn_pair.hpp"
 #include "attn_split.hpp"
 #include "select_blocks.hpp"
 #include "select_tokens.hpp"
@@ -27,6 +28,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct SplitPlan {
   int R = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;
+  bool pair = false;                 // 33..64 rows per KV head: one workgroup serves both row blocks (attn_pair_kernel)
   size_t off_part_o = 0, off_part_ml = 0, off_page_lse = 0, total = 0;
 };
 
@@ -59,24 +61,39 @@ int check_paged16(const vegas_desc* d) {
 // Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
 // max_len bounds the lengths the call may see; small problems get small workgroups.
 // collect: 0 nothing, 1 page log-sum-exps [pages x rows], 2 token sums [padded tokens] per (sequence, KV head)
-int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect, int wg_per_cu, SplitPlan* pl) {
+int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect, int wg_per_cu, SplitPlan* pl,
+               bool may_pair = false) {
   pl->R = rows_per_head;
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
   if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
-  pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks, one workgroup each
+  pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks
   pl->NW = 4;                                        // measured: 4-wave groups match or beat 8-wave groups everywhere
+  // Two row blocks: one workgroup per chunk reads K/V once for both (attn_pair_kernel) when the chunk holds an even
+  // number of tiles and its LDS fits twice into a CU; otherwise (and for 3 or 4 blocks) sibling workgroups, one
+  // per block, share an XCD's L2.
+  const size_t pair_lds_budget = 78 * 1024;
+  pl->pair = may_pair && pl->NB == 2;
+  if (pl->pair && d->kv_chunk_tokens != 0 &&
+      (d->kv_chunk_tokens % (kTile * kPairs) != 0 ||
+       pair_lds_bytes(rows_per_head, collect, d->kv_chunk_tokens, d->head_dim) > 160 * 1024))
+    pl->pair = false;
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
     // Verification: one workgroup per CU when the batch is small (at 32K context 256 equal workgroups
     // beat 512); draft calls are latency-bound and like two small workgroups per CU.  With many
     // (sequence, head) columns, shorter chunks balance ragged lengths better.
-    const int64_t columns = heads * pl->NB;
+    const int64_t columns = heads * (pl->pair ? 1 : pl->NB);
     int64_t splits = static_cast<int64_t>(kNumCU) * wg_per_cu / columns;
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
-    const int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
+    int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
+    if (pl->pair) {                                  // what is parked per chunk must leave room for two workgroups per CU
+      cap = 4096;
+      while (cap > unit && pair_lds_bytes(rows_per_head, collect, static_cast<int>(cap), d->head_dim) > pair_lds_budget)
+        cap -= unit;
+    }
     if (c > cap) c = cap;
     chunk = static_cast<int>(c);
   }
@@ -103,7 +120,7 @@ int plan_verify(const vegas_desc* d, SplitPlan* pl) {
   const int collect = d->collect_rows == 0 ? 0 : (d->score_metric == VEGAS_METRIC_TOKEN_LOGITS ? 2 : 1);
   // the logit metric needs two spare rows in the last 32-row block of a KV head
   if (collect == 2 && (R % 32 == 0 || R % 32 > 30)) return VEGAS_ERR_UNSUPPORTED;
-  return plan_split(d, R, d->max_seq_len, collect, 1, pl);
+  return plan_split(d, R, d->max_seq_len, collect, 1, pl, d->window == 0);
 }
 
 int plan_draft(const vegas_desc* d, SplitPlan* pl) {
@@ -141,6 +158,16 @@ int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, con
 
 template <bool CAUSAL, int COLLECT, int D>
 int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size) {
+  if constexpr (CAUSAL) {
+    if (pl.pair) {                                  // both row blocks from one read of K/V
+      const dim3 pgrid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
+      const size_t plds = pair_lds_bytes(pl.R, COLLECT, pl.chunk, D);
+      sp.lds_q_off = static_cast<int32_t>(plds - pair_lds_tail_bytes(D));
+      sp.row_blocks = 1;
+      if (plds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
+      return launch_one(attn_pair_kernel<COLLECT, D>, pgrid, dim3(kPairWaves * 64), plds, st, sp);
+    }
+  }
   const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
   const int rows = pl.R < 32 ? pl.R : 32;
   const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT, pl.chunk, D);

@@ -114,3 +114,11 @@ def test_other_head_dims_are_refused():
     desc = vb.make_desc(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, max_blocks=64, max_sel_blocks=64,
                         max_seq_len=1024, num_pages=64, softmax_scale=0.1, head_dim=96)
     assert vb.vegas_workspace_bytes(desc) == 0
+
+
+@pytest.mark.parametrize("chunk", [64, 192, 256, 0])
+def test_two_row_blocks_from_one_read_head_dim_64(chunk):
+    L = synth.make_random_case(seed=990 + chunk, batch=3, num_q_heads=64, num_kv_heads=8, num_queries=5,
+                               seq_lens=[1000, 2049 + 32, 31], head_dim=D, logit_std=2.0, value_std=1.0, outliers=3,
+                               outlier_logit=30.0)
+    run_chain(L, 128, verify_chunk=chunk, name=f"hd64.pair.chunk{chunk}")

@@ -390,3 +390,32 @@ def test_local_masking_refuses_score_collection():
     with pytest.raises(vb.VegasError) as e:
         vb.vegas_verify_attention(desc, z, z, z, z, z, z, z.view(torch.float32), ws)
     assert e.value.status == vb.VEGAS_ERR_UNSUPPORTED
+
+
+# 33..64 rows per KV head: one workgroup serves both 32-row blocks from one read of K/V.  The chunk sizes make
+# every pair run 1, 2, 3, 4, 5 and many steps (the stream's tail is peeled by hand), with odd and even tile
+# counts in the last chunk; a chunk of 96 tokens holds an odd number of tiles and takes the sibling-workgroup path.
+PAIR_CASES = [
+    # name, Hq, Hkv, G, lens
+    ("rows40", 64, 8, 5, [1000, 2049 + 32, 31]),
+    ("rows33", 33, 1, 1, [777, 64]),
+    ("rows64", 64, 8, 8, [1500, 640 + 17]),
+    ("rows48_g16", 32, 2, 3, [905]),
+]
+
+
+@pytest.mark.parametrize("chunk", [64, 128, 192, 256, 320, 96, 0])
+@pytest.mark.parametrize("name,Hq,Hkv,G,lens", PAIR_CASES, ids=[c[0] for c in PAIR_CASES])
+def test_two_row_blocks_from_one_read(name, Hq, Hkv, G, lens, chunk):
+    L = synth.make_random_case(seed=1200 + len(name) + chunk, batch=len(lens), num_q_heads=Hq, num_kv_heads=Hkv,
+                               num_queries=G, seq_lens=lens, logit_std=2.0, value_std=1.0, outliers=3,
+                               outlier_logit=30.0)
+    collect = vb.COLLECT_FIRST_LAST if chunk in (128, 320) else vb.COLLECT_ALL_ROWS
+    run_chain(L, 128, collect=collect, verify_chunk=chunk, name=f"pair.{name}.chunk{chunk}")
+    dl = harness.DeviceLayer.upload(L)
+    plain = harness.VegasPath.for_layer(L, budget_tokens=128, collect_rows=vb.COLLECT_NONE, verify_chunk=chunk)
+    plain.workspace.fill_(0xFF)
+    plain.verify(dl)
+    torch.cuda.synchronize()
+    ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 0)
+    U.check_out(f"pair.{name}.chunk{chunk}.collect_none", plain.out_verify, ref_out, U.vmax_visible(L))

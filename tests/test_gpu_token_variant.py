@@ -70,6 +70,8 @@ CASES = [
     ("ragged_batch", 3, 32, 8, 5, [700, 2049, 3], 256),
     ("gamma6", 1, 32, 8, 7, [5000], 512),
     ("group8_two_row_blocks", 2, 64, 8, 5, [1500, 640], 0),
+    ("group8_two_row_blocks_chunk192", 2, 64, 8, 5, [1500, 640 + 45], 192),
+    ("rows62_chunk64", 1, 62, 2, 2, [700], 64),
     ("single_row", 1, 32, 8, 1, [777], 0),
     ("mha_like", 1, 8, 8, 3, [900], 0),
 ]
