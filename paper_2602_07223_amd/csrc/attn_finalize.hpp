@@ -17,13 +17,14 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const CombineParams p
   const int T = p.D;                                              // threads of this workgroup = head dims
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-  const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
-  const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
+  const ColumnSlots cs = column_slots(p.plan, p.slots_total, b, p.Hkv, p.nsplit, p.chunk_tokens);
+  const int ns = (n + cs.chunk - 1) / cs.chunk;
+  const int64_t pbase = cs.off + static_cast<int64_t>(h) * cs.stride_h;
   const float2* ml = p.part_ml + pbase * p.R + r;                 // stride R between chunks
   const float* po = p.part_o + (pbase * p.R + r) * T + tid;       // stride R*D between chunks
   const int64_t ostride = static_cast<int64_t>(p.R) * T;
 
-  const int s_lo = first_live_chunk(n, p.G, p.window, p.chunk_tokens);   // earlier chunks were skipped (local masking)
+  const int s_lo = first_live_chunk(n, p.G, p.window, cs.chunk);   // earlier chunks were skipped (local masking)
   // pass 1: global max over chunks
   float m = -INFINITY;
   for (int s = s_lo + tid; s < ns; s += T) m = fmaxf(m, ml[static_cast<int64_t>(s) * p.R].x);
@@ -75,11 +76,12 @@ struct RowMerge {
   f32x2 mine;        // (max, sum) of chunk `lane`
   float x[MAXS];     // this thread's head dim of every chunk's partial row
   // ml, po: the row's first chunk (wave-uniform); d: head dim of this thread
-  __device__ __forceinline__ void issue(const float2* ml, const float* po, int d, int R, int nsplit, int D) {
+  // last: the largest chunk index whose slot may be read (slots past the row's chunks are loaded and discarded)
+  __device__ __forceinline__ void issue(const float2* ml, const float* po, int d, int R, int last_slot, int D) {
     const int lane = threadIdx.x & 63;
     const unsigned char* mlb = uniform_ptr(reinterpret_cast<const unsigned char*>(ml));
     const unsigned char* pob = uniform_ptr(reinterpret_cast<const unsigned char*>(po));
-    const uint32_t last = static_cast<uint32_t>(nsplit - 1);
+    const uint32_t last = static_cast<uint32_t>(last_slot);
     mine = gload<f32x2, false>(mlb, min(static_cast<uint32_t>(lane), last) * static_cast<uint32_t>(R) * 8u);
     const uint32_t stride = static_cast<uint32_t>(R) * static_cast<uint32_t>(D) * 4u;
     const uint32_t off = static_cast<uint32_t>(d) * 4u;
@@ -115,13 +117,14 @@ template <int MAXS>
 __global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombineParams p) {   // launched with D threads
   const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
-  const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
+  const ColumnSlots cs = column_slots(p.plan, p.slots_total, b, p.Hkv, p.nsplit, p.chunk_tokens);
+  const int64_t pbase = cs.off + static_cast<int64_t>(h) * cs.stride_h;
   int n = p.lens[b];
   RowMerge<MAXS> rm;
-  rm.issue(p.part_ml + pbase * p.R + r, p.part_o + (pbase * p.R + r) * p.D, tid, p.R, p.nsplit, p.D);
+  rm.issue(p.part_ml + pbase * p.R + r, p.part_o + (pbase * p.R + r) * p.D, tid, p.R, cs.last, p.D);
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-  const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
-  const float o = rm.finish(ns, first_live_chunk(n, p.G, p.window, p.chunk_tokens));
+  const int ns = (n + cs.chunk - 1) / cs.chunk;
+  const float o = rm.finish(ns, first_live_chunk(n, p.G, p.window, cs.chunk));
   const int t = r / p.g, j = r % p.g;
   p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * p.D + tid] = float_to_bf16_bits(o);
 }
@@ -148,6 +151,7 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
   const int HR = p.Hkv * p.R;
+  const ColumnSlots cs = column_slots(p.plan, p.slots_total, b, p.Hkv, p.nsplit, p.chunk_tokens);
 
   if (static_cast<int>(blockIdx.x) < p.nA) {
     // ---- role A: 256 / D consecutive rows of the Hkv*R rows, D threads (= head dims) each
@@ -157,19 +161,19 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     const bool valid = rr_raw < HR;
     const int rr = valid ? rr_raw : HR - 1;
     const int h = rr / p.R, r = rr % p.R;
-    const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit;
+    const int64_t pbase = cs.off + static_cast<int64_t>(h) * cs.stride_h;
     const float2* ml = p.part_ml + pbase * p.R + r;
     float o;
     if constexpr (MAXS > 0) {
       int n = p.lens[b];
       RowMerge<MAXS> rm;
-      rm.issue(ml, p.part_o + (pbase * p.R + r) * T, t128, p.R, p.nsplit, T);
+      rm.issue(ml, p.part_o + (pbase * p.R + r) * T, t128, p.R, cs.last, T);
       n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-      o = rm.finish((n + p.chunk_tokens - 1) / p.chunk_tokens);
+      o = rm.finish((n + cs.chunk - 1) / cs.chunk);
     } else {
       int n = p.lens[b];
       n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-      const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+      const int ns = (n + cs.chunk - 1) / cs.chunk;
       const float* po = p.part_o + (pbase * p.R + r) * T + t128;
       float* sw = smf + sub * T;
       float* sred = smf + 256 + sub * 4;
@@ -254,10 +258,10 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
       const int u = u0 + 256 * a;
       const int i = u < HR * 8 ? (u >> 3) : 0, sg = u & 7;
       const int h = i / p.R, r = i % p.R;
-      const float2* ml = p.part_ml + (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit * p.R + r;
+      const float2* ml = p.part_ml + (cs.off + static_cast<int64_t>(h) * cs.stride_h) * p.R + r;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int sidx = min(s0 + sg + 8 * q, p.nsplit - 1);
+        const int sidx = min(s0 + sg + 8 * q, cs.last);
         v[a][q] = ml[static_cast<int64_t>(sidx) * p.R];
       }
     }
@@ -277,7 +281,7 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
 
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-  const int ns = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+  const int ns = (n + cs.chunk - 1) / cs.chunk;
   const int nblk = (n + kPage - 1) / kPage;
   if (jbase >= nblk) {                                             // whole workgroup past the sequence
     if (tid < 32 && jbase + tid < p.max_blocks) out_row[jbase + tid] = 0.f;

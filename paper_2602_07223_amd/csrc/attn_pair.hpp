@@ -12,6 +12,13 @@
 //   * both waves drop their page into the pair's K and V tiles in LDS, the workgroup meets at a barrier, and both
 //     read the whole tile from there: K as the A operand of S^T = K Q^T, V as the A operand of O^T += V^T P^T
 //     (8-byte reads in the same token/lane pattern the register path uses), then a second barrier frees the tile.
+// What a step collects (the page log-sum-exps of its four pages, or the token sums of its 64 tokens) meets in a few
+// hundred bytes of LDS and leaves right after the step's closing barrier in ONE store per thread, so a chunk may be
+// arbitrarily long.  That store is unconditional and issued after the step's loads: invalid elements go to a
+// scratch word instead of being branched around, because a store under a run-time branch would make the
+// compiler's load-counter waits assume the worst and stall every step on the loads it has just issued (the
+// counter covers loads and stores in issue order).  A bulk flush of a longer LDS ring every 2048 tokens was
+// measured 15 % slower: the whole GPU drained its loads behind a synchronised burst of stores.
 // Every pair runs the same number of steps (a pair whose last tile lies past the chunk works on a fully masked
 // tile; that only happens in a sequence's last chunk because a full chunk holds an even number of tiles), and
 // every load is unconditional with clamped page ids, so the barriers are uniform and the load counter waits exact.
@@ -44,8 +51,8 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   unsigned char* qlds = smem + p.lds_q_off;
   float* sm_m = reinterpret_cast<float*>(qlds + 64 * kRowPitch);
   float* sm_l = sm_m + NP * 64;
-  float* lse_lds = reinterpret_cast<float*>(smem + NP * 2 * kTileBytes);   // COLLECT 1: [pages of the chunk][R]
-  float* tok_lds = lse_lds;                                                // COLLECT 2: [2][chunk tokens]
+  float* lse_lds = reinterpret_cast<float*>(smem + NP * 2 * kTileBytes);   // COLLECT 1: [4 pages of the step][R]
+  float* tok_lds = lse_lds;                                                // COLLECT 2: [2][64 tokens of the step]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -54,15 +61,27 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   const int half = lane >> 5;
   const int l32 = lane & 31;
   const int h = blockIdx.x % p.Hkv;
-  const int split = blockIdx.x / p.Hkv;
-  const int b = blockIdx.y;
+  int split = blockIdx.x / p.Hkv;
+  int b = blockIdx.y;
+  int chunk_tokens = p.chunk_tokens;
+  int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot
+  if (p.plan) {                              // balanced chunking: slot j of this head -> (sequence, chunk)
+    const int j = split;
+    const BalancedSlot bs = balanced_slot(p.lens, p.batch, p.max_tokens, p.slots_target, p.chunk_unit, j,
+                                          (blockIdx.x == 0 && wave == 0) ? p.plan : nullptr);
+    if (bs.b < 0) return;
+    b = bs.b;
+    split = bs.split;
+    chunk_tokens = bs.chunk;
+    pbase = static_cast<int64_t>(h) * p.slots_total + j;
+  }
   const int row0 = 32 * role;                // first query row (of this KV head) of this wave's block
   const int Rl = min(32, p.R - row0);        // valid rows in it (R > 32)
 
   // Page ids of this wave's page of the pair's next 64 tiles, one per lane, read back with readlane.  Requested
   // before the sequence length is known; indices are clamped to the table row and ids to the pool.
   const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
-  const int c0 = split * p.chunk_tokens;
+  const int c0 = split * chunk_tokens;
   const int tile0 = c0 / kTile;
   int pagevec = 0;
   auto load_pagevec = [&](int kbase) {
@@ -77,7 +96,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   if (c0 >= n) return;                       // whole workgroup: nothing to do, no partial is read
-  const int c1 = min(c0 + p.chunk_tokens, n);
+  const int c1 = min(c0 + chunk_tokens, n);
   const int nblk = (n + kPage - 1) / kPage;
   const int tile_end = (c1 + kTile - 1) / kTile;
   const int T = (tile_end - tile0 + NP - 1) / NP;      // steps of every pair (>= 1)
@@ -159,6 +178,20 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   const int limit = n - p.G + ((l32 < Rl) ? (row0 + l32) / p.g : 0);   // last visible token of this lane's row
   // (the first barrier of the first step also publishes the queries)
 
+  // ---- collection: the element of a step's collected values this thread stores (elements repeat when there are
+  //      fewer than threads: the same value goes to the same address twice), and where step 0's copy goes
+  int col_elem = 0, col_page = 0;
+  float* col_dst = p.trash;
+  if constexpr (COLLECT == 1) {
+    col_elem = tid % (4 * p.R);                // [page of the step][row]
+    col_page = col_elem / p.R;
+    col_dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0 / kPage) * p.R + col_elem;
+  }
+  if constexpr (COLLECT == 2) {
+    col_elem = tid % (kTile * NP);             // token of the step
+    col_dst = p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0 + col_elem;
+  }
+
   // ---- running state: lane (row, half) keeps the row max m (same in both halves), its half's partial sum l,
   //      and O^T accumulators acc[blk][i] = O[row][NBLK*(8(i/4) + 4half + i%4) + blk]
   float m_run = -INFINITY, l_run = 0.f;
@@ -197,7 +230,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
     if constexpr (COLLECT == 2) {
       // Columns xr and xr + 1 of block 1's S^T hold k_i . (high part) and k_i . (low part) for the tile's tokens.
       if (has_extra && (l32 == xr || l32 == xr + 1)) {
-        float* dst = tok_lds + (l32 - xr) * p.chunk_tokens + (tok0 - c0) + 4 * half;
+        float* dst = tok_lds + (l32 - xr) * (kTile * NP) + pr * kTile + 4 * half;
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4)
           *reinterpret_cast<f32x4*>(dst + 8 * i4) = f32x4{st[4 * i4], st[4 * i4 + 1], st[4 * i4 + 2], st[4 * i4 + 3]};
@@ -229,9 +262,8 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
     m_run = m_new;
     if (COLLECT == 1) {
       const float f0 = half_sum(ps0);
-      const float f1 = half_sum(ps1);
-      const int page = cur * 2 + half;                   // parked in LDS, written out in bulk at the end
-      if (l32 < Rl && page < nblk) lse_lds[(page - c0 / kPage) * p.R + row0 + l32] = m_use + fast_log2(half ? f1 : f0);
+      const float f1 = half_sum(ps1);                    // page 2 pr + half of the step
+      if (l32 < Rl) lse_lds[(2 * pr + half) * p.R + row0 + l32] = m_use + fast_log2(half ? f1 : f0);
     }
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
@@ -274,6 +306,18 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
       }
     }
     __syncthreads();                         // everybody is done with the tile: the next step may overwrite it
+    // What the step collected leaves now (nobody writes the LDS values again before the next step's first barrier,
+    // which no wave passes before every wave has read its element here).
+    if constexpr (COLLECT == 1) {
+      const bool ok = c0 / kPage + 4 * k + col_page < nblk;
+      float* dst = ok ? col_dst + static_cast<int64_t>(k) * (4 * p.R) : p.trash;
+      *dst = lse_lds[col_elem];
+    }
+    if constexpr (COLLECT == 2) {
+      const bool ok = c0 + (kTile * NP) * k + col_elem < c1;
+      float* dst = ok ? col_dst + k * (kTile * NP) : p.trash;
+      *dst = tok_lds[col_elem] + tok_lds[kTile * NP + col_elem];
+    }
   };
 
   // ---- stream the chunk: T steps, slots alternate; the last two steps issue no loads
@@ -299,18 +343,6 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
     }
   }
 
-  // ---- collected values leave in one coalesced write each (the last step's barrier has been passed)
-  if constexpr (COLLECT == 2) {
-    float* dst = p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0;
-    for (int e = tid; e < c1 - c0; e += NW * 64) dst[e] = tok_lds[e] + tok_lds[p.chunk_tokens + e];
-  }
-  if constexpr (COLLECT == 1) {
-    const int pg0 = c0 / kPage;
-    const int npg = min(nblk, (c1 + kPage - 1) / kPage) - pg0;
-    float* dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + pg0) * p.R;
-    for (int e = tid; e < npg * p.R; e += NW * 64) dst[e] = lse_lds[e];
-  }
-
   // ---- merge the two pairs, one row block after the other (the merge buffer aliases the tiles and the parked
   //      values): row maxima meet in LDS, every wave rescales, the waves of the block park their rows as
   //      [pair][row][d], all threads add the pairs and write the block's rows of the workgroup's partial.
@@ -322,7 +354,6 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   const float lsum = half_sum(l_run * sc);
   if (half == 0) sm_l[pr * 64 + row0 + l32] = lsum;
   float* red = reinterpret_cast<float*>(smem);
-  const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
 #pragma unroll 1
   for (int blk_rows = 0; blk_rows < 2; ++blk_rows) {
     const int rows = min(32, p.R - 32 * blk_rows);       // valid rows of this block
@@ -356,10 +387,10 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
 inline size_t pair_lds_tail_bytes(int D) {
   return static_cast<size_t>(64) * row_pitch(D) + 2 * static_cast<size_t>(kPairs) * 64 * sizeof(float);   // queries, row maxima and sums
 }
-inline size_t pair_lds_bytes(int R, int collect, int chunk_tokens, int D) {
-  size_t park = 0;
-  if (collect == 1) park = static_cast<size_t>(chunk_tokens / kPage) * R * sizeof(float);
-  if (collect == 2) park = 2 * static_cast<size_t>(chunk_tokens) * sizeof(float);
+inline size_t pair_lds_bytes(int R, int collect, int D) {
+  size_t park = 0;                                                         // what one step collects
+  if (collect == 1) park = static_cast<size_t>(4) * R * sizeof(float);
+  if (collect == 2) park = 2 * static_cast<size_t>(kTile * kPairs) * sizeof(float);
   size_t stage = static_cast<size_t>(kPairs) * 2 * 32 * row_pitch(D) + park;
   const size_t red = static_cast<size_t>(kPairs) * 32 * red_pitch(D) * sizeof(float);
   if (red > stage) stage = red;

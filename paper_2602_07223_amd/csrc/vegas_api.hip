@@ -29,6 +29,10 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 struct SplitPlan {
   int R = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;
   bool pair = false;                 // 33..64 rows per KV head: one workgroup serves both row blocks (attn_pair_kernel)
+  bool balanced = false;             // chunk lengths per sequence, computed on the GPU from the lengths (ragged batches)
+  int J = 0, JS = 0;                 // balanced: workgroups per KV head the lengths are apportioned to; slots held (J + B)
+  size_t off_trash = 0;              // a word for stores that must go nowhere
+  size_t off_plan = 0;               // balanced: [B] (first slot, chunk tokens)
   size_t off_part_o = 0, off_part_ml = 0, off_page_lse = 0, total = 0;
 };
 
@@ -69,14 +73,10 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks
   pl->NW = 4;                                        // measured: 4-wave groups match or beat 8-wave groups everywhere
   // Two row blocks: one workgroup per chunk reads K/V once for both (attn_pair_kernel) when the chunk holds an even
-  // number of tiles and its LDS fits twice into a CU; otherwise (and for 3 or 4 blocks) sibling workgroups, one
-  // per block, share an XCD's L2.
-  const size_t pair_lds_budget = 78 * 1024;
+  // number of tiles; otherwise (and for 3 or 4 blocks) sibling workgroups, one per block, share an XCD's L2.
   pl->pair = may_pair && pl->NB == 2;
-  if (pl->pair && d->kv_chunk_tokens != 0 &&
-      (d->kv_chunk_tokens % (kTile * kPairs) != 0 ||
-       pair_lds_bytes(rows_per_head, collect, d->kv_chunk_tokens, d->head_dim) > 160 * 1024))
-    pl->pair = false;
+  if (pl->pair && d->kv_chunk_tokens != 0 && d->kv_chunk_tokens % (kTile * kPairs) != 0) pl->pair = false;
+  if (pl->pair) wg_per_cu = 2;                       // measured on 16 x 36864 tokens, 40 rows: 512 workgroups 75 %, 256: 61 %
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
@@ -88,24 +88,41 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
-    int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
-    if (pl->pair) {                                  // what is parked per chunk must leave room for two workgroups per CU
-      cap = 4096;
-      while (cap > unit && pair_lds_bytes(rows_per_head, collect, static_cast<int>(cap), d->head_dim) > pair_lds_budget)
-        cap -= unit;
-    }
-    if (c > cap) c = cap;
+    const int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
+    if (!pl->pair && c > cap) c = cap;               // (the pair kernel parks nothing per chunk: any chunk length)
     chunk = static_cast<int>(c);
   }
+  // A batch of several sequences whose lengths the host does not know: the GPU apportions one launch wave of
+  // workgroups (two per CU) to the sequences in proportion to their lengths, so that every workgroup streams
+  // about the same number of tokens.  (A host-side chunk length cuts a ragged batch into unequal numbers of
+  // equal chunks: measured 45 % of the HBM peak on 16 sequences of 8K..64K tokens against 68 % with this.)
+  pl->balanced = pl->pair && d->kv_chunk_tokens == 0 && d->batch >= 2 && d->batch <= 64 && max_len <= (1 << 24) &&
+                 d->num_kv_heads <= 2 * kNumCU;
   pl->chunk = chunk;
   pl->nsplit = (max_len + chunk - 1) / chunk;
-  pl->lse_pages = collect == 1 ? (max_len + kPage - 1) / kPage : (collect == 2 ? pl->nsplit * chunk : 0);
+  size_t slots = static_cast<size_t>(heads) * pl->nsplit;       // chunk partials the workspace holds
+  if (pl->balanced) {
+    // workgroups per KV head: one launch wave (two per CU) without collection; with it, shorter chunks in two
+    // waves were measured faster (16 sequences of 8K..64K tokens, 40 rows: 505 us against 515 us)
+    pl->J = (collect ? 4 : 2) * kNumCU / d->num_kv_heads;
+    if (pl->J < d->batch) pl->J = d->batch;
+    pl->JS = pl->J + d->batch;
+    pl->chunk = unit;                                           // (unused: every sequence has its own)
+    pl->nsplit = pl->J;                                         // most chunks one sequence can get
+    slots = static_cast<size_t>(d->num_kv_heads) * pl->JS;
+  }
+  pl->lse_pages = collect == 1 ? (max_len + kPage - 1) / kPage
+                               : (collect == 2 ? (pl->balanced ? (max_len + unit - 1) / unit * unit : pl->nsplit * chunk) : 0);
   size_t off = 0;
   const size_t hs = static_cast<size_t>(heads);
-  pl->off_part_o = off;  off += align_up(hs * pl->nsplit * pl->R * d->head_dim * sizeof(float));
-  pl->off_part_ml = off; off += align_up(hs * pl->nsplit * pl->R * sizeof(float2));
+  pl->off_part_o = off;  off += align_up(slots * pl->R * d->head_dim * sizeof(float));
+  pl->off_part_ml = off; off += align_up(slots * pl->R * sizeof(float2));
   pl->off_page_lse = off;
   off += align_up(hs * static_cast<size_t>(pl->lse_pages) * (collect == 2 ? 1 : pl->R) * sizeof(float));
+  pl->off_plan = off;
+  if (pl->balanced) off += align_up(static_cast<size_t>(d->batch) * sizeof(int2));
+  pl->off_trash = off;
+  off += kAlign;
   pl->total = off;
   return VEGAS_OK;
 }
@@ -160,8 +177,9 @@ template <bool CAUSAL, int COLLECT, int D>
 int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size) {
   if constexpr (CAUSAL) {
     if (pl.pair) {                                  // both row blocks from one read of K/V
-      const dim3 pgrid(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
-      const size_t plds = pair_lds_bytes(pl.R, COLLECT, pl.chunk, D);
+      const dim3 pgrid = pl.balanced ? dim3(static_cast<unsigned>(sp.Hkv) * pl.JS, 1)
+                                     : dim3(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
+      const size_t plds = pair_lds_bytes(pl.R, COLLECT, D);
       sp.lds_q_off = static_cast<int32_t>(plds - pair_lds_tail_bytes(D));
       sp.row_blocks = 1;
       if (plds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
@@ -223,6 +241,12 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->lse_pages = pl.lse_pages;
   sp->collect_rows = d->collect_rows;
   sp->window = 0;
+  sp->trash = reinterpret_cast<float*>(ws + pl.off_trash);
+  sp->plan = pl.balanced ? reinterpret_cast<int2*>(ws + pl.off_plan) : nullptr;
+  sp->batch = d->batch;
+  sp->slots_target = pl.J;
+  sp->slots_total = pl.JS;
+  sp->chunk_unit = kTile * pl.NW;
   sp->max_tokens = d->max_seq_len;
   sp->page_stride = d->kv_page_stride;
   sp->token_stride = d->kv_token_stride;
@@ -256,6 +280,8 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   cp.chunk_tokens = pl.chunk; cp.nsplit = pl.nsplit; cp.max_tokens = d->max_seq_len;
   cp.window = sp.window;
   cp.D = d->head_dim;
+  cp.plan = sp.plan;
+  cp.slots_total = sp.slots_total;
   const dim3 grid(pl.R, sp.Hkv, d->batch);
   if (pl.nsplit <= 8)
     hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(cp.D), 0, st, cp);
@@ -348,6 +374,8 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   fp.chunk_tokens = pl.chunk; fp.nsplit = pl.nsplit; fp.max_tokens = desc->max_seq_len;
   fp.max_blocks = desc->max_blocks; fp.lse_pages = pl.lse_pages; fp.collect_rows = desc->collect_rows;
   fp.D = desc->head_dim;
+  fp.plan = sp.plan;
+  fp.slots_total = sp.slots_total;
   const int rows_per_wg = 256 / fp.D;                  // merge workgroups: 256 threads, D per row
   fp.nA = (sp.Hkv * pl.R + rows_per_wg - 1) / rows_per_wg;
   const int nrows = (desc->collect_rows == VEGAS_COLLECT_ALL_ROWS) ? desc->num_queries

@@ -79,6 +79,13 @@ struct SplitParams {
   int32_t row_blocks;       // ceil(R / 32): 32-row blocks of one KV head, one workgroup each
   int32_t collect_rows;     // which verification rows are collected (1: all, 2: first and last)
   int32_t window;           // > 0: local masking, a row at position pos sees keys pos - window + 1 .. pos (causal calls)
+  float* trash;             // attn_pair_kernel: a word of the workspace that takes the stores of invalid elements
+  int2* plan;               // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens) per sequence,
+                            // computed by every workgroup from the lengths and written here by workgroup 0
+  int32_t batch;            // B (balanced chunking)
+  int32_t slots_target;     // J: partial slots (= workgroups) per KV head the lengths are apportioned to
+  int32_t slots_total;      // JS = J + B: slots per KV head the workspace holds
+  int32_t chunk_unit;       // chunk lengths are multiples of this many tokens
   int64_t page_stride, token_stride, head_stride, num_pages;
   float scale_log2e;
 };
@@ -91,6 +98,8 @@ struct CombineParams {
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t window;           // > 0: chunks wholly before token n - G - window + 1 were skipped and hold nothing
   int32_t D;                // head dimension (128 or 64) = threads per row
+  const int2* plan;         // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens)
+  int32_t slots_total;      // balanced chunking: partial slots per KV head
 };
 
 // First chunk that any row of a (windowed) verification call can see.
@@ -98,6 +107,90 @@ __device__ __forceinline__ int first_live_chunk(int n, int G, int window, int ch
   if (window <= 0) return 0;
   const int lo = n - G - window + 1;
   return lo > 0 ? lo / chunk_tokens : 0;
+}
+
+// Where the chunk partials of sequence b live and how long its chunks are.  Partial slot of (KV head h, chunk s):
+// off + h * stride_h + s.  Uniform chunking: every (sequence, head) column owns nsplit slots of chunk_tokens
+// tokens.  Balanced chunking: the slots of one head are shared by all sequences, sequence b starts at plan[b].x
+// and its chunks are plan[b].y tokens long.  `last`: the largest s that still is a slot of the workspace (loads
+// of slots past a column's chunks are clamped to it and discarded).
+struct ColumnSlots {
+  int64_t off;
+  int32_t stride_h, chunk, last;
+};
+__device__ __forceinline__ ColumnSlots column_slots(const int2* plan, int slots_total, int b, int Hkv, int nsplit,
+                                                    int chunk_tokens) {
+  ColumnSlots c;
+  if (plan) {
+    const int2 e = plan[b];
+    c.off = e.x;
+    c.stride_h = slots_total;
+    c.chunk = e.y > 0 ? e.y : 1;
+    c.last = slots_total - 1 - e.x;
+  } else {
+    c.off = static_cast<int64_t>(b) * Hkv * nsplit;
+    c.stride_h = nsplit;
+    c.chunk = chunk_tokens;
+    c.last = nsplit - 1;
+  }
+  return c;
+}
+
+// Balanced chunking of a ragged batch (B <= 64 sequences, lengths <= 2^24), computed identically by every wave
+// that calls it.  The J >= B slots of a KV head go to the sequences so that the longest chunk is as short as
+// possible: with C the smallest chunk length for which sum_b ceil(n_b / C) <= J, sequence b is cut into
+// s_b = ceil(n_b / C) equal chunks (rounded up to `unit` tokens), and slot j maps to chunk j - P_b of the sequence
+// whose slot range [P_b, P_b + s_b) holds it.  With as many workgroups as the GPU runs at once, every workgroup then streams
+// about the same number of tokens in ONE launch wave, however ragged the batch is.
+struct BalancedSlot {
+  int32_t b, split, chunk;      // b < 0: slot j is not used
+};
+__device__ __forceinline__ BalancedSlot balanced_slot(const int32_t* lens, int B, int max_tokens, int J, int unit, int j,
+                                                      int2* plan_out) {
+  const int lane = threadIdx.x & 63;
+  uint32_t n = 0u;
+  if (lane < B) {
+    const int v = lens[lane];
+    n = static_cast<uint32_t>(v < 0 ? 0 : (v > max_tokens ? max_tokens : v));
+  }
+  uint32_t N = n;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) N += __shfl_xor(N, off, 64);
+  BalancedSlot r;
+  r.b = -1; r.split = 0; r.chunk = unit;
+  if (N == 0u) {
+    if (plan_out && lane < B) plan_out[lane] = make_int2(0, unit);
+    return r;
+  }
+  // Smallest chunk length C (in units) for which sum_b ceil(n_b / C) <= J: bisection, 18 rounds cover 2^24 tokens.
+  const uint32_t nu = (n + unit - 1u) / unit;                   // length in units
+  uint32_t lo = 1u, hi = nu;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) hi = max(hi, static_cast<uint32_t>(__shfl_xor(hi, off, 64)));
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    uint32_t cnt = (nu + mid - 1u) / mid;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+    if (cnt <= static_cast<uint32_t>(J)) hi = mid; else lo = mid + 1u;
+  }
+  const uint32_t s = (nu + lo - 1u) / lo;                       // chunks of this sequence (0 if empty)
+  const int chunk = s > 0u ? static_cast<int>((nu + s - 1u) / s * unit) : unit;   // equal chunks, at most C
+  uint32_t incl = s;                                            // inclusive prefix sum over lanes
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += o;
+  }
+  const int P = static_cast<int>(incl - s);
+  if (plan_out && lane < B) plan_out[lane] = make_int2(P, chunk);
+  const uint64_t hit = __builtin_amdgcn_ballot_w64(lane < B && s > 0u && j >= P && j < P + static_cast<int>(s));
+  if (hit == 0ull) return r;
+  const int b = __builtin_ctzll(hit);
+  r.b = b;
+  r.split = j - __shfl(P, b, 64);
+  r.chunk = __shfl(chunk, b, 64);
+  return r;
 }
 
 struct FinalizeParams {
@@ -110,6 +203,8 @@ struct FinalizeParams {
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t max_blocks, lse_pages, collect_rows;
   int32_t D;                // head dimension (128 or 64)
+  const int2* plan;         // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens)
+  int32_t slots_total;      // balanced chunking: partial slots per KV head
   int32_t nC;               // logit metric: workgroups that sum the token partials (1024 tokens each)
   float tok_norm;           // logit metric: softmax_scale / (collected rows * H_q)
   int32_t nA;               // workgroups that merge rows (two rows each); the rest score pages

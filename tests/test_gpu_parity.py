@@ -419,3 +419,40 @@ def test_two_row_blocks_from_one_read(name, Hq, Hkv, G, lens, chunk):
     torch.cuda.synchronize()
     ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 0)
     U.check_out(f"pair.{name}.chunk{chunk}.collect_none", plain.out_verify, ref_out, U.vmax_visible(L))
+
+
+@pytest.mark.parametrize("chunk,lens", [(4096, [9000, 4100]), (8192, [8192 + 77]), (2176, [6000])],
+                         ids=["chunk4096", "chunk8192", "chunk2176"])
+def test_long_chunks_flush_collected_values_in_rings(chunk, lens):
+    """Chunks longer than the LDS ring that parks the page log-sum-exps: the ring is written out whenever it is
+    full (every 2048 tokens) and once more at the end of the chunk."""
+    L = synth.make_random_case(seed=1300 + chunk, batch=len(lens), num_q_heads=64, num_kv_heads=8, num_queries=5,
+                               seq_lens=lens, logit_std=2.0, value_std=1.0, outliers=3, outlier_logit=30.0)
+    run_chain(L, 512, verify_chunk=chunk, name=f"pair.ring.chunk{chunk}")
+
+
+BALANCED_CASES = [
+    # name, G, lens  (64 query / 8 KV heads: 8 G rows per KV head; no chunk length given, so the GPU plans the chunks)
+    ("empty_and_tiny_members", 5, [3000, 0, 17, 900]),
+    ("one_long_many_short", 5, [20000, 33, 5, 64, 2]),
+    ("all_empty_but_one", 6, [0, 0, 4097, 0]),
+    ("all_empty", 5, [0, 0]),
+    ("sixty_four_sequences", 5, [1 + (37 * i * i + 11 * i) % 700 for i in range(64)]),
+    ("equal_lengths", 8, [4096, 4096, 4096]),
+]
+
+
+@pytest.mark.parametrize("name,G,lens", BALANCED_CASES, ids=[c[0] for c in BALANCED_CASES])
+def test_balanced_chunking_of_ragged_batches(name, G, lens):
+    """Several sequences, two row blocks, no chunk length from the caller: the kernels apportion one launch wave of
+    workgroups to the sequences by length (every workgroup computes the same plan from seq_lens)."""
+    L = synth.make_random_case(seed=1400 + len(name), batch=len(lens), num_q_heads=64, num_kv_heads=8, num_queries=G,
+                               seq_lens=lens, logit_std=2.0, value_std=1.0, outliers=2, outlier_logit=25.0)
+    run_chain(L, 256, name=f"balanced.{name}")
+    dl = harness.DeviceLayer.upload(L)
+    plain = harness.VegasPath.for_layer(L, budget_tokens=256, collect_rows=vb.COLLECT_NONE)
+    plain.workspace.fill_(0xFF)
+    plain.verify(dl)
+    torch.cuda.synchronize()
+    ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 0)
+    U.check_out(f"balanced.{name}.collect_none", plain.out_verify, ref_out, U.vmax_visible(L))

@@ -72,6 +72,7 @@ CASES = [
     ("group8_two_row_blocks", 2, 64, 8, 5, [1500, 640], 0),
     ("group8_two_row_blocks_chunk192", 2, 64, 8, 5, [1500, 640 + 45], 192),
     ("rows62_chunk64", 1, 62, 2, 2, [700], 64),
+    ("group8_long_chunk_rings", 2, 64, 8, 5, [9000, 4100], 4096),
     ("single_row", 1, 32, 8, 1, [777], 0),
     ("mha_like", 1, 8, 8, 3, [900], 0),
 ]
