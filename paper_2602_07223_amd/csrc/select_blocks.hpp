@@ -23,7 +23,7 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const SelectParams p) {
   extern __shared__ uint32_t skeys[];                 // [min(prefix pages, key_cap)]
   __shared__ uint32_t hist[kSelectThreads / 64][256];   // one digit histogram per wave: no cross-wave contention
-  __shared__ uint32_t sh_prefix, sh_need;
+  __shared__ uint32_t sh_prefix, sh_need, sh_count;
   __shared__ uint32_t wave_take[kSelectThreads / 64], wave_eq[kSelectThreads / 64];
 
   const int b = blockIdx.x;
@@ -32,6 +32,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
   int32_t* sel = p.sel_table + static_cast<int64_t>(b) * p.max_sel_blocks;
   const int32_t* table = p.block_table + static_cast<int64_t>(b) * p.max_blocks;
   const float* scores = p.block_scores + static_cast<int64_t>(b) * p.max_blocks;
+
+  // With at most 4096 pages per row the scores are requested before the sequence length is known (one memory
+  // round trip less): every index below max_blocks is a valid address, what lies past the prefix is dropped.
+  constexpr int kPre = 4;
+  const bool prefetched = p.max_blocks <= kPre * kSelectThreads;
+  float pre[kPre];
+  if (prefetched) {
+#pragma unroll
+    for (int i = 0; i < kPre; ++i) pre[i] = scores[min(tid + i * kSelectThreads, p.max_blocks - 1)];
+  }
 
   int n = p.seq_lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
@@ -54,13 +64,22 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
 
   // ---- keys of the prefix scores go to LDS once
   const bool in_lds = f0 <= p.key_cap;
-  if (need_search && in_lds)
-    for (int j = tid; j < f0; j += kSelectThreads) skeys[j] = score_key(scores[j]);
+  if (need_search && in_lds) {
+    if (prefetched) {
+#pragma unroll
+      for (int i = 0; i < kPre; ++i)
+        if (tid + i * kSelectThreads < f0) skeys[tid + i * kSelectThreads] = score_key(pre[i]);
+    } else {
+      for (int j = tid; j < f0; j += kSelectThreads) skeys[j] = score_key(scores[j]);
+    }
+  }
   __syncthreads();
   auto key_at = [&](int j) -> uint32_t { return in_lds ? skeys[j] : score_key(scores[j]); };
 
-  // ---- radix select: key of the kc-th largest prefix score, and how many of its ties to take
-  uint32_t T = 0u, need_eq = 0u;
+  // ---- radix select: key of the kc-th largest prefix score, and how many of its ties to take.  The search stops
+  //      as soon as the digit bin that holds the kc-th key is needed whole (distinct scores: after three passes
+  //      as a rule): T then is a key PREFIX, kmask its resolved bits, and every key with that prefix is a "tie".
+  uint32_t T = 0u, need_eq = 0u, kmask = 0xFFFFFFFFu;
   if (need_search) {
     uint32_t prefix = 0u, mask = 0u, need = static_cast<uint32_t>(kc);
 #pragma unroll 1
@@ -113,6 +132,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
           if (above < need && need <= above + c[i]) {
             sh_prefix = prefix | (static_cast<uint32_t>(4 * lane + i) << shift);
             sh_need = need - above;
+            sh_count = c[i];
           }
           above += c[i];
         }
@@ -121,9 +141,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       prefix = sh_prefix;
       need = sh_need;
       mask |= 255u << shift;
+      if (sh_count == need) break;           // the whole bin is taken: its lower digits do not matter
     }
     T = prefix;
     need_eq = need;
+    kmask = mask;
   }
 
   // ---- ordered compaction of the prefix: wave w owns the contiguous pages [w*span, (w+1)*span) and
@@ -140,7 +162,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     if (!take_all)
       for (int base = w0; base < w1; base += 64) {
         const int j = base + lane;
-        const bool eq = j < w1 && key_at(j) == T;
+        const bool eq = j < w1 && (key_at(j) & kmask) == T;
         eq_wave += __popcll(__builtin_amdgcn_ballot_w64(eq));
       }
     if (lane == 0) wave_eq[wave] = eq_wave;
@@ -155,7 +177,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       if (!take_all) {
         bool eq = false, gt = false;
         if (j < w1) {
-          const uint32_t key = key_at(j);
+          const uint32_t key = key_at(j) & kmask;
           eq = key == T;
           gt = key > T;
         }
@@ -177,7 +199,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       if (!take_all) {
         bool eq = false, gt = false;
         if (j < w1) {
-          const uint32_t key = key_at(j);
+          const uint32_t key = key_at(j) & kmask;
           eq = key == T;
           gt = key > T;
         }
