@@ -76,7 +76,6 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   // number of tiles; otherwise (and for 3 or 4 blocks) sibling workgroups, one per block, share an XCD's L2.
   pl->pair = may_pair && pl->NB == 2;
   if (pl->pair && d->kv_chunk_tokens != 0 && d->kv_chunk_tokens % (kTile * kPairs) != 0) pl->pair = false;
-  if (pl->pair) wg_per_cu = 2;                       // measured on 16 x 36864 tokens, 40 rows: 512 workgroups 75 %, 256: 61 %
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (chunk == 0) {
@@ -88,8 +87,15 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
+    // What a workgroup collects is parked in LDS until its chunk ends, so a chunk cannot be arbitrarily long.  A
+    // chunk that gives every CU exactly one workgroup is taken as it is while its LDS fits (batch 4 x 64K tokens:
+    // 256 chunks of 8192 tokens reach 78 % of the HBM peak, 512 chunks of 4096 tokens 75 %); otherwise chunks are
+    // capped so that two workgroups fit a CU.  (The pair kernel parks nothing per chunk: any chunk length.)
     const int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
-    if (!pl->pair && c > cap) c = cap;               // (the pair kernel parks nothing per chunk: any chunk length)
+    const int prows = rows_per_head < 32 ? rows_per_head : 32;
+    const bool fits_alone = columns * splits >= kNumCU / 2 &&
+                            split_lds_bytes(pl->NW, prows, collect, static_cast<int>(c), d->head_dim) <= 150 * 1024;
+    if (!pl->pair && c > cap && !(wg_per_cu == 1 && fits_alone)) c = cap;
     chunk = static_cast<int>(c);
   }
   // A batch of several sequences whose lengths the host does not know: the GPU apportions one launch wave of
