@@ -319,7 +319,9 @@ def main() -> int:
         return e0.elapsed_ms(e1) / reps * 1e3
 
     traffic = VERIFY_TRAFFIC_BYTES if workload == DEFAULT_WORKLOAD and args.verify_chunk == 0 and not token else None
-    roofline = {"bound": "hbm", "kernel": "attn_split_kernel<causal, collect> (KV-streaming kernel of vegas_verify_attention)",
+    rows_per_kv_head = G * (spec.num_q_heads // spec.num_kv_heads)
+    vkernel = "attn_pair_kernel<collect>" if 32 < rows_per_kv_head <= 64 else "attn_split_kernel<causal, collect>"
+    roofline = {"bound": "hbm", "kernel": vkernel + " (KV-streaming kernel of vegas_verify_attention)",
                 "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": traffic,
                 "bytes_per_launch": verify_bytes}
     roofline_draft = None
