@@ -268,14 +268,15 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   };
   // The first batch, and (with few rows) this thread's page log-sum-exps, are
   // requested before the sequence length is needed.
-  const bool pre_ok = (p.R & 3) == 0 && p.R <= 4 * kFinPre && p.Hkv <= 8;
+  const int Rc = p.Rc;                        // collected rows per KV head: the only ones that were written
+  const bool pre_ok = (Rc & 3) == 0 && Rc <= 4 * kFinPre && p.Hkv <= 8;
   f32x4 pre[kFinPre];
   const int jpre = min(jbase + pg, p.lse_pages - 1);
   if (pre_ok && slot < p.Hkv) {
-    const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + slot) * p.lse_pages + jpre) * p.R;
+    const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + slot) * p.lse_pages + jpre) * Rc;
 #pragma unroll
     for (int q = 0; q < kFinPre; ++q)
-      if (4 * q < p.R) pre[q] = *reinterpret_cast<const f32x4*>(pl + 4 * q);
+      if (4 * q < Rc) pre[q] = *reinterpret_cast<const f32x4*>(pl + 4 * q);
   }
   load_units(0, tid);
 
@@ -314,20 +315,19 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     }
   }
   __syncthreads();
-  for (int i = tid; i < HR; i += 256) {
-    const int t = (i % p.R) / p.g;
-    const bool use = (p.collect_rows == 1) || (t == 0) || (t == p.G - 1);
+  for (int i = tid; i < p.Hkv * Rc; i += 256) {           // sm_row: [Hkv][Rc], the collected rows only
+    const int src = (i / Rc) * p.R + collected_row(i % Rc, p.collect_rows, p.G, p.g);
     float m = -INFINITY;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) m = fmaxf(m, sm_pair[i * 8 + q].x);
+    for (int q = 0; q < 8; ++q) m = fmaxf(m, sm_pair[src * 8 + q].x);
     const float m_use = (m == -INFINITY) ? 0.f : m;
     float L = 0.f;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const float2 pr = sm_pair[i * 8 + q];
+      const float2 pr = sm_pair[src * 8 + q];
       L += fast_exp2(pr.x - m_use) * pr.y;
     }
-    sm_row[i] = (use && L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
+    sm_row[i] = (L > 0.f) ? m_use + fast_log2(L) : -INFINITY;
   }
   __syncthreads();
   {
@@ -336,10 +336,10 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     if (j < nblk) {
       if (pre_ok) {
         if (slot < p.Hkv) {
-          const float* rl = sm_row + slot * p.R;
+          const float* rl = sm_row + slot * Rc;
 #pragma unroll
           for (int q = 0; q < kFinPre; ++q) {
-            if (4 * q < p.R) {
+            if (4 * q < Rc) {
 #pragma unroll
               for (int e = 0; e < 4; ++e)
                 if (rl[4 * q + e] != -INFINITY) sc += fast_exp2(pre[q][e] - rl[4 * q + e]);
@@ -348,17 +348,17 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
         }
       } else {
         for (int h = slot; h < p.Hkv; h += 8) {
-          const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * p.R;
-          const float* rl = sm_row + h * p.R;
-          if ((p.R & 3) == 0) {
-            for (int r = 0; r < p.R; r += 4) {
+          const float* pl = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + j) * Rc;
+          const float* rl = sm_row + h * Rc;
+          if ((Rc & 3) == 0) {
+            for (int r = 0; r < Rc; r += 4) {
               const f32x4 x = *reinterpret_cast<const f32x4*>(pl + r);
 #pragma unroll
               for (int q = 0; q < 4; ++q)
                 if (rl[r + q] != -INFINITY) sc += fast_exp2(x[q] - rl[r + q]);
             }
           } else {
-            for (int r = 0; r < p.R; ++r)
+            for (int r = 0; r < Rc; ++r)
               if (rl[r] != -INFINITY) sc += fast_exp2(pl[r] - rl[r]);
           }
         }

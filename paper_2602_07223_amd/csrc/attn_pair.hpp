@@ -12,7 +12,7 @@
 //   * both waves drop their page into the pair's K and V tiles in LDS, the workgroup meets at a barrier, and both
 //     read the whole tile from there: K as the A operand of S^T = K Q^T, V as the A operand of O^T += V^T P^T
 //     (8-byte reads in the same token/lane pattern the register path uses), then a second barrier frees the tile.
-// What a step collects (the page log-sum-exps of its four pages, or the token sums of its 64 tokens) meets in a few
+// What a step collects (the page log-sum-exps of its four pages for the collected rows, or the token sums of its 64 tokens) meets in a few
 // hundred bytes of LDS and leaves right after the step's closing barrier in ONE store per thread, so a chunk may be
 // arbitrarily long.  That store is unconditional and issued after the step's loads: invalid elements go to a
 // scratch word instead of being branched around, because a store under a run-time branch would make the
@@ -183,9 +183,10 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   int col_elem = 0, col_page = 0;
   float* col_dst = p.trash;
   if constexpr (COLLECT == 1) {
-    col_elem = tid % (4 * p.R);                // [page of the step][row]
-    col_page = col_elem / p.R;
-    col_dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0 / kPage) * p.R + col_elem;
+    const int e = tid % (4 * p.Rc);            // [page of the step][collected row]
+    col_page = e / p.Rc;
+    col_elem = col_page * p.R + collected_row(e % p.Rc, p.collect_rows, p.G, p.g);   // where it sits in LDS
+    col_dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0 / kPage) * p.Rc + e;
   }
   if constexpr (COLLECT == 2) {
     col_elem = tid % (kTile * NP);             // token of the step
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
     // which no wave passes before every wave has read its element here).
     if constexpr (COLLECT == 1) {
       const bool ok = c0 / kPage + 4 * k + col_page < nblk;
-      float* dst = ok ? col_dst + static_cast<int64_t>(k) * (4 * p.R) : p.trash;
+      float* dst = ok ? col_dst + static_cast<int64_t>(k) * (4 * p.Rc) : p.trash;
       *dst = lse_lds[col_elem];
     }
     if constexpr (COLLECT == 2) {

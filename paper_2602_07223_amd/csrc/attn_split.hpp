@@ -475,11 +475,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     // streaming loop costs ~14 % of the kernel: small scattered writes disturb the read stream).
     const int pg0 = c0 / kPage;
     const int npg = min(nblk, (c1 + kPage - 1) / kPage) - pg0;
-    float* dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + pg0) * p.R + row0;
-    if (Rl == p.R) {
+    float* dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + pg0) * p.Rc;
+    if (Rl == p.R && p.Rc == p.R) {
       for (int e = tid; e < npg * Rl; e += NW * 64) dst[e] = lse_lds[e];
-    } else {
-      for (int e = tid; e < npg * Rl; e += NW * 64) dst[(e / Rl) * p.R + (e % Rl)] = lse_lds[e];
+    } else {                                 // only the collected rows, and of those the ones in this row block
+      for (int e = tid; e < npg * p.Rc; e += NW * 64) {
+        const int r = collected_row(e % p.Rc, p.collect_rows, p.G, p.g) - row0;
+        if (r >= 0 && r < Rl) dst[e] = lse_lds[(e / p.Rc) * Rl + r];
+      }
     }
     __syncthreads();
   }

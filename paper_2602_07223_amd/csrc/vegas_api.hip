@@ -27,7 +27,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct SplitPlan {
-  int R = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;
+  int R = 0, Rc = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;   // Rc: collected rows per KV head
   bool pair = false;                 // 33..64 rows per KV head: one workgroup serves both row blocks (attn_pair_kernel)
   bool balanced = false;             // chunk lengths per sequence, computed on the GPU from the lengths (ragged batches)
   int J = 0, JS = 0;                 // balanced: workgroups per KV head the lengths are apportioned to; slots held (J + B)
@@ -124,7 +124,8 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   pl->off_part_o = off;  off += align_up(slots * pl->R * d->head_dim * sizeof(float));
   pl->off_part_ml = off; off += align_up(slots * pl->R * sizeof(float2));
   pl->off_page_lse = off;
-  off += align_up(hs * static_cast<size_t>(pl->lse_pages) * (collect == 2 ? 1 : pl->R) * sizeof(float));
+  pl->Rc = collected_count(d->collect_rows, d->num_queries, d->num_q_heads / d->num_kv_heads);
+  off += align_up(hs * static_cast<size_t>(pl->lse_pages) * (collect == 2 ? 1 : pl->Rc) * sizeof(float));
   pl->off_plan = off;
   if (pl->balanced) off += align_up(static_cast<size_t>(d->batch) * sizeof(int2));
   pl->off_trash = off;
@@ -246,6 +247,7 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->nsplit = pl.nsplit;
   sp->lse_pages = pl.lse_pages;
   sp->collect_rows = d->collect_rows;
+  sp->Rc = pl.Rc;
   sp->window = 0;
   sp->trash = reinterpret_cast<float*>(ws + pl.off_trash);
   sp->plan = pl.balanced ? reinterpret_cast<int2*>(ws + pl.off_plan) : nullptr;
@@ -379,6 +381,7 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   fp.G = desc->num_queries; fp.g = sp.g; fp.R = pl.R; fp.Hq = sp.Hq; fp.Hkv = sp.Hkv;
   fp.chunk_tokens = pl.chunk; fp.nsplit = pl.nsplit; fp.max_tokens = desc->max_seq_len;
   fp.max_blocks = desc->max_blocks; fp.lse_pages = pl.lse_pages; fp.collect_rows = desc->collect_rows;
+  fp.Rc = pl.Rc;
   fp.D = desc->head_dim;
   fp.plan = sp.plan;
   fp.slots_total = sp.slots_total;

@@ -70,14 +70,16 @@ struct SplitParams {
   const int32_t* lens;      // [B] valid tokens
   float* part_o;            // [B, Hkv, nsplit, R, D] un-normalised partial outputs
   float2* part_ml;          // [B, Hkv, nsplit, R]    (running max in log2 units, partial sum)
-  float* page_lse;          // [B, Hkv, lse_pages, R] log2-sum-exp2 of each page's scaled logits; or, for the
-                            // logit metric, [B, Hkv, lse_pages] per-token sums of the collected rows' q . k
+  float* page_lse;          // [B, Hkv, lse_pages, Rc] log2-sum-exp2 of each page's scaled logits for the Rc collected
+                            // rows of a KV head; or, for the logit metric, [B, Hkv, lse_pages] per-token sums of
+                            // the collected rows' q . k
   int32_t table_stride;
   int32_t G, g, R, Hq, Hkv;
   int32_t chunk_tokens, nsplit, lse_pages, max_tokens;
   int32_t lds_q_off;        // byte offset of the query tile inside dynamic LDS
   int32_t row_blocks;       // ceil(R / 32): 32-row blocks of one KV head, one workgroup each
   int32_t collect_rows;     // which verification rows are collected (1: all, 2: first and last)
+  int32_t Rc;               // collected rows per KV head (collected_count)
   int32_t window;           // > 0: local masking, a row at position pos sees keys pos - window + 1 .. pos (causal calls)
   float* trash;             // attn_pair_kernel: a word of the workspace that takes the stores of invalid elements
   int2* plan;               // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens) per sequence,
@@ -101,6 +103,16 @@ struct CombineParams {
   const int2* plan;         // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens)
   int32_t slots_total;      // balanced chunking: partial slots per KV head
 };
+
+// The rows of one KV head (row = t * g + j for verification token t, head j of the group) whose page log-sum-exps
+// are collected: all G g rows (Eq. 2), or the g rows of the first verification token and the g rows of the bonus
+// token (Eq. 3; with G <= 2 that is every row).  Only these are written and read back.
+__host__ __device__ __forceinline__ int collected_count(int collect_rows, int G, int g) {
+  return (collect_rows == 1 || G <= 2) ? G * g : 2 * g;
+}
+__device__ __forceinline__ int collected_row(int ci, int collect_rows, int G, int g) {   // ci-th collected row
+  return (collect_rows == 1 || G <= 2 || ci < g) ? ci : ci + (G - 2) * g;
+}
 
 // First chunk that any row of a (windowed) verification call can see.
 __device__ __forceinline__ int first_live_chunk(int n, int G, int window, int chunk_tokens) {
@@ -202,6 +214,7 @@ struct FinalizeParams {
   float* block_scores;      // [B, max_blocks]
   int32_t G, g, R, Hq, Hkv, chunk_tokens, nsplit, max_tokens;
   int32_t max_blocks, lse_pages, collect_rows;
+  int32_t Rc;               // collected rows per KV head (collected_count)
   int32_t D;                // head dimension (128 or 64)
   const int2* plan;         // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens)
   int32_t slots_total;      // balanced chunking: partial slots per KV head
