@@ -251,6 +251,15 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
   // kFinUnits units (four chunks each) at once and merges them afterwards, so the table costs about one
   // memory round trip per batch instead of one per chunk.  Slots of chunks past the sequence's end are
   // loaded too (the workspace holds nsplit of them) and dropped at the merge.
+  // ns_live: chunk slots worth loading.  With balanced chunking the slots of a head are shared by all sequences and
+  // one sequence owns few of them, so its count is worked out first (one more round trip, in a kernel that is
+  // bound by bytes at such batch sizes); otherwise every slot up to the host's bound is requested at once.
+  int ns_live = p.nsplit;
+  if (p.plan) {
+    int n0 = p.lens[b];
+    n0 = n0 < 0 ? 0 : (n0 > p.max_tokens ? p.max_tokens : n0);
+    ns_live = (n0 + cs.chunk - 1) / cs.chunk;
+  }
   float2 v[kFinUnits][4];
   auto load_units = [&](int s0, int u0) {
 #pragma unroll
@@ -261,8 +270,8 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
       const float2* ml = p.part_ml + (cs.off + static_cast<int64_t>(h) * cs.stride_h) * p.R + r;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int sidx = min(s0 + sg + 8 * q, cs.last);
-        v[a][q] = ml[static_cast<int64_t>(sidx) * p.R];
+        const int sidx = s0 + sg + 8 * q;
+        v[a][q] = sidx < ns_live ? ml[static_cast<int64_t>(min(sidx, cs.last)) * p.R] : make_float2(-INFINITY, 0.f);
       }
     }
   };
