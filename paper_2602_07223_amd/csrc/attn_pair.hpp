@@ -67,7 +67,8 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
   int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot
   if (p.plan) {                              // balanced chunking: slot j of this head -> (sequence, chunk)
     const int j = split;
-    const BalancedSlot bs = balanced_slot(p.lens, p.batch, p.max_tokens, p.slots_target, p.chunk_unit, j,
+    const BalancedSlot bs = balanced_slot(p.lens, p.batch, p.max_tokens, p.slots_target, p.slots_target2,
+                                          p.chunk_cap_units, p.chunk_unit, j,
                                           (blockIdx.x == 0 && wave == 0) ? p.plan : nullptr);
     if (bs.b < 0) return;
     b = bs.b;

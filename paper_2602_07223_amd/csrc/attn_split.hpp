@@ -105,8 +105,23 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   const int l32 = lane & 31;
   const int h = blockIdx.x % p.Hkv;
   const int rb = (blockIdx.x / p.Hkv) % p.row_blocks;
-  const int split = blockIdx.x / (p.Hkv * p.row_blocks);
-  const int b = blockIdx.y;
+  int split = blockIdx.x / (p.Hkv * p.row_blocks);
+  int b = blockIdx.y;
+  int chunk_tokens = p.chunk_tokens;
+  int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot
+  if constexpr (CAUSAL && PS == 4 && !LOCAL) {
+    if (p.plan) {                            // balanced chunking: slot j of this head -> (sequence, chunk)
+      const int j = split;
+      const BalancedSlot bs = balanced_slot(p.lens, p.batch, p.max_tokens, p.slots_target, p.slots_target2,
+                                            p.chunk_cap_units, p.chunk_unit, j,
+                                            (blockIdx.x == 0 && wave == 0) ? p.plan : nullptr);
+      if (bs.b < 0) return;
+      b = bs.b;
+      split = bs.split;
+      chunk_tokens = bs.chunk;
+      pbase = static_cast<int64_t>(h) * p.slots_total + j;
+    }
+  }
   const int row0 = rb * 32;                  // first query row (of this KV head) handled here
   int* ids_lds = reinterpret_cast<int*>(sm_l + NW * NB * 32) + wave * 64;   // [2 tiles][32 page ids] of this wave
   const int Rl = min(32, p.R - row0);        // valid rows in this block
@@ -117,7 +132,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   // known (one memory round trip less at the head of the kernel): indices are clamped to the table
   // row, entries past the sequence's pages are read but never used.
   const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
-  const int c0 = split * p.chunk_tokens;
+  const int c0 = split * chunk_tokens;
   const int tile_first = c0 / kTile + wave;
   int pagevec = 0;
   auto load_pagevec = [&](int kbase) {
@@ -142,10 +157,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   if (c0 >= n) return;                       // whole workgroup: nothing to do, no partial is read
-  const int c1 = min(c0 + p.chunk_tokens, n);
+  const int c1 = min(c0 + chunk_tokens, n);
   // Local masking: no row sees a token before lo_min; chunks and tiles wholly before it are skipped.
   const int lo_min = LOCAL ? max(n - p.G - p.window + 1, 0) : 0;
-  if (LOCAL && c0 / p.chunk_tokens < first_live_chunk(n, p.G, p.window, p.chunk_tokens)) return;
+  if (LOCAL && c0 / chunk_tokens < first_live_chunk(n, p.G, p.window, chunk_tokens)) return;
   const int nblk = (n + kPage - 1) / kPage;
 
   // ---- per-lane constants
@@ -338,7 +353,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
       // Columns Rl and Rl + 1 of S^T hold k_i . (high part) and k_i . (low part) for the tile's 32 tokens:
       // those two lanes (of each half) park them; register i covers token 8(i/4) + 4 half + i%4.
       if (has_extra && (l32 == Rl || l32 == Rl + 1)) {
-        float* dst = tok_lds + (l32 - Rl) * p.chunk_tokens + (tok0 - c0) + 4 * half;
+        float* dst = tok_lds + (l32 - Rl) * chunk_tokens + (tok0 - c0) + 4 * half;
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4)
           *reinterpret_cast<f32x4*>(dst + 8 * i4) =
@@ -466,7 +481,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     // end of the sequence are never read.
     if (has_extra) {
       float* dst = p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0;
-      for (int e = tid; e < c1 - c0; e += NW * 64) dst[e] = tok_lds[e] + tok_lds[p.chunk_tokens + e];
+      for (int e = tid; e < c1 - c0; e += NW * 64) dst[e] = tok_lds[e] + tok_lds[chunk_tokens + e];
     }
     __syncthreads();
   }
@@ -512,7 +527,6 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
     }
   }
   __syncthreads();
-  const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
   float* po = p.part_o + (pbase * p.R + row0) * D;
   for (int e = tid; e < Rl * D; e += NW * 64) {
     const int row = e / D, d = e % D;

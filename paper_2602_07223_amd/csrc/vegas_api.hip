@@ -30,7 +30,8 @@ struct SplitPlan {
   int R = 0, Rc = 0, NB = 0, NW = 0, chunk = 0, nsplit = 0, lse_pages = 0;   // Rc: collected rows per KV head
   bool pair = false;                 // 33..64 rows per KV head: one workgroup serves both row blocks (attn_pair_kernel)
   bool balanced = false;             // chunk lengths per sequence, computed on the GPU from the lengths (ragged batches)
-  int J = 0, JS = 0;                 // balanced: workgroups per KV head the lengths are apportioned to; slots held (J + B)
+  int J = 0, J2 = 0, JS = 0;         // balanced: workgroups per KV head of a one-wave and a two-wave plan; slots held
+  int cap_units = 0;                 // balanced: longest chunk, in units of kTile * NW tokens
   size_t off_trash = 0;              // a word for stores that must go nowhere
   size_t off_plan = 0;               // balanced: [B] (first slot, chunk tokens)
   size_t off_part_o = 0, off_part_ml = 0, off_page_lse = 0, total = 0;
@@ -98,24 +99,55 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     if (!pl->pair && c > cap && !(wg_per_cu == 1 && fits_alone)) c = cap;
     chunk = static_cast<int>(c);
   }
-  // A batch of several sequences whose lengths the host does not know: the GPU apportions one launch wave of
-  // workgroups (two per CU) to the sequences in proportion to their lengths, so that every workgroup streams
-  // about the same number of tokens.  (A host-side chunk length cuts a ragged batch into unequal numbers of
-  // equal chunks: measured 45 % of the HBM peak on 16 sequences of 8K..64K tokens against 68 % with this.)
-  pl->balanced = pl->pair && d->kv_chunk_tokens == 0 && d->batch >= 2 && d->batch <= 64 && max_len <= (1 << 24) &&
-                 d->num_kv_heads <= 2 * kNumCU;
+  // A batch of several sequences whose lengths the host does not know (only max_seq_len, which may be loose): every
+  // workgroup derives the chunk length of each sequence from seq_lens on the GPU (balanced_slot), so that a fixed
+  // number of workgroups stream about the same number of tokens each.  (A host-side chunk length cuts a ragged
+  // batch into unequal numbers of equal chunks: 45 % of the HBM peak on 16 sequences of 8K..64K tokens, 40 rows,
+  // against 68 % with the plan; and it sizes chunks for lengths that may never occur.)
+  const int64_t per_head = static_cast<int64_t>(d->num_kv_heads) * (pl->pair ? 1 : pl->NB);   // workgroups per slot
+  pl->balanced = may_pair && d->kv_chunk_tokens == 0 && d->batch >= 2 && d->batch <= 64 && max_len < (1 << 24) &&
+                 per_head <= kNumCU;
   pl->chunk = chunk;
   pl->nsplit = (max_len + chunk - 1) / chunk;
   size_t slots = static_cast<size_t>(heads) * pl->nsplit;       // chunk partials the workspace holds
   if (pl->balanced) {
-    // workgroups per KV head: one launch wave (two per CU) without collection; with it, shorter chunks in two
-    // waves were measured faster (16 sequences of 8K..64K tokens, 40 rows: 505 us against 515 us)
-    pl->J = (collect ? 4 : 2) * kNumCU / d->num_kv_heads;
-    if (pl->J < d->batch) pl->J = d->batch;
-    pl->JS = pl->J + d->batch;
-    pl->chunk = unit;                                           // (unused: every sequence has its own)
-    pl->nsplit = pl->J;                                         // most chunks one sequence can get
-    slots = static_cast<size_t>(d->num_kv_heads) * pl->JS;
+    int64_t most_chunks;                                        // of one sequence
+    if (pl->pair) {
+      // one launch wave (two workgroups per CU) without collection; with it, shorter chunks in two waves were
+      // measured faster (16 sequences of 8K..64K tokens, 40 rows: 505 us against 515 us).  Nothing is parked.
+      pl->J = pl->J2 = static_cast<int>((collect ? 4 : 2) * kNumCU / per_head);
+      pl->cap_units = 1 << 20;
+      pl->chunk = unit;                                         // (unused: every sequence has its own)
+      most_chunks = pl->J;
+    } else {
+      // one workgroup per CU with chunks as long as its LDS can park (16 x 36864 tokens, 20 rows: 256 chunks of
+      // 18432 tokens reach 80 % of the peak, 512 of 9216 75 %, 4096-token chunks 69 %); two waves when the
+      // lengths are too ragged for one
+      pl->J = static_cast<int>(kNumCU / per_head);
+      // (slots no plan uses still cost a workgroup that works that out, at one workgroup per CU in a wave of their
+      // own behind the others: a small batch, whose kernel is short, gets the one-wave plan only)
+      pl->J2 = d->batch >= 8 ? 2 * pl->J : pl->J;
+      const int prows = rows_per_head < 32 ? rows_per_head : 32;
+      int cap = 1 << 24;
+      if (collect != 0) {
+        cap = unit;
+        while (split_lds_bytes(pl->NW, prows, collect, cap + unit, d->head_dim) <= 150 * 1024 && cap < (1 << 24)) cap += unit;
+      }
+      pl->cap_units = cap / unit;
+      pl->chunk = collect != 0 ? cap : unit;                    // sizes the LDS that parks a chunk's collected values
+      most_chunks = (static_cast<int64_t>(max_len) + cap - 1) / cap;
+      if (most_chunks < pl->J2) most_chunks = pl->J2;
+    }
+    if (pl->J < 1) pl->J = 1;
+    if (pl->J2 < pl->J) pl->J2 = pl->J;
+    // slots: a plan for J2 workgroups never takes more than max(J2, B) of them; a capped one B * most_chunks
+    int64_t js = pl->J2 > d->batch ? pl->J2 : d->batch;
+    const int64_t capped = static_cast<int64_t>(d->batch) * ((static_cast<int64_t>(max_len) + static_cast<int64_t>(pl->cap_units) * unit - 1) /
+                                                            (static_cast<int64_t>(pl->cap_units) * unit));
+    if (capped > js) js = capped;
+    pl->JS = static_cast<int>(js);
+    pl->nsplit = static_cast<int>(most_chunks);                 // most chunks one sequence can get
+    slots = static_cast<size_t>(d->num_kv_heads) * pl->JS;   // (sibling row blocks share a slot)
   }
   pl->lse_pages = collect == 1 ? (max_len + kPage - 1) / kPage
                                : (collect == 2 ? (pl->balanced ? (max_len + unit - 1) / unit * unit : pl->nsplit * chunk) : 0);
@@ -193,7 +225,8 @@ int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t s
       return launch_one(attn_pair_kernel<COLLECT, D>, pgrid, dim3(kPairWaves * 64), plds, st, sp);
     }
   }
-  const dim3 grid(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
+  const dim3 grid = pl.balanced ? dim3(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.JS, 1)
+                                : dim3(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
   const int rows = pl.R < 32 ? pl.R : 32;
   const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT, pl.chunk, D);
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW, D));
@@ -253,6 +286,8 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->plan = pl.balanced ? reinterpret_cast<int2*>(ws + pl.off_plan) : nullptr;
   sp->batch = d->batch;
   sp->slots_target = pl.J;
+  sp->slots_target2 = pl.J2;
+  sp->chunk_cap_units = pl.cap_units;
   sp->slots_total = pl.JS;
   sp->chunk_unit = kTile * pl.NW;
   sp->max_tokens = d->max_seq_len;
@@ -413,10 +448,12 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   if (logits) {
     if (pl.nsplit <= 16) rc = launch_finalize(verify_finalize_kernel<16, 1>);
     else if (pl.nsplit <= 32) rc = launch_finalize(verify_finalize_kernel<32, 1>);
+    else if (pl.nsplit <= 64) rc = launch_finalize(verify_finalize_kernel<64, 1>);
     else rc = launch_finalize(verify_finalize_kernel<0, 1>);
   } else {
     if (pl.nsplit <= 16) rc = launch_finalize(verify_finalize_kernel<16>);
     else if (pl.nsplit <= 32) rc = launch_finalize(verify_finalize_kernel<32>);
+    else if (pl.nsplit <= 64) rc = launch_finalize(verify_finalize_kernel<64>);
     else rc = launch_finalize(verify_finalize_kernel<0>);
   }
   if (rc != VEGAS_OK) return rc;

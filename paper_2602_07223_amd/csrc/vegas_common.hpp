@@ -85,8 +85,10 @@ struct SplitParams {
   int2* plan;               // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens) per sequence,
                             // computed by every workgroup from the lengths and written here by workgroup 0
   int32_t batch;            // B (balanced chunking)
-  int32_t slots_target;     // J: partial slots (= workgroups) per KV head the lengths are apportioned to
-  int32_t slots_total;      // JS = J + B: slots per KV head the workspace holds
+  int32_t slots_target;     // j1: workgroups per KV head (and row block) of one launch wave
+  int32_t slots_target2;    // j2: of two waves (= j1 where only one plan is wanted)
+  int32_t chunk_cap_units;  // longest chunk the plan may produce, in units
+  int32_t slots_total;      // slots per KV head the workspace holds
   int32_t chunk_unit;       // chunk lengths are multiples of this many tokens
   int64_t page_stride, token_stride, head_stride, num_pages;
   float scale_log2e;
@@ -148,54 +150,82 @@ __device__ __forceinline__ ColumnSlots column_slots(const int2* plan, int slots_
   return c;
 }
 
-// Balanced chunking of a ragged batch (B <= 64 sequences, lengths <= 2^24), computed identically by every wave
-// that calls it.  The J >= B slots of a KV head go to the sequences so that the longest chunk is as short as
-// possible: with C the smallest chunk length for which sum_b ceil(n_b / C) <= J, sequence b is cut into
-// s_b = ceil(n_b / C) equal chunks (rounded up to `unit` tokens), and slot j maps to chunk j - P_b of the sequence
-// whose slot range [P_b, P_b + s_b) holds it.  With as many workgroups as the GPU runs at once, every workgroup then streams
-// about the same number of tokens in ONE launch wave, however ragged the batch is.
+// Balanced chunking of a batch (B <= 64 sequences, lengths < 2^24), computed identically by every wave that
+// calls it, from the lengths alone (the host does not know them).  J workgroups per KV head are given to the
+// sequences so that the longest chunk is as short as possible: with C the smallest chunk length for which
+// sum_b ceil(n_b / C) <= J, sequence b is cut into s_b = ceil(n_b / C) equal chunks (multiples of `unit` tokens).
+// J is j1 (one launch wave of workgroups) unless the lengths are so ragged that the chunks of that plan would
+// leave more than a tenth of the wave idle; then it is j2 (two waves of half-size chunks, handed out longest
+// first, which evens the waves out).  No chunk is longer than cap_units * unit tokens (what a workgroup can park
+// in LDS); a batch too long for J chunks of that size simply takes more slots.  Slot ranges [P_b, P_b + s_b)
+// are laid out by descending chunk length, so workgroups start in that order; slot j maps to chunk j - P_b of
+// the sequence whose range holds it.
 struct BalancedSlot {
   int32_t b, split, chunk;      // b < 0: slot j is not used
 };
-__device__ __forceinline__ BalancedSlot balanced_slot(const int32_t* lens, int B, int max_tokens, int J, int unit, int j,
-                                                      int2* plan_out) {
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+// ceil(x / d) for 0 <= x < 2^23, 1 <= d < 2^23 (a float reciprocal and one correction step instead of an integer division)
+__device__ __forceinline__ uint32_t ceil_div_small(uint32_t x, uint32_t d) {
+  uint32_t q = static_cast<uint32_t>(static_cast<float>(x) * __builtin_amdgcn_rcpf(static_cast<float>(d)));
+  q = q * d > x ? q - 1u : q;                                   // (the estimate is off by one at most)
+  q = (q + 1u) * d <= x ? q + 1u : q;                           // q = floor(x / d)
+  return q * d < x ? q + 1u : q;
+}
+// Smallest C >= 1 (in units) with sum over lanes of ceil(nu / C) <= J; nu is this lane's length in units (< 2^18),
+// total their sum, longest their maximum (the condition always holds there when J >= number of sequences, and
+// nothing changes beyond it).  No plan can beat ceil(total / J), and a batch of equal lengths meets it, so the
+// search starts there and widens its steps before it bisects: one evaluation for a uniform batch.
+__device__ __forceinline__ uint32_t balanced_chunk_units(uint32_t nu, uint32_t total, uint32_t longest, uint32_t J) {
+  auto fits = [&](uint32_t c) { return wave_sum_u32(ceil_div_small(nu, c)) <= J; };
+  uint32_t lo = (total + J - 1u) / J;                           // wave-uniform from here on
+  lo = lo < 1u ? 1u : lo;
+  if (lo >= longest || fits(lo)) return lo < longest ? lo : longest;
+  uint32_t step = (lo + 15u) / 16u, hi = lo + step;             // lo fails; find a length that fits
+  while (hi < longest && !fits(hi)) { lo = hi; step *= 2u; hi = lo + step; }
+  hi = hi < longest ? hi : longest;
+  ++lo;                                                         // invariant: everything below lo fails, hi fits (or is the end)
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (fits(mid)) hi = mid; else lo = mid + 1u;
+  }
+  return lo;
+}
+__device__ __forceinline__ BalancedSlot balanced_slot(const int32_t* lens, int B, int max_tokens, int j1, int j2,
+                                                      int cap_units, int unit, int j, int2* plan_out) {
   const int lane = threadIdx.x & 63;
   uint32_t n = 0u;
   if (lane < B) {
     const int v = lens[lane];
     n = static_cast<uint32_t>(v < 0 ? 0 : (v > max_tokens ? max_tokens : v));
   }
-  uint32_t N = n;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) N += __shfl_xor(N, off, 64);
+  const uint32_t nu = (n + unit - 1u) / unit;                   // length in units
+  const uint32_t total = wave_sum_u32(nu);
   BalancedSlot r;
   r.b = -1; r.split = 0; r.chunk = unit;
-  if (N == 0u) {
+  if (total == 0u) {
     if (plan_out && lane < B) plan_out[lane] = make_int2(0, unit);
     return r;
   }
-  // Smallest chunk length C (in units) for which sum_b ceil(n_b / C) <= J: bisection, 18 rounds cover 2^24 tokens.
-  const uint32_t nu = (n + unit - 1u) / unit;                   // length in units
-  uint32_t lo = 1u, hi = nu;
+  uint32_t longest = nu;
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) hi = max(hi, static_cast<uint32_t>(__shfl_xor(hi, off, 64)));
-  while (lo < hi) {
-    const uint32_t mid = (lo + hi) >> 1;
-    uint32_t cnt = (nu + mid - 1u) / mid;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
-    if (cnt <= static_cast<uint32_t>(J)) hi = mid; else lo = mid + 1u;
+  for (int off = 32; off >= 1; off >>= 1) longest = max(longest, static_cast<uint32_t>(__shfl_xor(longest, off, 64)));
+  uint32_t C = balanced_chunk_units(nu, total, longest, static_cast<uint32_t>(j1));
+  if (j2 > j1 && 10u * total < 9u * static_cast<uint32_t>(j1) * C)   // less than 90 % of the wave would be busy
+    C = balanced_chunk_units(nu, total, longest, static_cast<uint32_t>(j2));
+  C = min(C, static_cast<uint32_t>(cap_units));
+  const uint32_t s = (nu + C - 1u) / C;                         // chunks of this sequence (0 if empty)
+  const int chunk = s > 0u ? static_cast<int>((nu + s - 1u) / s * unit) : 0;   // equal chunks, at most C units
+  int P = 0;                                                    // slots of the sequences with longer chunks
+  for (int i = 0; i < B; ++i) {
+    const int ci = __shfl(chunk, i, 64);
+    const int si = static_cast<int>(__shfl(s, i, 64));
+    P += (ci > chunk || (ci == chunk && i < lane)) ? si : 0;
   }
-  const uint32_t s = (nu + lo - 1u) / lo;                       // chunks of this sequence (0 if empty)
-  const int chunk = s > 0u ? static_cast<int>((nu + s - 1u) / s * unit) : unit;   // equal chunks, at most C
-  uint32_t incl = s;                                            // inclusive prefix sum over lanes
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += o;
-  }
-  const int P = static_cast<int>(incl - s);
-  if (plan_out && lane < B) plan_out[lane] = make_int2(P, chunk);
+  if (plan_out && lane < B) plan_out[lane] = make_int2(P, chunk > 0 ? chunk : unit);
   const uint64_t hit = __builtin_amdgcn_ballot_w64(lane < B && s > 0u && j >= P && j < P + static_cast<int>(s));
   if (hit == 0ull) return r;
   const int b = __builtin_ctzll(hit);
