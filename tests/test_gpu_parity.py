@@ -460,3 +460,34 @@ def test_balanced_chunking_of_ragged_batches(name, G, lens, Hq):
     torch.cuda.synchronize()
     ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale, 0)
     U.check_out(f"balanced.{name}.collect_none", plain.out_verify, ref_out, U.vmax_visible(L))
+
+
+@pytest.mark.parametrize("Hq", [32, 64], ids=["one_row_block", "two_row_blocks"])
+def test_loose_max_seq_len_does_not_change_results(Hq):
+    """A serving engine passes its model limit as max_seq_len, far above what the batch holds: the chunk plan comes
+    from seq_lens on the GPU, and the results are those of a tight bound."""
+    lens = [3000, 900, 17]
+    L = synth.make_random_case(seed=1500 + Hq, batch=3, num_q_heads=Hq, num_kv_heads=8, num_queries=5, seq_lens=lens,
+                               logit_std=2.0, value_std=1.0, outliers=2, outlier_logit=25.0, max_blocks=4096)
+    print(f"[case] loose_max_seq_len Hq={Hq}", flush=True)
+    s = L.spec
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath(batch=3, num_q_heads=Hq, num_kv_heads=8, num_queries=5, max_blocks=4096,
+                             max_seq_len=65536, num_pages=L.num_pages, budget_tokens=256,
+                             softmax_scale=L.softmax_scale)
+    path.block_scores.fill_(float("nan"))
+    path.workspace.fill_(0xFF)
+    path.iteration(dl)
+    torch.cuda.synchronize()
+    ref_out, ref_scores = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                                             L.softmax_scale, vb.COLLECT_ALL_ROWS)
+    vs = U.vmax_visible(L)
+    U.check_out("loose.verify.out", path.out_verify, ref_out, vs)
+    U.check_scores("loose.scores", path.block_scores, ref_scores)
+    sel = path.sel_table.cpu().numpy()
+    ssl = path.sel_seq_lens.cpu().numpy()
+    _, _, ref_logical = O.select_blocks(ref_scores, L.block_table, L.seq_lens, 5, 256, path.max_sel_blocks)
+    U.check_selection("loose.select", sel, ssl, L, ref_scores, ref_logical, 5, 256)
+    for step in range(5):
+        ref_d = O.draft_attention(L.q_draft[step], L.k_cache, L.v_cache, sel, ssl, L.softmax_scale)
+        U.check_out(f"loose.draft{step}", path.out_draft[step], ref_d, vs)
