@@ -84,9 +84,9 @@ typedef struct vegas_desc {
                               and select, <= max_sel_blocks*page_size for draft */
   int32_t collect_rows;    /* VEGAS_COLLECT_* */
   int32_t kv_chunk_tokens; /* tokens of one sequence handled by one workgroup (a multiple of 32); 0 = the library
-                              chooses: from batch, heads and max_seq_len on the host, or, for a batch of 2..64
-                              sequences with 33..64 query rows per KV head, per sequence on the GPU from seq_lens
-                              so that all workgroups stream about the same number of tokens */
+                              chooses: from batch, heads and max_seq_len on the host, or, for a verification call
+                              on a batch of 2..64 sequences, per sequence on the GPU from seq_lens, so that all
+                              workgroups stream about the same number of tokens however loose max_seq_len is */
   int32_t launch_stages;   /* profiling aid: 0 = whole call; else VEGAS_STAGE_* bits to launch only
                               those kernels of an attention call (outputs then incomplete) */
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
