@@ -88,6 +88,13 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     c = (c + unit - 1) / unit * unit;
+    if (pl->pair) {
+      // the pair kernel likes two workgroups per CU once their chunks are long enough (one sequence of 128K tokens,
+      // 40 rows: 512 chunks of 2048 tokens 115 us, 256 of 4096 132 us; at 32K tokens the finalising kernel's
+      // larger table of chunks eats the gain)
+      const int64_t c2 = ((max_len + 2 * splits - 1) / (2 * splits) + unit - 1) / unit * unit;
+      if (wg_per_cu == 1 && c2 >= 2048) { c = c2; splits *= 2; }
+    }
     // What a workgroup collects is parked in LDS until its chunk ends, so a chunk cannot be arbitrarily long.  A
     // chunk that gives every CU exactly one workgroup is taken as it is while its LDS fits (batch 4 x 64K tokens:
     // 256 chunks of 8192 tokens reach 78 % of the HBM peak, 512 chunks of 4096 tokens 75 %); otherwise chunks are
