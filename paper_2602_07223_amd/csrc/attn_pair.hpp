@@ -136,44 +136,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const Spl
 
   // ---- query rows -> LDS [64 rows][CH chunks of 16 B], padded rows; rows past R are zero.
   // COLLECT == 2: rows R (high part) and R + 1 (low part) carry the sum of the collected query rows.
-  for (int idx = tid; idx < 64 * CH; idx += NW * 64) {
-    const int row = idx / CH, chunk = idx % CH;
-    u32x4 raw = {0u, 0u, 0u, 0u};
-    if (row < p.R) {
-      const int t = row / p.g, j = row % p.g;
-      raw = *reinterpret_cast<const u32x4*>(
-          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
-    }
-    if (COLLECT == 2 && row == p.R) {
-      float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int t = 0; t < p.G; ++t) {
-        if (p.collect_rows != 1 && t != 0 && t != p.G - 1) continue;       // Eq. 3: first draft row and bonus row
-        for (int j = 0; j < p.g; ++j) {
-          const u32x4 qv = *reinterpret_cast<const u32x4*>(
-              p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] & 0xFFFFu));
-            sum[2 * e + 1] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] >> 16));
-          }
-        }
-      }
-      u32x4 hi, lo;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint16_t h0 = float_to_bf16_bits(sum[2 * e]), h1 = float_to_bf16_bits(sum[2 * e + 1]);
-        const uint16_t l0 = float_to_bf16_bits(sum[2 * e] - bf16_bits_to_float(h0));
-        const uint16_t l1 = float_to_bf16_bits(sum[2 * e + 1] - bf16_bits_to_float(h1));
-        hi[e] = static_cast<uint32_t>(h0) | (static_cast<uint32_t>(h1) << 16);
-        lo[e] = static_cast<uint32_t>(l0) | (static_cast<uint32_t>(l1) << 16);
-      }
-      *reinterpret_cast<u32x4*>(qlds + p.R * kRowPitch + chunk * 16) = hi;
-      *reinterpret_cast<u32x4*>(qlds + (p.R + 1) * kRowPitch + chunk * 16) = lo;
-      continue;
-    }
-    if (COLLECT == 2 && row == p.R + 1) continue;                            // written together with row R
-    *reinterpret_cast<u32x4*>(qlds + row * kRowPitch + chunk * 16) = raw;
-  }
+  load_queries_to_lds<D>(qlds, p, b, h, 64, 0, p.R, COLLECT == 2, tid, NW * 64);
   const int xr = p.R - row0;                 // COLLECT 2: column of the high-part sum row inside block 1
   const bool has_extra = COLLECT == 2 && role == 1;
   const int limit = n - p.G + ((l32 < Rl) ? (row0 + l32) / p.g : 0);   // last visible token of this lane's row

@@ -56,6 +56,55 @@ __device__ __forceinline__ float half_sum(float x) {
 constexpr int row_pitch(int D) { return 2 * D + 16; }
 constexpr int red_pitch(int D) { return D + 4; }
 
+// Query rows of one KV head -> LDS [rows][D / 8 chunks of 16 B] with padded rows, by all `threads` threads of the
+// workgroup.  Tile row r holds row row0 + r of the head's R = G g rows (row = t g + j) for r < valid; later rows
+// are zero.  with_sums (the logit metric, Sec. 3.2 footnote / App. B): rows `valid` and `valid + 1` carry the sum of
+// the collected query rows of this KV head as a bf16 high part and a bf16 low part (together good to 2^-17).
+template <int D>
+__device__ __forceinline__ void load_queries_to_lds(unsigned char* qlds, const SplitParams& p, int b, int h, int rows,
+                                                    int row0, int valid, bool with_sums, int tid, int threads) {
+  constexpr int CH = D / 8;
+  constexpr int pitch = row_pitch(D);
+  for (int idx = tid; idx < rows * CH; idx += threads) {
+    const int row = idx / CH, chunk = idx % CH;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (row < valid) {
+      const int t = (row0 + row) / p.g, j = (row0 + row) % p.g;
+      raw = *reinterpret_cast<const u32x4*>(
+          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
+    }
+    if (with_sums && row == valid) {
+      float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < p.G; ++t) {
+        if (p.collect_rows != 1 && t != 0 && t != p.G - 1) continue;       // Eq. 3: first draft row and bonus row
+        for (int j = 0; j < p.g; ++j) {
+          const u32x4 qv = *reinterpret_cast<const u32x4*>(
+              p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] & 0xFFFFu));
+            sum[2 * e + 1] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] >> 16));
+          }
+        }
+      }
+      u32x4 hi, lo;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint16_t h0 = float_to_bf16_bits(sum[2 * e]), h1 = float_to_bf16_bits(sum[2 * e + 1]);
+        const uint16_t l0 = float_to_bf16_bits(sum[2 * e] - bf16_bits_to_float(h0));
+        const uint16_t l1 = float_to_bf16_bits(sum[2 * e + 1] - bf16_bits_to_float(h1));
+        hi[e] = static_cast<uint32_t>(h0) | (static_cast<uint32_t>(h1) << 16);
+        lo[e] = static_cast<uint32_t>(l0) | (static_cast<uint32_t>(l1) << 16);
+      }
+      *reinterpret_cast<u32x4*>(qlds + valid * pitch + chunk * 16) = hi;
+      *reinterpret_cast<u32x4*>(qlds + (valid + 1) * pitch + chunk * 16) = lo;
+      continue;
+    }
+    if (with_sums && row == valid + 1) continue;                             // written together with row `valid`
+    *reinterpret_cast<u32x4*>(qlds + row * pitch + chunk * 16) = raw;
+  }
+}
+
 // NW: waves per workgroup; WPS: waves per SIMD the register budget is sized for (2 -> at most
 // 256 registers per lane).  One workgroup handles up to 32 query rows of one KV head.
 // NT_LOADS: K/V are read with the non-temporal hint -- right for the verification pass that streams
@@ -249,44 +298,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitPar
   // ---- query rows -> LDS [row][CH chunks of 16 B], padded rows; rows past R are zero
   // COLLECT == 2: the last row block carries the sum of the collected query rows in rows Rl (high part) and Rl + 1 (low part)
   const bool has_extra = COLLECT == 2 && rb == p.row_blocks - 1;
-  for (int idx = tid; idx < NB * 32 * CH; idx += NW * 64) {
-    const int row = idx / CH, chunk = idx % CH;
-    u32x4 raw = {0u, 0u, 0u, 0u};
-    if (row < Rl) {
-      const int t = (row0 + row) / p.g, j = (row0 + row) % p.g;
-      raw = *reinterpret_cast<const u32x4*>(
-          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
-    }
-    if (has_extra && row == Rl) {
-      float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int t = 0; t < p.G; ++t) {
-        if (p.collect_rows != 1 && t != 0 && t != p.G - 1) continue;       // Eq. 3: first draft row and bonus row
-        for (int j = 0; j < p.g; ++j) {
-          const u32x4 qv = *reinterpret_cast<const u32x4*>(
-              p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] & 0xFFFFu));
-            sum[2 * e + 1] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] >> 16));
-          }
-        }
-      }
-      u32x4 hi, lo;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint16_t h0 = float_to_bf16_bits(sum[2 * e]), h1 = float_to_bf16_bits(sum[2 * e + 1]);
-        const uint16_t l0 = float_to_bf16_bits(sum[2 * e] - bf16_bits_to_float(h0));
-        const uint16_t l1 = float_to_bf16_bits(sum[2 * e + 1] - bf16_bits_to_float(h1));
-        hi[e] = static_cast<uint32_t>(h0) | (static_cast<uint32_t>(h1) << 16);
-        lo[e] = static_cast<uint32_t>(l0) | (static_cast<uint32_t>(l1) << 16);
-      }
-      *reinterpret_cast<u32x4*>(qlds + Rl * kRowPitch + chunk * 16) = hi;
-      *reinterpret_cast<u32x4*>(qlds + (Rl + 1) * kRowPitch + chunk * 16) = lo;
-      continue;
-    }
-    if (has_extra && row == Rl + 1) continue;                                // written together with row Rl
-    *reinterpret_cast<u32x4*>(qlds + row * kRowPitch + chunk * 16) = raw;
-  }
+  load_queries_to_lds<D>(qlds, p, b, h, NB * 32, row0, Rl, has_extra, tid, NW * 64);
   int limit[NB];                             // last visible token of this lane's row
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
