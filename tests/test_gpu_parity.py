@@ -150,6 +150,13 @@ def test_baseline_config4_full():
     run_chain(L, L.spec.budget_tokens, name="ragged16")
 
 
+def test_ragged_batch_one_row_block_full():
+    """The ragged16 lengths with 32 query heads (20 rows per KV head): attn_split_kernel under the two-wave balanced
+    plan, chunks of about 10K tokens parked whole in LDS, at the size its launch configuration is meant for."""
+    L = synth.make_layer(synth.scaled(synth.CONFIGS["ragged16"], num_q_heads=32))
+    run_chain(L, L.spec.budget_tokens, collect=vb.COLLECT_FIRST_LAST, name="ragged16_32heads")
+
+
 @pytest.mark.parametrize("layer", [0, 13, 31])
 def test_baseline_config5_sampled_layers(layer):
     """The 32-layer stack is 32 independent single-layer calls; three layers are checked in full."""
