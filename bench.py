@@ -16,8 +16,8 @@ launches of that kernel alone over the same rotating caches, bracketed by two HI
 launch stream) and the CPU oracle timed on the host cores as a reported baseline.
 
 Beyond the default run:
-  --workload NAME      another synthetic workload (ctx4k, ctx128k_drift, ragged16, stack32, or hd64_ctx32k: the
-                       head-dimension-64 shape at 32K context); the
+  --workload NAME      another synthetic workload (ctx4k, ctx128k_drift, ragged16, stack32; extras: hd64_ctx32k, the
+                       head-dimension-64 shape at 32K context, and ctx32k_batch4); the
                        CPU baseline and the counter-derived traffic belong to the default workload only
   --extras             adds per-iteration percentiles, the warm-cache figure (one cache copy) and the
                        iteration replayed from captured HIP graphs to the same JSON line

@@ -87,7 +87,13 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     int64_t splits = static_cast<int64_t>(kNumCU) * wg_per_cu / columns;
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
-    c = (c + unit - 1) / unit * unit;
+    {
+      // Round to whole units: up, unless a bound a little above a multiple (a selection table with two pages of
+      // slack) would then double every wave's tiles -- a quarter more workgroups than planned is the better price.
+      const int64_t up = (c + unit - 1) / unit * unit, down = c / unit * unit;
+      c = up;
+      if (down >= unit && ((max_len + down - 1) / down) * columns * 4 <= static_cast<int64_t>(kNumCU) * wg_per_cu * 5) c = down;
+    }
     if (pl->pair) {
       // the pair kernel likes two workgroups per CU once their chunks are long enough (one sequence of 128K tokens,
       // 40 rows: 512 chunks of 2048 tokens 115 us, 256 of 4096 132 us; at 32K tokens the finalising kernel's

@@ -112,6 +112,9 @@ CONFIGS: Dict[str, WorkloadSpec] = {
 EXTRA_CONFIGS: Dict[str, WorkloadSpec] = {
     "hd64_ctx32k": WorkloadSpec("hd64_ctx32k", 6, batch=1, num_q_heads=64, num_kv_heads=8, gamma=4,
                                 budget_tokens=2048, seq_len=32768, hitters=128, hitter_run=16, head_dim=64),
+    # "ctx32k" at the batch size the paper runs its long-context workloads with (Sec. 2.2, Sec. 5: batch 4)
+    "ctx32k_batch4": WorkloadSpec("ctx32k_batch4", 7, batch=4, num_q_heads=32, num_kv_heads=8, gamma=4,
+                                  budget_tokens=2048, seq_len=32768, hitters=128, hitter_run=16),
 }
 
 
