@@ -33,9 +33,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
   const int32_t* table = p.block_table + static_cast<int64_t>(b) * p.max_blocks;
   const float* scores = p.block_scores + static_cast<int64_t>(b) * p.max_blocks;
 
-  // With at most 4096 pages per row the scores are requested before the sequence length is known (one memory
-  // round trip less): every index below max_blocks is a valid address, what lies past the prefix is dropped.
-  constexpr int kPre = 4;
+  // With at most 8192 pages per row the scores are requested before the sequence length is known (one memory
+  // round trip less, and all requests in flight together): every index below max_blocks is a valid address, what
+  // lies past the prefix is dropped.
+  constexpr int kPre = 8;
   const bool prefetched = p.max_blocks <= kPre * kSelectThreads;
   float pre[kPre];
   if (prefetched) {
@@ -70,7 +71,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       for (int i = 0; i < kPre; ++i)
         if (tid + i * kSelectThreads < f0) skeys[tid + i * kSelectThreads] = score_key(pre[i]);
     } else {
-      for (int j = tid; j < f0; j += kSelectThreads) skeys[j] = score_key(scores[j]);
+      // groups of kPre independent requests (clamped, so that none sits behind a branch)
+      for (int base = tid; base < f0; base += kPre * kSelectThreads) {
+        float v[kPre];
+#pragma unroll
+        for (int i = 0; i < kPre; ++i) v[i] = scores[min(base + i * kSelectThreads, f0 - 1)];
+#pragma unroll
+        for (int i = 0; i < kPre; ++i)
+          if (base + i * kSelectThreads < f0) skeys[base + i * kSelectThreads] = score_key(v[i]);
+      }
     }
   }
   __syncthreads();
@@ -191,28 +200,38 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     __syncthreads();
     uint32_t pos_run = 0u;
     for (int w = 0; w < wave; ++w) pos_run += wave_take[w];
-    // pass C: same decisions, now with positions; gather the physical page ids
+    // pass C: same decisions, now with positions; gather the physical page ids.  The page ids of kGather steps
+    //         are requested together and unconditionally (coalesced, clamped): a request per taken page behind
+    //         its decision would cost one memory round trip per step.
+    constexpr int kGather = 8;
     eq_run = eq_before;
-    for (int base = w0; base < w1; base += 64) {
-      const int j = base + lane;
-      bool take = j < w1 && take_all;
-      if (!take_all) {
-        bool eq = false, gt = false;
-        if (j < w1) {
-          const uint32_t key = key_at(j) & kmask;
-          eq = key == T;
-          gt = key > T;
+    for (int base = w0; base < w1; base += 64 * kGather) {
+      int32_t page[kGather];
+#pragma unroll
+      for (int i = 0; i < kGather; ++i) page[i] = table[min(base + 64 * i + lane, f0 - 1)];
+#pragma unroll
+      for (int i = 0; i < kGather; ++i) {
+        if (base + 64 * i >= w1) break;
+        const int j = base + 64 * i + lane;
+        bool take = j < w1 && take_all;
+        if (!take_all) {
+          bool eq = false, gt = false;
+          if (j < w1) {
+            const uint32_t key = key_at(j) & kmask;
+            eq = key == T;
+            gt = key > T;
+          }
+          const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
+          take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
+          eq_run += __popcll(beq);
         }
-        const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
-        take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
-        eq_run += __popcll(beq);
+        const uint64_t btk = __builtin_amdgcn_ballot_w64(take);
+        if (take) {
+          const uint32_t pos = pos_run + __popcll(btk & lt);
+          if (pos < static_cast<uint32_t>(p.max_sel_blocks)) sel[pos] = page[i];
+        }
+        pos_run += __popcll(btk);
       }
-      const uint64_t btk = __builtin_amdgcn_ballot_w64(take);
-      if (take) {
-        const uint32_t pos = pos_run + __popcll(btk & lt);
-        if (pos < static_cast<uint32_t>(p.max_sel_blocks)) sel[pos] = table[j];
-      }
-      pos_run += __popcll(btk);
     }
   }
 
