@@ -81,7 +81,8 @@ typedef struct vegas_desc {
   int32_t max_sel_blocks;  /* row stride of sel_table */
   int32_t max_seq_len;     /* upper bound on every seq_lens[b] (and sel_seq_lens[b]); sizes the
                               launch grid and the workspace; <= max_blocks*page_size for verify
-                              and select, <= max_sel_blocks*page_size for draft */
+                              and select, <= max_sel_blocks*page_size for draft; at most 2^30
+                              (VEGAS_ERR_UNSUPPORTED above that) */
   int32_t collect_rows;    /* VEGAS_COLLECT_* */
   int32_t kv_chunk_tokens; /* tokens of one sequence handled by one workgroup (a multiple of 32); 0 = the library
                               chooses: from batch, heads and max_seq_len on the host, or, for a verification call

@@ -107,6 +107,17 @@ class VegasPath:
     def _addrs(self, dl: DeviceLayer):
         a = getattr(dl, "_addrs", None)
         if a is None:
+            # checked once per layer, since the calls below hand over addresses: both descriptors' cache extents
+            for desc in (self.desc_verify, self.desc_draft):
+                need = vb.cache_extent_bytes(desc)
+                for name in ("k_cache", "v_cache"):
+                    have = vb._avail_bytes(getattr(dl, name))
+                    if have < need:
+                        raise ValueError(f"{name} spans {have} bytes, the descriptor needs {need}")
+            B, G = self.B, self.G
+            if (dl.q_verify.numel() < B * G * self.Hq * self.D or dl.q_draft.numel() < G * B * self.Hq * self.D or
+                    dl.block_table.numel() < B * self.desc_verify.max_blocks or dl.seq_lens.numel() < B):
+                raise ValueError("layer tensors are smaller than the descriptor's shapes")
             step_bytes = dl.q_draft[0].numel() * dl.q_draft.element_size()
             a = dict(qv=dl.q_verify.data_ptr(), k=dl.k_cache.data_ptr(), v=dl.v_cache.data_ptr(),
                      bt=dl.block_table.data_ptr(), sl=dl.seq_lens.data_ptr(),

@@ -129,3 +129,41 @@ def test_product_path_does_not_touch_the_oracle():
         if fn.endswith(".py"):
             with open(os.path.join(ROOT, "oracle", fn)) as f:
                 assert not re.search(r"^\s*(from|import)\s+paper_2602_07223_amd", f.read(), flags=re.M), fn
+
+
+def test_binding_refuses_tensors_smaller_than_the_descriptor():
+    """The C ABI sees bare pointers; the binding compares tensor extents with what the descriptor lets the
+    kernels address and raises before anything reaches the library (CPU tensors here: nothing is launched)."""
+    import torch
+    d = good_desc(batch=2, max_blocks=8, max_sel_blocks=4, max_seq_len=100, num_pages=10)
+    assert vb.cache_extent_bytes(d) == 10 * 16 * 8 * 128 * 2
+    q = torch.zeros((2, 5, 32, 128), dtype=torch.bfloat16)
+    cache = torch.zeros((10, 16, 8, 128), dtype=torch.bfloat16)
+    half_width = torch.zeros((10, 16, 8, 64), dtype=torch.bfloat16)        # a head_dim-64 cache under a 128 descriptor
+    table = torch.zeros((2, 8), dtype=torch.int32)
+    lens = torch.zeros((2,), dtype=torch.int32)
+    scores = torch.zeros((2, 8), dtype=torch.float32)
+    ws = torch.zeros(vb.vegas_workspace_bytes(d), dtype=torch.uint8)
+    with pytest.raises(ValueError, match="k_cache"):
+        vb.vegas_verify_attention(d, q, half_width, cache, table, lens, torch.zeros_like(q), scores, ws)
+    with pytest.raises(ValueError, match="v_cache"):
+        vb.vegas_verify_attention(d, q, cache, cache[:9].clone(), table, lens, torch.zeros_like(q), scores, ws)
+    with pytest.raises(ValueError, match="block_scores"):
+        vb.vegas_verify_attention(d, q, cache, cache, table, lens, torch.zeros_like(q), scores[:1].clone(), ws)
+    with pytest.raises(ValueError, match="out"):
+        vb.vegas_verify_attention(d, q, cache, cache, table, lens, torch.zeros_like(q[:, :4]), scores, ws)
+    sel = torch.zeros((2, 4), dtype=torch.int32)
+    with pytest.raises(ValueError, match="sel_table"):
+        vb.vegas_select_blocks(d, scores, table, lens, 32, sel[:, :3].contiguous(), lens.clone())
+    with pytest.raises(ValueError, match="token_scores"):
+        vb.vegas_select_tokens(d, scores, table, lens, 32, sel, lens.clone(), ws)
+    qd = torch.zeros((2, 32, 128), dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="k_cache"):
+        vb.vegas_draft_attention(d, qd, half_width, cache, sel, lens, torch.zeros_like(qd), ws)
+    # a strided view into a larger allocation is measured to the end of its storage
+    big = torch.zeros((10, 16, 9, 192), dtype=torch.bfloat16)
+    view = big[:, :, :8, :128]
+    dv = good_desc(batch=2, max_blocks=8, max_sel_blocks=4, max_seq_len=100, num_pages=10,
+                   kv_page_stride=view.stride(0), kv_token_stride=view.stride(1), kv_head_stride=view.stride(2))
+    assert vb._avail_bytes(view) >= vb.cache_extent_bytes(dv)
+    assert vb._avail_bytes(view[1:]) < vb.cache_extent_bytes(dv)

@@ -84,6 +84,36 @@ def test_small_cases(name, B, Hq, Hkv, G, lens, kw, sharp):
     run_chain(L, budget, name=name + ("_sharp" if sharp else "_flat"), **kw)
 
 
+def random_case(i):
+    """Shape i of a seeded sweep over KV heads, group sizes, rows (up to 128 per KV head), batch, head dimension,
+    lengths (empty, shorter than the verification rows, ragged), chunk lengths, budgets and collect modes."""
+    rng = np.random.default_rng(4100 + i)
+    Hkv, g = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 8, 16]))
+    G = int(rng.integers(1, min(17, 128 // g) + 1))
+    B, D = int(rng.integers(1, 6)), int(rng.choice([128, 64]))
+    top = int(rng.choice([40, 300, 2000, 6000]))
+    lens = [int(rng.integers(0, top + 1)) if rng.random() < 0.9 else int(rng.integers(0, G + 2)) for _ in range(B)]
+    if max(lens) == 0:
+        lens[0] = G + 3
+    return dict(B=B, Hq=Hkv * g, Hkv=Hkv, G=G, D=D, lens=lens,
+                collect=int(rng.choice([vb.COLLECT_ALL_ROWS, vb.COLLECT_FIRST_LAST])),
+                verify_chunk=int(rng.choice([0, 0, 128, 256, 512, 1024, 2048])),
+                draft_chunk=int(rng.choice([0, 0, 64, 128, 512])),
+                budget=int(rng.choice([16, 32, 100, 256, 1000, 10 ** 6])), sharp=bool(rng.random() < 0.5))
+
+
+@pytest.mark.parametrize("i", range(32))
+def test_random_shapes(i):
+    c = random_case(i)
+    print(f"[case] random shape {i}: {c}", flush=True)
+    L = synth.make_random_case(seed=5100 + i, batch=c["B"], num_q_heads=c["Hq"], num_kv_heads=c["Hkv"],
+                               num_queries=c["G"], seq_lens=c["lens"], head_dim=c["D"],
+                               logit_std=2.0 if c["sharp"] else 0.3, value_std=1.0,
+                               outliers=3 if c["sharp"] else 0, outlier_logit=30.0)
+    run_chain(L, c["budget"], collect=c["collect"], verify_chunk=c["verify_chunk"], draft_chunk=c["draft_chunk"],
+              name=f"random{i}")
+
+
 @pytest.mark.parametrize("collect", [vb.COLLECT_FIRST_LAST, vb.COLLECT_ALL_ROWS])
 def test_collect_modes(collect):
     L = synth.make_random_case(seed=77, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=6,
@@ -392,7 +422,7 @@ def test_verify_with_local_masking(name, B, Hq, Hkv, G, lens, window, chunk):
 def test_local_masking_refuses_score_collection():
     desc = vb.make_desc(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, max_blocks=64, max_sel_blocks=64,
                         max_seq_len=1024, num_pages=64, softmax_scale=0.1, window=128)
-    z = torch.zeros(1 << 16, dtype=torch.int32, device="cuda:0")
+    z = torch.zeros(1 << 19, dtype=torch.int32, device="cuda:0")
     ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
     with pytest.raises(vb.VegasError) as e:
         vb.vegas_verify_attention(desc, z, z, z, z, z, z, z.view(torch.float32), ws)

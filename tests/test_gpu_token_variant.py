@@ -105,7 +105,7 @@ def test_rows_without_spare_columns_are_refused():
     desc = vb.make_desc(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=8, max_blocks=64, max_sel_blocks=64,
                         max_seq_len=1024, num_pages=64, softmax_scale=0.1, score_metric=vb.METRIC_TOKEN_LOGITS)
     dev = torch.device("cuda:0")
-    z = torch.zeros(1 << 16, dtype=torch.int32, device=dev)
+    z = torch.zeros(1 << 19, dtype=torch.int32, device=dev)
     with pytest.raises(vb.VegasError) as e:
         vb.vegas_verify_attention(desc, z, z, z, z, z, z, z.view(torch.float32), z)
     assert e.value.status == vb.VEGAS_ERR_UNSUPPORTED
@@ -193,7 +193,7 @@ def run_token_chain(L, budget, collect=vb.COLLECT_FIRST_LAST, name="case"):
     max_sel = min(max(budget, G), int(L.seq_lens.max())) + 2
     desc_sel = vb.make_desc(batch=s.batch, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads, num_queries=G,
                             max_blocks=L.max_blocks, max_sel_blocks=max_sel, max_seq_len=max(int(L.seq_lens.max()), 1),
-                            num_pages=L.num_pages, softmax_scale=L.softmax_scale)
+                            num_pages=L.num_pages, softmax_scale=L.softmax_scale, head_dim=s.head_dim)
     ws = torch.empty(vb.vegas_workspace_bytes(desc_sel), dtype=torch.uint8, device=dev)
     sel = torch.empty((s.batch, max_sel), dtype=torch.int32, device=dev)
     ssl = torch.empty((s.batch,), dtype=torch.int32, device=dev)
@@ -229,7 +229,7 @@ def run_token_chain(L, budget, collect=vb.COLLECT_FIRST_LAST, name="case"):
     # (3) draft over the GPU's selection, one-token pages
     desc_d = vb.make_desc(batch=s.batch, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads, num_queries=1,
                           max_blocks=max_sel, max_sel_blocks=max_sel, max_seq_len=max(int(ssl_h.max()), 1),
-                          num_pages=L.num_pages * PAGE, softmax_scale=L.softmax_scale, page_size=1)
+                          num_pages=L.num_pages * PAGE, softmax_scale=L.softmax_scale, page_size=1, head_dim=s.head_dim)
     wsd = torch.empty(vb.vegas_workspace_bytes(desc_d), dtype=torch.uint8, device=dev)
     kc1 = L.k_cache.reshape(-1, 1, s.num_kv_heads, s.head_dim)
     vc1 = L.v_cache.reshape(-1, 1, s.num_kv_heads, s.head_dim)
@@ -245,6 +245,39 @@ def test_token_chain_small_ragged():
     L = synth.make_random_case(seed=611, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
                                seq_lens=[5000, 4, 1300], logit_std=1.5, value_std=1.0, outliers=3, outlier_logit=20.0)
     run_token_chain(L, 400, name="token_chain_ragged")
+
+
+def test_token_chain_head_dim_64():
+    L = synth.make_random_case(seed=612, batch=2, num_q_heads=16, num_kv_heads=4, num_queries=3, head_dim=64,
+                               seq_lens=[2100, 37], logit_std=1.5, value_std=1.0, outliers=3, outlier_logit=20.0)
+    run_token_chain(L, 257, collect=vb.COLLECT_ALL_ROWS, name="token_chain_hd64")
+
+
+def random_token_case(i):
+    """Shape i of a seeded sweep over KV heads, group sizes, rows, batch, head dimension, lengths, budgets."""
+    rng = np.random.default_rng(77000 + i)
+    while True:
+        Hkv, g = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 8, 16]))
+        G = int(rng.integers(1, min(17, 128 // g) + 1))
+        if 0 < (G * g) % 32 <= 30:                       # the logit metric needs two spare rows in the last block
+            break
+    B, D = int(rng.integers(1, 5)), int(rng.choice([128, 64]))
+    top = int(rng.choice([40, 300, 2000, 6000]))
+    lens = [int(rng.integers(0, top + 1)) if rng.random() < 0.9 else int(rng.integers(0, G + 2)) for _ in range(B)]
+    lens[0] = max(lens[0], G + 3)
+    collect = int(rng.choice([vb.COLLECT_ALL_ROWS, vb.COLLECT_FIRST_LAST]))
+    budget = int(rng.choice([1, 16, 33, 100, 257, 1000, 10 ** 6]))
+    return dict(B=B, Hq=Hkv * g, Hkv=Hkv, G=G, D=D, lens=lens, collect=collect, budget=budget)
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_token_chain_random_shapes(i):
+    c = random_token_case(i)
+    print(f"[case] random token shape {i}: {c}", flush=True)
+    L = synth.make_random_case(seed=9000 + i, batch=c["B"], num_q_heads=c["Hq"], num_kv_heads=c["Hkv"],
+                               num_queries=c["G"], seq_lens=c["lens"], head_dim=c["D"], logit_std=1.5, value_std=1.0,
+                               outliers=3, outlier_logit=20.0)
+    run_token_chain(L, c["budget"], collect=c["collect"], name=f"token_random{i}")
 
 
 def test_token_chain_ctx32k_full():
