@@ -114,6 +114,39 @@ def test_random_shapes(i):
               name=f"random{i}")
 
 
+def random_batch(i):
+    """Ragged batch i of a seeded sweep: 2..64 sequences (uniform, random, one long among short ones, some empty),
+    no chunk length passed, so verification plans its chunks per sequence on the GPU."""
+    rng = np.random.default_rng(31000 + i)
+    Hkv, g = int(rng.choice([2, 4, 8])), int(rng.choice([2, 4, 8]))
+    G = int(rng.integers(2, min(17, 128 // g) + 1))
+    B, D = int(rng.choice([2, 3, 7, 8, 9, 16, 33, 64])), int(rng.choice([128, 64]))
+    kind, top = int(rng.integers(0, 4)), int(rng.choice([600, 3000]))
+    if kind == 0:
+        lens = [int(rng.integers(0, top + 1)) for _ in range(B)]
+    elif kind == 1:
+        lens = [top] * B
+    elif kind == 2:
+        lens = [top * 8 if b == 0 else int(rng.integers(0, 60)) for b in range(B)]
+    else:
+        lens = [int(rng.integers(top // 2, top + 1)) if rng.random() < 0.7 else 0 for _ in range(B)]
+    if max(lens) == 0:
+        lens[0] = G + 3
+    return dict(B=B, Hq=Hkv * g, Hkv=Hkv, G=G, D=D, lens=lens,
+                collect=int(rng.choice([vb.COLLECT_ALL_ROWS, vb.COLLECT_FIRST_LAST])),
+                budget=int(rng.choice([64, 256, 1000])))
+
+
+@pytest.mark.parametrize("i", range(12))
+def test_random_ragged_batches(i):
+    c = random_batch(i)
+    print(f"[case] random batch {i}: {c}", flush=True)
+    L = synth.make_random_case(seed=12000 + i, batch=c["B"], num_q_heads=c["Hq"], num_kv_heads=c["Hkv"],
+                               num_queries=c["G"], seq_lens=c["lens"], head_dim=c["D"], logit_std=1.0, value_std=1.0,
+                               outliers=2, outlier_logit=30.0)
+    run_chain(L, c["budget"], collect=c["collect"], name=f"random_batch{i}")
+
+
 @pytest.mark.parametrize("collect", [vb.COLLECT_FIRST_LAST, vb.COLLECT_ALL_ROWS])
 def test_collect_modes(collect):
     L = synth.make_random_case(seed=77, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=6,
