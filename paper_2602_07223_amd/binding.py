@@ -182,14 +182,15 @@ def vegas_workspace_bytes(desc: VegasDesc) -> int:
 def vegas_verify_attention(desc: VegasDesc, q, k_cache, v_cache, block_table, seq_lens, out, block_scores,
                            workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
-    d = desc
-    rows = d.batch * d.num_queries * d.num_q_heads * d.head_dim * 2
-    per_page = 16 if d.score_metric == METRIC_TOKEN_LOGITS else 1
-    _check_extents("vegas_verify_attention", q=(q, rows), out=(out, rows),
-                   k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
-                   block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
-                   block_scores=(block_scores if d.collect_rows != COLLECT_NONE else None,
-                                 d.batch * d.max_blocks * per_page * 4))
+    if not (isinstance(q, int) and isinstance(k_cache, int)):      # raw addresses: the caller has checked (harness)
+        d = desc
+        rows = d.batch * d.num_queries * d.num_q_heads * d.head_dim * 2
+        per_page = 16 if d.score_metric == METRIC_TOKEN_LOGITS else 1
+        _check_extents("vegas_verify_attention", q=(q, rows), out=(out, rows),
+                       k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
+                       block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
+                       block_scores=(block_scores if d.collect_rows != COLLECT_NONE else None,
+                                     d.batch * d.max_blocks * per_page * 4))
     rc = load_library().vegas_verify_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                                _ptr(block_table), _ptr(seq_lens), _ptr(out), _ptr(block_scores),
                                                _ptr(workspace), wb, _stream(stream))
@@ -200,11 +201,12 @@ def vegas_verify_attention(desc: VegasDesc, q, k_cache, v_cache, block_table, se
 def vegas_select_blocks(desc: VegasDesc, block_scores, block_table, seq_lens, budget_tokens: int, sel_table,
                         sel_seq_lens, budgets=None, workspace=None, stream=None) -> None:
     wb = _nbytes(workspace) if workspace is not None and not isinstance(workspace, int) else 0
-    d = desc
-    _check_extents("vegas_select_blocks", block_scores=(block_scores, d.batch * d.max_blocks * 4),
-                   block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
-                   budgets=(budgets, d.batch * 4), sel_table=(sel_table, d.batch * d.max_sel_blocks * 4),
-                   sel_seq_lens=(sel_seq_lens, d.batch * 4))
+    if not (isinstance(block_scores, int) and isinstance(sel_table, int)):
+        d = desc
+        _check_extents("vegas_select_blocks", block_scores=(block_scores, d.batch * d.max_blocks * 4),
+                       block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
+                       budgets=(budgets, d.batch * 4), sel_table=(sel_table, d.batch * d.max_sel_blocks * 4),
+                       sel_seq_lens=(sel_seq_lens, d.batch * 4))
     rc = load_library().vegas_select_blocks(ctypes.byref(desc), _ptr(block_scores), _ptr(block_table),
                                             _ptr(seq_lens), int(budget_tokens), _ptr(budgets), _ptr(sel_table),
                                             _ptr(sel_seq_lens), _ptr(workspace), wb, _stream(stream))
@@ -215,11 +217,12 @@ def vegas_select_blocks(desc: VegasDesc, block_scores, block_table, seq_lens, bu
 def vegas_select_tokens(desc: VegasDesc, token_scores, block_table, seq_lens, budget_tokens: int, sel_table,
                         sel_seq_lens, workspace, budgets=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
-    d = desc
-    _check_extents("vegas_select_tokens", token_scores=(token_scores, d.batch * d.max_blocks * 16 * 4),
-                   block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
-                   budgets=(budgets, d.batch * 4), sel_table=(sel_table, d.batch * d.max_sel_blocks * 4),
-                   sel_seq_lens=(sel_seq_lens, d.batch * 4))
+    if not (isinstance(token_scores, int) and isinstance(sel_table, int)):
+        d = desc
+        _check_extents("vegas_select_tokens", token_scores=(token_scores, d.batch * d.max_blocks * 16 * 4),
+                       block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
+                       budgets=(budgets, d.batch * 4), sel_table=(sel_table, d.batch * d.max_sel_blocks * 4),
+                       sel_seq_lens=(sel_seq_lens, d.batch * 4))
     rc = load_library().vegas_select_tokens(ctypes.byref(desc), _ptr(token_scores), _ptr(block_table),
                                             _ptr(seq_lens), int(budget_tokens), _ptr(budgets), _ptr(sel_table),
                                             _ptr(sel_seq_lens), _ptr(workspace), wb, _stream(stream))
@@ -229,10 +232,11 @@ def vegas_select_tokens(desc: VegasDesc, token_scores, block_table, seq_lens, bu
 
 def vegas_extend_selection(desc: VegasDesc, block_table, seq_lens, num_new: int, sel_table, sel_seq_lens,
                            stream=None) -> None:
-    d = desc
-    _check_extents("vegas_extend_selection", block_table=(block_table, d.batch * d.max_blocks * 4),
-                   seq_lens=(seq_lens, d.batch * 4), sel_table=(sel_table, d.batch * d.max_sel_blocks * 4),
-                   sel_seq_lens=(sel_seq_lens, d.batch * 4))
+    if not (isinstance(block_table, int) and isinstance(sel_table, int)):
+        d = desc
+        _check_extents("vegas_extend_selection", block_table=(block_table, d.batch * d.max_blocks * 4),
+                       seq_lens=(seq_lens, d.batch * 4), sel_table=(sel_table, d.batch * d.max_sel_blocks * 4),
+                       sel_seq_lens=(sel_seq_lens, d.batch * 4))
     rc = load_library().vegas_extend_selection(ctypes.byref(desc), _ptr(block_table), _ptr(seq_lens), int(num_new),
                                                _ptr(sel_table), _ptr(sel_seq_lens), _stream(stream))
     if rc != VEGAS_OK:
@@ -242,11 +246,12 @@ def vegas_extend_selection(desc: VegasDesc, block_table, seq_lens, num_new: int,
 def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace,
                           stream=None, workspace_bytes: Optional[int] = None) -> None:
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
-    d = desc
-    rows = d.batch * d.num_q_heads * d.head_dim * 2
-    _check_extents("vegas_draft_attention", q=(q, rows), out=(out, rows),
-                   k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
-                   sel_table=(sel_table, d.batch * d.max_sel_blocks * 4), sel_seq_lens=(sel_seq_lens, d.batch * 4))
+    if not (isinstance(q, int) and isinstance(k_cache, int)):
+        d = desc
+        rows = d.batch * d.num_q_heads * d.head_dim * 2
+        _check_extents("vegas_draft_attention", q=(q, rows), out=(out, rows),
+                       k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
+                       sel_table=(sel_table, d.batch * d.max_sel_blocks * 4), sel_seq_lens=(sel_seq_lens, d.batch * 4))
     rc = load_library().vegas_draft_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                               _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out), _ptr(workspace),
                                               wb, _stream(stream))
