@@ -518,8 +518,6 @@ def test_balanced_chunking_of_ragged_batches(name, G, lens, Hq):
     """Several sequences and no chunk length from the caller: the kernels give a fixed number of workgroups to the
     sequences by length (every workgroup computes the same plan from seq_lens), in every streaming kernel:
     attn_pair_kernel (two row blocks), attn_split_kernel (one) and its sibling workgroups (three)."""
-    if Hq == 96 and len(lens) > 8:
-        pytest.skip("oracle time")
     L = synth.make_random_case(seed=1400 + len(name) + Hq, batch=len(lens), num_q_heads=Hq, num_kv_heads=8, num_queries=G,
                                seq_lens=lens, logit_std=2.0, value_std=1.0, outliers=2, outlier_logit=25.0)
     run_chain(L, 256, name=f"balanced.{name}.Hq{Hq}")
