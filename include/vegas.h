@@ -71,7 +71,7 @@ enum {
 };
 
 typedef struct vegas_desc {
-  int32_t batch;           /* B: sequences */
+  int32_t batch;           /* B: sequences (at most 65535) */
   int32_t num_q_heads;     /* H_q */
   int32_t num_kv_heads;    /* H_kv, divides H_q */
   int32_t head_dim;        /* 128, or 64 (the 2 KB-per-token shape of App. D); anything else: VEGAS_ERR_UNSUPPORTED */

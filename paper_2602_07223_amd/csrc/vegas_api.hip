@@ -45,6 +45,7 @@ int check_common(const vegas_desc* d) {
   if (d->num_q_heads % d->num_kv_heads != 0) return VEGAS_ERR_SHAPE;
   if (d->head_dim != 128 && d->head_dim != 64) return VEGAS_ERR_UNSUPPORTED;
   if (d->max_seq_len > (1 << 30)) return VEGAS_ERR_UNSUPPORTED;      // token counts and offsets are 32-bit in the kernels
+  if (d->batch > 65535) return VEGAS_ERR_UNSUPPORTED;                // sequences are a grid's y or z dimension
   if (d->page_size != 1 && d->page_size != 2 && d->page_size != 4 && d->page_size != 8 && d->page_size != kPage)
     return VEGAS_ERR_UNSUPPORTED;
   if (d->kv_head_stride < d->head_dim || d->kv_token_stride < d->head_dim ||
@@ -621,7 +622,7 @@ const char* vegas_strerror(int status) {
     case VEGAS_ERR_SHAPE: return "a size is non-positive or inconsistent";
     case VEGAS_ERR_UNSUPPORTED:
       return "shape not supported by this build (head_dim 128 or 64; page_size 16, in draft calls also 1, 2, 4, 8; "
-             "<= 128 rows per KV head; max_seq_len <= 2^30)";
+             "<= 128 rows per KV head; max_seq_len <= 2^30; batch <= 65535)";
     case VEGAS_ERR_ALIGN: return "pointer or stride alignment";
     case VEGAS_ERR_WORKSPACE: return "workspace missing or too small";
     case VEGAS_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
