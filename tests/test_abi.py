@@ -67,6 +67,8 @@ A = 4096  # a 16-byte aligned fake device address: never dereferenced because va
     (dict(kv_chunk_tokens=100), vb.VEGAS_ERR_SHAPE),
     (dict(kv_token_stride=1028), vb.VEGAS_ERR_ALIGN),
     (dict(softmax_scale=0.0), vb.VEGAS_ERR_SHAPE),
+    (dict(batch=65536), vb.VEGAS_ERR_UNSUPPORTED),             # sequences are a grid dimension
+    (dict(max_seq_len=(1 << 30) + 16, max_blocks=(1 << 26) + 1), vb.VEGAS_ERR_UNSUPPORTED),
 ])
 def test_verify_rejects_bad_descriptors(over, status):
     with pytest.raises(vb.VegasError) as e:
