@@ -625,3 +625,36 @@ def test_window_of_one_returns_the_rows_own_value():
     for t in range(G):
         for h in range(Hq):
             np.testing.assert_allclose(out[0, t, h], c["Vd"][n - G + t, h // (Hq // Hkv)], atol=1e-15)
+
+
+def test_bf16_decoding_against_the_format_definition():
+    """bf16 = sign, 8 exponent bits (bias 127), 7 fraction bits; hand-computed values of single patterns, the
+    subnormal range, and every finite pattern against the definition evaluated with Python's exact fractions."""
+    from fractions import Fraction
+    hand = {0x0000: 0.0, 0x3F80: 1.0, 0xBF80: -1.0, 0x4000: 2.0, 0xC000: -2.0, 0x3FC0: 1.5, 0x3E00: 0.125,
+            0x4049: 3.140625, 0x0080: 2.0 ** -126, 0x0001: 2.0 ** -133, 0x7F7F: (2 - 2.0 ** -7) * 2.0 ** 127}
+    for bits, want in hand.items():
+        assert O.decode_bf16(np.array([bits], dtype=np.uint16))[0] == want, hex(bits)
+    assert np.isposinf(O.decode_bf16(np.array([0x7F80], dtype=np.uint16))[0])
+    assert np.isneginf(O.decode_bf16(np.array([0xFF80], dtype=np.uint16))[0])
+    assert np.isnan(O.decode_bf16(np.array([0x7FC0], dtype=np.uint16))[0])
+    every = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    with np.errstate(invalid="ignore"):                     # the signalling NaN patterns are part of "every"
+        got = O.decode_bf16(every)
+    for bits in range(0, 1 << 16, 97):                       # a stride that visits every exponent
+        e, f, s = (bits >> 7) & 0xFF, bits & 0x7F, bits >> 15
+        if e == 0xFF:
+            continue
+        mag = Fraction(f, 128) * Fraction(2) ** -126 if e == 0 else (1 + Fraction(f, 128)) * Fraction(2) ** (e - 127)
+        assert Fraction(float(got[bits])) == (-mag if s else mag), hex(bits)
+    with pytest.raises(TypeError):
+        O.decode_bf16(np.zeros(4, dtype=np.float32))
+
+
+def test_collected_row_sets_follow_eq2_and_eq3():
+    """Eq. 2 sums over all gamma+1 verification rows, Eq. 3 over the first draft token's row and the bonus row."""
+    assert O.collected_rows(5, O.COLLECT_ALL_ROWS) == (0, 1, 2, 3, 4)
+    assert O.collected_rows(5, O.COLLECT_FIRST_LAST) == (0, 4)
+    assert O.collected_rows(2, O.COLLECT_FIRST_LAST) == (0, 1) == O.collected_rows(2, O.COLLECT_ALL_ROWS)
+    assert O.collected_rows(1, O.COLLECT_FIRST_LAST) == (0,)
+    assert O.collected_rows(7, O.COLLECT_NONE) == ()
