@@ -93,7 +93,7 @@ typedef struct vegas_desc {
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
   int32_t score_metric;    /* VEGAS_METRIC_*: what vegas_verify_attention writes to block_scores */
   int32_t window;          /* vegas_verify_attention: > 0 = local ("sliding window") masking of a banded layer
-                              (Sec. 4: "after causal or local masking"): the row at position pos sees keys
+                              (Sec. 4 names the local mask beside the causal one): the row at position pos sees keys
                               pos - window + 1 .. pos.  Such layers are not sparsified, so collect_rows must
                               be VEGAS_COLLECT_NONE.  0 = plain causal masking */
   float   budget_ratio;    /* selection calls: if > 0 and no per-sequence budgets are passed, sequence b's budget

@@ -114,8 +114,8 @@ def verify_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
     seq_lens int32 [B].  Returns (out float64 [B, G, H_q, D], block_scores float64 [B, max_blocks]).
     block_scores[b, j] = 1/(|R| H_q) * sum_{t in R} sum_h sum_{i in page j} w[t, h, i]; entries
     j >= ceil(n_b/16) are 0.  With COLLECT_NONE the scores are all 0.
-    window > 0: local ("sliding window") masking for banded layers (Sec. 4 collects "after causal or
-    local masking"): the row at position pos sees keys pos - window + 1 .. pos only."""
+    window > 0: local ("sliding window") masking for banded layers (Sec. 4 takes the criticality after the causal
+    or the local mask): the row at position pos sees keys pos - window + 1 .. pos only."""
     B, G, Hq, D = q.shape
     Hkv = k_cache.shape[2]
     g = Hq // Hkv
