@@ -6,15 +6,15 @@ from the product.  It is a plain float64 NumPy implementation of the *definition
 
   * attention                         -- Eq. 1 (Sec. 2.1), softmax(q K^T / sqrt(d)) V
   * verification of gamma+1 tokens in one full-attention pass over the whole cache
-                                      -- Sec. 2.3; causal masking as in Sec. 4 ("after causal
-                                         or local masking")
+                                      -- Sec. 2.3; masked as in Sec. 4 (criticality is taken
+                                         after the causal or local mask)
   * criticality of prefix entries     -- Eq. 2 (all gamma+1 rows, all query heads) and Eq. 3
                                          (first draft row + bonus row), Sec. 3.2-3.3, with the
                                          attention *weights* as the metric (App. B) and the
                                          row/head averaging of Sec. 3.3's last paragraph
   * top-k selection                   -- the argmax of Eq. 2 / Eq. 3, here over unions of
-                                         16-token KV pages; "remaining tokens are kept"
-                                         (Sec. 3.2, last sentence) becomes the forced tail pages
+                                         16-token KV pages; what follows the prefix stays
+                                         (Sec. 3.2, last sentence): the forced tail pages
   * the paper's own selection variant -- logits as the metric (Sec. 3.2 footnote, App. B), single
                                          tokens as the unit (Sec. 4): token_logit_scores,
                                          select_tokens; drafting over them is draft_attention on
