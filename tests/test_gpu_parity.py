@@ -434,7 +434,7 @@ WINDOW_CASES = [
 
 @pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,window,chunk", WINDOW_CASES, ids=[c[0] for c in WINDOW_CASES])
 def test_verify_with_local_masking(name, B, Hq, Hkv, G, lens, window, chunk):
-    """Banded layers (Sec. 4: logits are taken "after causal or local masking"): the row at position pos sees
+    """Banded layers (Sec. 4 names a local mask beside the causal one): the row at position pos sees
     keys pos - window + 1 .. pos; chunks and tiles before the band are skipped, so their stale partials
     (poisoned here) must never be read."""
     L = synth.make_random_case(seed=700 + len(name), batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=G,
