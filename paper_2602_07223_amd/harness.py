@@ -51,9 +51,10 @@ class VegasPath:
                  max_seq_len: int, num_pages: int, budget_tokens: int, softmax_scale: float,
                  collect_rows: int = vb.COLLECT_ALL_ROWS, head_dim: int = 128, device="cuda:0",
                  verify_chunk: int = 0, draft_chunk: int = 0, max_sel_blocks: int = 0,
-                 score_metric: int = vb.METRIC_PAGE_WEIGHTS, token_granular: bool = False):
+                 score_metric: int = vb.METRIC_PAGE_WEIGHTS, token_granular: bool = False, window: int = 0):
         """token_granular: the paper's own variant -- verification collects averaged logits per token,
-        selection picks single tokens, drafting walks one-token pages (Sec. 3.3, Sec. 4)."""
+        selection picks single tokens, drafting walks one-token pages (Sec. 3.3, Sec. 4).
+        window > 0: verification of a banded layer (local masking; needs collect_rows = COLLECT_NONE)."""
         self.device = torch.device(device)
         self.token_granular = token_granular
         if token_granular:
@@ -69,7 +70,8 @@ class VegasPath:
                       max_blocks=max_blocks, max_sel_blocks=self.max_sel_blocks, num_pages=num_pages,
                       softmax_scale=softmax_scale, head_dim=head_dim)
         self.desc_verify = vb.make_desc(max_seq_len=max_seq_len, collect_rows=collect_rows,
-                                        kv_chunk_tokens=verify_chunk, score_metric=score_metric, **common)
+                                        kv_chunk_tokens=verify_chunk, score_metric=score_metric, window=window,
+                                        **common)
         if token_granular:
             draft_common = dict(common, max_blocks=self.max_sel_blocks, num_pages=num_pages * PAGE)
             self.desc_draft = vb.make_desc(max_seq_len=min(self.max_sel_blocks, max_seq_len), collect_rows=vb.COLLECT_NONE,

@@ -99,8 +99,8 @@ def test_local_masking_head_dim_64(name, B, Hq, G, lens, window, chunk):
                                outlier_logit=20.0)
     print(f"[case] hd64 window {name} W={window}", flush=True)
     dl = harness.DeviceLayer.upload(L)
-    path = harness.VegasPath.for_layer(L, budget_tokens=64, collect_rows=vb.COLLECT_NONE, verify_chunk=chunk)
-    path.desc_verify.window = window
+    path = harness.VegasPath.for_layer(L, budget_tokens=64, collect_rows=vb.COLLECT_NONE, verify_chunk=chunk,
+                                       window=window)
     path.workspace.fill_(0xFF)
     path.out_verify.fill_(float("nan"))
     path.verify(dl)

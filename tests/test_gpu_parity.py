@@ -441,8 +441,8 @@ def test_verify_with_local_masking(name, B, Hq, Hkv, G, lens, window, chunk):
                                seq_lens=lens, logit_std=1.5, value_std=1.0, outliers=2, outlier_logit=20.0)
     print(f"[case] window {name} W={window}", flush=True)
     dl = harness.DeviceLayer.upload(L)
-    path = harness.VegasPath.for_layer(L, budget_tokens=64, collect_rows=vb.COLLECT_NONE, verify_chunk=chunk)
-    path.desc_verify.window = window
+    path = harness.VegasPath.for_layer(L, budget_tokens=64, collect_rows=vb.COLLECT_NONE, verify_chunk=chunk,
+                                       window=window)
     path.workspace.fill_(0xFF)                                    # NaN bit patterns in every partial
     path.out_verify.fill_(float("nan"))
     path.verify(dl)
@@ -450,6 +450,39 @@ def test_verify_with_local_masking(name, B, Hq, Hkv, G, lens, window, chunk):
     ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale,
                                     0, window=window)
     U.check_out(name, path.out_verify, ref_out, U.vmax_visible(L))
+
+
+def random_window_case(i):
+    rng = np.random.default_rng(52000 + i)
+    Hkv, g = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 8, 16]))
+    G = int(rng.integers(1, min(17, 128 // g) + 1))
+    B, D = int(rng.integers(1, 5)), int(rng.choice([128, 64]))
+    top = int(rng.choice([40, 300, 2000, 9000]))
+    lens = [int(rng.integers(0, top + 1)) for _ in range(B)]
+    if max(lens) == 0:
+        lens[0] = G + 3
+    return dict(B=B, Hq=Hkv * g, Hkv=Hkv, G=G, D=D, lens=lens,
+                window=int(rng.choice([1, 2, 16, 17, 37, 100, 128, 1000, 5000, 20000])),
+                chunk=int(rng.choice([0, 0, 64, 128, 512, 2048])))
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_local_masking_random_shapes(i):
+    c = random_window_case(i)
+    print(f"[case] random window shape {i}: {c}", flush=True)
+    L = synth.make_random_case(seed=15000 + i, batch=c["B"], num_q_heads=c["Hq"], num_kv_heads=c["Hkv"],
+                               num_queries=c["G"], seq_lens=c["lens"], head_dim=c["D"], logit_std=1.5, value_std=1.0,
+                               outliers=2, outlier_logit=20.0)
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=64, collect_rows=vb.COLLECT_NONE, verify_chunk=c["chunk"],
+                                       window=c["window"])
+    path.workspace.fill_(0xFF)
+    path.out_verify.fill_(float("nan"))
+    path.verify(dl)
+    torch.cuda.synchronize()
+    ref_out, _ = O.verify_attention(L.q_verify, L.k_cache, L.v_cache, L.block_table, L.seq_lens, L.softmax_scale,
+                                    0, window=c["window"])
+    U.check_out(f"window_random{i}", path.out_verify, ref_out, U.vmax_visible(L))
 
 
 def test_local_masking_refuses_score_collection():
