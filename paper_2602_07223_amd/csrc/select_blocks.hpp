@@ -7,6 +7,8 @@
 // Everything is integer work on the score bits: the result is defined bit for bit, ties go to the
 // lower logical page index.
 #pragma once
+#include <type_traits>
+
 #include "vegas_common.hpp"
 
 namespace vegas {
@@ -97,28 +99,55 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       uint32_t* h = hist[wave];
 #pragma unroll
       for (int i = 0; i < 4; ++i) h[lane + 64 * i] = 0u;       // wave-private: ordered by the wave's own LDS stream
-      for (int base = 0; base < f0; base += kSelectThreads) {
-        const int j = base + tid;
-        uint32_t key = 0u;
-        bool act = false;
-        if (j < f0) {
-          key = key_at(j);
-          act = (key & mask) == prefix;
+      // Up to four key rows per trip: the rows' ballot / readlane / atomic chains are independent, so they hide
+      // one another's latency (a wave is bound by dependent instruction latency here, not by issue slots).
+      // Scores cluster (the top byte of most keys is identical): lanes with the leader's digit are counted by
+      // one atomic; what is left after two rounds adds itself.
+      auto count_rows = [&](int base, auto rows_tag) {
+        constexpr int kR = decltype(rows_tag)::value;
+        uint32_t d[kR];
+        bool act[kR];
+        bool any = false;
+#pragma unroll
+        for (int u = 0; u < kR; ++u) {
+          const int j = base + u * kSelectThreads + tid;
+          const uint32_t key = key_at(min(j, f0 - 1));
+          act[u] = j < f0 && (key & mask) == prefix;
+          d[u] = (key >> shift) & 255u;
+          any = any || act[u];
         }
-        const uint32_t d = (key >> shift) & 255u;
-        // Scores cluster (the top byte of most keys is identical): lanes with the leader's digit
-        // are counted by one atomic; what is left after two rounds adds itself.
 #pragma unroll
         for (int round = 0; round < 2; ++round) {
-          const uint64_t am = __builtin_amdgcn_ballot_w64(act);
-          if (am == 0ull) break;
-          const int leader = __builtin_ctzll(am);
-          const uint32_t dl = __builtin_amdgcn_readlane(d, leader);
-          const uint64_t same = __builtin_amdgcn_ballot_w64(act && d == dl);
-          if (lane == leader) atomicAdd(&h[dl], static_cast<uint32_t>(__popcll(same)));
-          if (d == dl) act = false;
+          if (__builtin_amdgcn_ballot_w64(any) == 0ull) return;
+          any = false;
+#pragma unroll
+          for (int u = 0; u < kR; ++u) {
+            const uint64_t am = __builtin_amdgcn_ballot_w64(act[u]);
+            const int leader = am ? __builtin_ctzll(am) : 0;
+            const uint32_t dl = __builtin_amdgcn_readlane(d[u], leader);
+            const bool hit = act[u] && d[u] == dl;
+            const uint64_t same = __builtin_amdgcn_ballot_w64(hit);
+            if (hit && lane == leader) atomicAdd(&h[dl], static_cast<uint32_t>(__popcll(same)));
+            act[u] = act[u] && !hit;
+            any = any || act[u];
+          }
         }
-        if (act) atomicAdd(&h[d], 1u);
+#pragma unroll
+        for (int u = 0; u < kR; ++u)
+          if (act[u]) atomicAdd(&h[d[u]], 1u);
+      };
+      for (int base = 0; base < f0;) {
+        const int rows = (f0 - base + kSelectThreads - 1) / kSelectThreads;
+        if (rows >= 4) {
+          count_rows(base, std::integral_constant<int, 4>{});
+          base += 4 * kSelectThreads;
+        } else if (rows >= 2) {
+          count_rows(base, std::integral_constant<int, 2>{});
+          base += 2 * kSelectThreads;
+        } else {
+          count_rows(base, std::integral_constant<int, 1>{});
+          base += kSelectThreads;
+        }
       }
       __syncthreads();
       if (wave == 0) {
@@ -159,48 +188,42 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
 
   // ---- ordered compaction of the prefix: wave w owns the contiguous pages [w*span, (w+1)*span) and
   //      walks them 64 at a time (lane = page), so page order is (wave, step, lane) and every memory
-  //      access is coalesced.  Ballots count ties and takes; two 16-entry prefixes over the wave totals
-  //      turn the counts into global ranks and output positions.
+  //      access is coalesced.  Ballots count the keys above T and the ties; a 16-entry prefix over the wave
+  //      totals turns the counts into global tie ranks and output positions.
   if (kc > 0) {
     constexpr int kWaves = kSelectThreads / 64;
     const int span = ((f0 + kWaves - 1) / kWaves + 63) / 64 * 64;
     const int w0 = min(wave * span, f0), w1 = min(w0 + span, f0);
     const uint64_t lt = (1ull << lane) - 1ull;
-    // pass A: ties in this wave's pages
-    uint32_t eq_wave = 0u;
-    if (!take_all)
-      for (int base = w0; base < w1; base += 64) {
-        const int j = base + lane;
-        const bool eq = j < w1 && (key_at(j) & kmask) == T;
-        eq_wave += __popcll(__builtin_amdgcn_ballot_w64(eq));
-      }
-    if (lane == 0) wave_eq[wave] = eq_wave;
-    __syncthreads();
-    uint32_t eq_before = 0u;
-    for (int w = 0; w < wave; ++w) eq_before += wave_eq[w];
-    // pass B: pages taken by this wave
-    uint32_t take_wave = 0u, eq_run = eq_before;
-    for (int base = w0; base < w1; base += 64) {
-      const int j = base + lane;
-      bool take = j < w1 && take_all;
-      if (!take_all) {
-        bool eq = false, gt = false;
-        if (j < w1) {
-          const uint32_t key = key_at(j) & kmask;
-          eq = key == T;
-          gt = key > T;
+    // pass A: keys above T and ties in this wave's pages (four steps per trip: independent chains).  A wave's
+    //         takes follow from the counts: its keys above T plus as many of its ties as are still wanted.
+    uint32_t eq_wave = 0u, gt_wave = 0u;
+    if (!take_all) {
+      for (int base = w0; base < w1; base += 64 * 4) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = base + 64 * i + lane;
+          const uint32_t key = key_at(min(j, f0 - 1)) & kmask;
+          eq_wave += __popcll(__builtin_amdgcn_ballot_w64(j < w1 && key == T));
+          gt_wave += __popcll(__builtin_amdgcn_ballot_w64(j < w1 && key > T));
         }
-        const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
-        take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
-        eq_run += __popcll(beq);
       }
-      take_wave += __popcll(__builtin_amdgcn_ballot_w64(take));
+    } else {
+      gt_wave = static_cast<uint32_t>(w1 - w0);
     }
-    if (lane == 0) wave_take[wave] = take_wave;
+    if (lane == 0) {
+      wave_eq[wave] = eq_wave;
+      wave_take[wave] = gt_wave;
+    }
     __syncthreads();
-    uint32_t pos_run = 0u;
-    for (int w = 0; w < wave; ++w) pos_run += wave_take[w];
-    // pass C: same decisions, now with positions; gather the physical page ids.  The page ids of kGather steps
+    uint32_t eq_before = 0u, pos_run = 0u, eq_run;
+    for (int w = 0; w < wave; ++w) {
+      const uint32_t e = wave_eq[w];
+      const uint32_t wanted = need_eq > eq_before ? need_eq - eq_before : 0u;   // ties still wanted where wave w starts
+      pos_run += wave_take[w] + min(e, wanted);
+      eq_before += e;
+    }
+    // pass B: the decisions, now with positions; gather the physical page ids.  The page ids of kGather steps
     //         are requested together and unconditionally (coalesced, clamped): a request per taken page behind
     //         its decision would cost one memory round trip per step.
     constexpr int kGather = 8;
