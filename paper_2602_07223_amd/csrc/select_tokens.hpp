@@ -55,18 +55,6 @@ __device__ __forceinline__ TokenPlan token_plan(const TokenSelectParams& p, int 
   return t;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS).
-__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
-  int v = static_cast<int>(x);
-  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
-  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
-  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
-  return static_cast<uint32_t>(v);
-}
-
 // All threads: sh_tot[q][bin] = sum over the sequence's slices of histogram (pass q, bin) for q < passes,
 // and, if sh_bef is given, the same sum over the slices before `upto` only.  Followed by a barrier.
 __device__ __forceinline__ void token_sum_hists(const TokenSelectParams& p, int b, int passes, int nslices, int upto,
