@@ -123,16 +123,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
         if (u >= rows) continue;
         const bool act = u * kSelectThreads + tid < f0 && (key[u] & mask) == prefix;
         const uint32_t d = (key[u] >> shift) & 255u;
-        if (pass == 0) {
-          // the top byte: scores cluster, and a row whose lanes all carry one digit is counted by one atomic
+        if (pass <= 1) {
+          // the top two bytes: scores cluster (background pages agree to a percent or so), and per-lane atomics
+          // would collide on one address: the lanes that share the first active lane's digit are counted by
+          // one atomic, the others add themselves
           const uint64_t am = __builtin_amdgcn_ballot_w64(act);
-          const uint32_t dl = __builtin_amdgcn_readlane(d, am ? __builtin_ctzll(am) : 0);
+          const int leader = am ? __builtin_ctzll(am) : 0;
+          const uint32_t dl = __builtin_amdgcn_readlane(d, leader);
           const uint64_t same = __builtin_amdgcn_ballot_w64(act && d == dl);
-          if (same == am) {
-            if (lane == 0 && am != 0ull) atomicAdd(&h[dl], static_cast<uint32_t>(__popcll(am)));
-          } else if (act) {
-            atomicAdd(&h[d], 1u);
-          }
+          if (lane == leader && am != 0ull) atomicAdd(&h[dl], static_cast<uint32_t>(__popcll(same)));
+          if (act && d != dl) atomicAdd(&h[d], 1u);
         } else if (act) {
           atomicAdd(&h[d], 1u);
         }
