@@ -114,7 +114,9 @@ struct RowMerge {
 };
 
 template <int MAXS>
-__global__ __launch_bounds__(128) void attn_combine_small_kernel(const CombineParams p) {   // launched with D threads
+__global__ __launch_bounds__(128) void attn_combine_small_kernel(VEGAS_COMBINE_HOT_PARAMS, const CombineParams pfull) {   // launched with D threads
+  CombineParams p = pfull;                   // what the requests depend on arrives preloaded in scalar registers
+  VEGAS_COMBINE_HOT_ASSIGN(p);
   const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const ColumnSlots cs = column_slots(p.plan, p.slots_total, b, p.Hkv, p.nsplit, p.chunk_tokens);

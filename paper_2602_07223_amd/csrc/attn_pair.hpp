@@ -34,7 +34,9 @@ constexpr int kPairWaves = 4;    // two pairs
 constexpr int kPairs = 2;
 
 template <int COLLECT, int D>
-__global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(const SplitParams p) {
+__global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPLIT_HOT_PARAMS, const SplitParams pfull) {
+  SplitParams p = pfull;                     // (see attn_split_kernel: the preloaded arguments)
+  VEGAS_SPLIT_HOT_ASSIGN(p);
   static_assert(D == 128 || D == 64, "head dimension");
   // Dynamic LDS: [pair][K tile | V tile][page lse or token sums | merge buffer (aliases everything before)]
   //              [queries, 64 rows][row maxima][row sums]

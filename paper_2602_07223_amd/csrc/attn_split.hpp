@@ -124,7 +124,11 @@ __device__ __forceinline__ void load_queries_to_lds(unsigned char* qlds, const S
 // D: head dimension.  64 halves everything that scales with it: a 16-byte K load covers 8 token rows instead of
 // 4, the first contraction has 4 steps, the output has 2 blocks of 32, a V load is 4 bytes (2 head dims).
 template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4, bool LOCAL = false, int D = 128>
-__global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(const SplitParams p) {
+__global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HOT_PARAMS, const SplitParams pfull) {
+  // What the first memory requests need arrives in scalar registers with the wave (kernel-argument preloading)
+  // instead of through a load of the argument block: one dependent round trip less at the head of the kernel.
+  SplitParams p = pfull;
+  VEGAS_SPLIT_HOT_ASSIGN(p);
   static_assert(PS == 4 || (!CAUSAL && COLLECT == 0 && !NT_LOADS), "small pages: draft calls only");
   static_assert(!LOCAL || (CAUSAL && COLLECT == 0), "local masking: verification without collection only");
   // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]

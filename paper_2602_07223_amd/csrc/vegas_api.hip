@@ -223,7 +223,7 @@ int ensure_dynamic_lds(const void* kern, size_t lds) {
 template <typename Kern>
 int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, const SplitParams& sp) {
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds)) return rc;
-  hipLaunchKernelGGL(kern, grid, block, lds, st, sp);
+  hipLaunchKernelGGL(kern, grid, block, lds, st, VEGAS_SPLIT_HOT_ARGS(sp), sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
@@ -342,23 +342,23 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   cp.slots_total = sp.slots_total;
   const dim3 grid(pl.R, sp.Hkv, d->batch);
   if (pl.nsplit <= 8)
-    hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<8>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 12)
-    hipLaunchKernelGGL(attn_combine_small_kernel<12>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<12>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 16)
-    hipLaunchKernelGGL(attn_combine_small_kernel<16>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<16>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 20)
-    hipLaunchKernelGGL(attn_combine_small_kernel<20>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<20>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 24)
-    hipLaunchKernelGGL(attn_combine_small_kernel<24>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<24>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 32)
-    hipLaunchKernelGGL(attn_combine_small_kernel<32>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<32>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 40)
-    hipLaunchKernelGGL(attn_combine_small_kernel<40>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<40>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 48)
-    hipLaunchKernelGGL(attn_combine_small_kernel<48>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<48>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else if (pl.nsplit <= 64)
-    hipLaunchKernelGGL(attn_combine_small_kernel<64>, grid, dim3(cp.D), 0, st, cp);
+    hipLaunchKernelGGL(attn_combine_small_kernel<64>, grid, dim3(cp.D), 0, st, VEGAS_COMBINE_HOT_ARGS(cp), cp);
   else
     hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(cp.D), 0, st, cp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;

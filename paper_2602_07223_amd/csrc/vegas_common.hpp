@@ -94,6 +94,26 @@ struct SplitParams {
   float scale_log2e;
 };
 
+// Leading kernel arguments of the streaming kernels: the fields of SplitParams that the first memory requests (page
+// ids, sequence length) depend on.  Leading scalar arguments are preloaded into scalar registers when a wave starts
+// (the library is built with kernel-argument preloading); the copies inside SplitParams are then not read.
+#define VEGAS_SPLIT_HOT_PARAMS                                                                                     \
+  const int32_t *hot_table, const int32_t *hot_lens, int2 *hot_plan, int32_t hot_table_stride, int32_t hot_chunk_tokens, \
+      int32_t hot_Hkv, int32_t hot_row_blocks, int32_t hot_nsplit
+#define VEGAS_SPLIT_HOT_ASSIGN(p)            \
+  do {                                       \
+    (p).table = hot_table;                   \
+    (p).lens = hot_lens;                     \
+    (p).plan = hot_plan;                     \
+    (p).table_stride = hot_table_stride;     \
+    (p).chunk_tokens = hot_chunk_tokens;     \
+    (p).Hkv = hot_Hkv;                       \
+    (p).row_blocks = hot_row_blocks;         \
+    (p).nsplit = hot_nsplit;                 \
+  } while (0)
+#define VEGAS_SPLIT_HOT_ARGS(sp) \
+  (sp).table, (sp).lens, (sp).plan, (sp).table_stride, (sp).chunk_tokens, (sp).Hkv, (sp).row_blocks, (sp).nsplit
+
 struct CombineParams {
   const float* part_o;
   const float2* part_ml;
@@ -105,6 +125,26 @@ struct CombineParams {
   const int2* plan;         // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens)
   int32_t slots_total;      // balanced chunking: partial slots per KV head
 };
+
+// Leading (preloaded) kernel arguments of the one-round-trip merge kernel: everything its requests depend on.
+#define VEGAS_COMBINE_HOT_PARAMS                                                                                   \
+  const float *hot_part_o, const float2 *hot_part_ml, const int32_t *hot_lens, const int2 *hot_plan, int32_t hot_R, \
+      int32_t hot_Hkv, int32_t hot_nsplit, int32_t hot_chunk_tokens, int32_t hot_D, int32_t hot_slots_total
+#define VEGAS_COMBINE_HOT_ASSIGN(p)          \
+  do {                                       \
+    (p).part_o = hot_part_o;                 \
+    (p).part_ml = hot_part_ml;               \
+    (p).lens = hot_lens;                     \
+    (p).plan = hot_plan;                     \
+    (p).R = hot_R;                           \
+    (p).Hkv = hot_Hkv;                       \
+    (p).nsplit = hot_nsplit;                 \
+    (p).chunk_tokens = hot_chunk_tokens;     \
+    (p).D = hot_D;                           \
+    (p).slots_total = hot_slots_total;       \
+  } while (0)
+#define VEGAS_COMBINE_HOT_ARGS(cp) \
+  (cp).part_o, (cp).part_ml, (cp).lens, (cp).plan, (cp).R, (cp).Hkv, (cp).nsplit, (cp).chunk_tokens, (cp).D, (cp).slots_total
 
 // The rows of one KV head (row = t * g + j for verification token t, head j of the group) whose page log-sum-exps
 // are collected: all G g rows (Eq. 2), or the g rows of the first verification token and the g rows of the bonus
