@@ -41,8 +41,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the verification streaming kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9989 and 1.0).
-VERIFY_TRAFFIC_BYTES = 138_511_360   # (131385 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
+# runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9987 and 1.0).
+VERIFY_TRAFFIC_BYTES = 138529792   # (131403 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
 DEFAULT_WORKLOAD = "ctx32k"
 ROTATE_BYTES = 1.2e9           # rotate cache copies up to about this much K+V in total
 
