@@ -239,8 +239,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     __syncthreads();
   }
 
-  // The search and the compaction, compiled once for keys held in LDS and once for keys recomputed from the
-  // scores (prefixes longer than the LDS area): the choice is uniform for the workgroup and taken once.
+  // The search and the compaction for prefixes of more than 8192 pages (only reached when a search is needed),
+  // compiled once for keys held in LDS and once for keys recomputed from the scores (prefixes longer than the LDS
+  // area): the choice is uniform for the workgroup and taken once.
   auto search_and_compact = [&](auto lds_tag) {
     constexpr bool kKeysInLds = decltype(lds_tag)::value;
     auto key_at = [&](int j) -> uint32_t {
@@ -252,8 +253,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     //      stops as soon as the digit bin that holds the kc-th key is needed whole (distinct scores: after three
     //      passes as a rule): T then is a key PREFIX, kmask its resolved bits, and every key with that prefix is
     //      a "tie".
-    uint32_t T = 0u, need_eq = 0u, kmask = 0xFFFFFFFFu;
-    if (need_search) {
+    uint32_t T, need_eq, kmask;
+    {
       uint32_t prefix = 0u, mask = 0u, need = static_cast<uint32_t>(kc);
 #pragma unroll 1
       for (int pass = 0; pass < 4; ++pass) {
@@ -348,7 +349,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     //      them 64 at a time (lane = page), so page order is (wave, step, lane) and every memory access is
     //      coalesced.  Ballots count the keys above T and the ties; a 16-entry prefix over the wave totals turns
     //      the counts into global tie ranks and output positions.
-    if (kc > 0) {
+    {
       constexpr int kWaves = kSelectThreads / 64;
       const int span = ((f0 + kWaves - 1) / kWaves + 63) / 64 * 64;
       const int w0 = min(wave * span, f0), w1 = min(w0 + span, f0);
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       // pass A: keys above T and ties in this wave's pages (up to four steps per trip).  A wave's takes follow
       //         from the counts: its keys above T plus as many of its ties as are still wanted.
       uint32_t eq_wave = 0u, gt_wave = 0u;
-      if (!take_all) {
+      {
         auto count_steps = [&](int base, auto steps_tag) {
           constexpr int kS = decltype(steps_tag)::value;
 #pragma unroll
@@ -370,8 +371,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
         int base = w0;
         for (; base + 64 * 3 < w1; base += 64 * 4) count_steps(base, std::integral_constant<int, 4>{});
         for (; base < w1; base += 64) count_steps(base, std::integral_constant<int, 1>{});
-      } else {
-        gt_wave = static_cast<uint32_t>(w1 - w0);
       }
       if (lane == 0) {
         wave_eq[wave] = eq_wave;
@@ -398,15 +397,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
         for (int i = 0; i < kGather; ++i) {
           if (base + 64 * i >= w1) break;
           const int j = base + 64 * i + lane;
-          bool take = j < w1 && take_all;
-          if (!take_all) {
-            const uint32_t key = key_at(min(j, f0 - 1)) & kmask;
-            const bool eq = j < w1 && key == T;
-            const bool gt = j < w1 && key > T;
-            const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
-            take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
-            eq_run += __popcll(beq);
-          }
+          const uint32_t key = key_at(min(j, f0 - 1)) & kmask;
+          const bool eq = j < w1 && key == T;
+          const bool gt = j < w1 && key > T;
+          const uint64_t beq = __builtin_amdgcn_ballot_w64(eq);
+          const bool take = gt || (eq && eq_run + __popcll(beq & lt) < need_eq);
+          eq_run += __popcll(beq);
           const uint64_t btk = __builtin_amdgcn_ballot_w64(take);
           if (take) {
             const uint32_t pos = pos_run + __popcll(btk & lt);
