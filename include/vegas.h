@@ -22,8 +22,8 @@
  *   - Query head h uses KV head h / (num_q_heads / num_kv_heads).
  *   - Return value: VEGAS_OK (0) or a negative vegas_status.  Errors that the host can detect are
  *     reported before anything is launched and leave every output untouched.  Page ids are clamped
- *     into [0, num_pages) and lengths into [0, max_blocks*page_size] on the device, so a corrupt
- *     table cannot fault; results are then unspecified.
+ *     into [0, num_pages) and lengths into [0, max_seq_len] on the device, so a corrupt table or
+ *     length cannot fault; results are then unspecified.
  *   - `workspace` is caller-owned device scratch of at least vegas_workspace_bytes(desc) bytes,
  *     256-byte aligned.  Its contents are meaningless between calls; calls that share a workspace
  *     must be ordered on one stream.
