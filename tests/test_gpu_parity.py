@@ -592,3 +592,42 @@ def test_loose_max_seq_len_does_not_change_results(Hq):
     for step in range(5):
         ref_d = O.draft_attention(L.q_draft[step], L.k_cache, L.v_cache, sel, ssl, L.softmax_scale)
         U.check_out(f"loose.draft{step}", path.out_draft[step], ref_d, vs)
+
+
+def test_corrupt_lengths_and_page_ids_are_clamped():
+    """The kernels clamp lengths into [0, max_seq_len] and page ids into [0, num_pages): a negative length
+    behaves as an empty sequence, a huge length and a table of garbage ids give unspecified results for
+    that sequence but touch nothing outside the caches, and a clean neighbour is unaffected."""
+    L = synth.make_random_case(seed=91, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[1500, 700, 900], logit_std=1.0, outliers=2)
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=256)
+    lens = dl.seq_lens.clone()
+    lens[1] = -5
+    lens[2] = 1 << 30
+    table = dl.block_table.clone()
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    table[2] = torch.randint(-(1 << 31), (1 << 31) - 1, (table.shape[1],), generator=gen, dtype=torch.int64).to(torch.int32).to(table.device)
+    bad = harness.DeviceLayer(dl.q_verify, dl.q_draft, dl.k_cache, dl.v_cache, table, lens)
+    print("[case] corrupt lengths and page ids", flush=True)
+    path.out_verify.fill_(float("nan"))
+    path.iteration(bad)
+    torch.cuda.synchronize()
+    G = L.spec.num_queries
+    # the clean sequence: against the oracle run on it alone
+    ref_out, ref_scores = O.verify_attention(L.q_verify[:1], L.k_cache, L.v_cache, L.block_table[:1], L.seq_lens[:1],
+                                             L.softmax_scale, vb.COLLECT_ALL_ROWS)
+    vs = U.vmax_visible(L)
+    U.check_out("corrupt.clean.verify", path.out_verify[:1], ref_out, vs)
+    U.check_scores("corrupt.clean.scores", path.block_scores[:1], ref_scores)
+    sel = path.sel_table.cpu().numpy()
+    ssl = path.sel_seq_lens.cpu().numpy()
+    for s in range(G):
+        ref_d = O.draft_attention(L.q_draft[s][:1], L.k_cache, L.v_cache, sel[:1], ssl[:1], L.softmax_scale)
+        U.check_out(f"corrupt.clean.draft{s}", path.out_draft[s][:1], ref_d, vs)
+    # the sequence with a negative length is an empty one
+    assert bool((path.out_verify[1].view(torch.int16) == 0).all())
+    assert int(ssl[1]) == 0 and bool((sel[1] == -1).all())
+    assert bool((path.block_scores[1] == 0).all())
+    # the sequence with the huge length was cut at max_seq_len: its selection is within the row and padded
+    assert 0 <= int(ssl[2]) <= path.desc_draft.max_seq_len
