@@ -289,3 +289,43 @@ def test_token_chain_ctx32k_full():
 def test_token_chain_ctx128k_full():
     L = synth.make_layer(synth.CONFIGS["ctx128k_drift"])
     run_token_chain(L, int(0.07 * 131072), name="token_chain_ctx128k")
+
+
+def test_token_variant_clamps_corrupt_lengths_and_page_ids():
+    """As for the page variant: a negative length is an empty sequence, a huge length and garbage page ids stay
+    inside the caches, the clean neighbour's token selection and draft outputs are what they are without them."""
+    L = synth.make_random_case(seed=613, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=5,
+                               seq_lens=[1500, 700, 900], logit_std=1.5, outliers=2, outlier_logit=20.0)
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=200, token_granular=True, collect_rows=vb.COLLECT_FIRST_LAST)
+    lens = dl.seq_lens.clone()
+    lens[1] = -5
+    lens[2] = 1 << 30
+    table = dl.block_table.clone()
+    gen = torch.Generator(device="cpu").manual_seed(6)
+    table[2] = torch.randint(-(1 << 31), (1 << 31) - 1, (table.shape[1],), generator=gen, dtype=torch.int64).to(torch.int32).to(table.device)
+    bad = harness.DeviceLayer(dl.q_verify, dl.q_draft, dl.k_cache, dl.v_cache, table, lens)
+    print("[case] token variant, corrupt lengths and page ids", flush=True)
+    path.iteration(bad)
+    # growth of the selection with the same corrupt lengths: must complete as well
+    s = L.spec
+    desc_grow = vb.make_desc(batch=s.batch, num_q_heads=s.num_q_heads, num_kv_heads=s.num_kv_heads, num_queries=1,
+                             max_blocks=L.max_blocks, max_sel_blocks=path.max_sel_blocks,
+                             max_seq_len=min(path.max_sel_blocks, L.max_blocks * PAGE), num_pages=L.num_pages * PAGE,
+                             softmax_scale=L.softmax_scale, page_size=1)
+    vb.vegas_extend_selection(desc_grow, table, lens, 1, path.sel_table, path.sel_seq_lens)
+    torch.cuda.synchronize()
+    path.iteration(bad)
+    torch.cuda.synchronize()
+    G = L.spec.num_queries
+    sel, ssl = path.sel_table.cpu().numpy(), path.sel_seq_lens.cpu().numpy()
+    # clean sequence: its token selection from the GPU's own scores is the oracle's, and the draft over it matches
+    got_scores = path.block_scores.cpu().numpy()
+    ref_sel, ref_ssl, _ = O.select_tokens(got_scores[:1], L.block_table[:1], L.seq_lens[:1], G, 200, path.max_sel_blocks)
+    assert np.array_equal(sel[:1], ref_sel) and np.array_equal(ssl[:1], ref_ssl)
+    kc1 = L.k_cache.reshape(-1, 1, L.spec.num_kv_heads, L.spec.head_dim)
+    vc1 = L.v_cache.reshape(-1, 1, L.spec.num_kv_heads, L.spec.head_dim)
+    ref_d = O.draft_attention(L.q_draft[0][:1], kc1, vc1, sel[:1], ssl[:1], L.softmax_scale)
+    U.check_out("token.corrupt.clean.draft0", path.out_draft[0][:1], ref_d, U.vmax_visible(L))
+    assert int(ssl[1]) == 0 and bool((sel[1] == -1).all())
+    assert 0 <= int(ssl[2]) <= path.max_sel_blocks
