@@ -395,9 +395,42 @@ def main() -> int:
             graph.replay()
         torch.cuda.synchronize()
         graph_us = (time.perf_counter() - t0) / (replays * len(copies)) * 1e6
+        # (4) the launch floor: the library's smallest kernel (selection growth on an empty selection: it reads one
+        #     length and returns), 200 dependent launches replayed from a graph, and the same calls issued eagerly
+        #     through the binding (which measures the host: the GPU is waiting)
+        tiny = vb.make_desc(batch=1, num_q_heads=spec.num_q_heads, num_kv_heads=spec.num_kv_heads, num_queries=1,
+                            max_blocks=64, max_sel_blocks=64, max_seq_len=1024, num_pages=64,
+                            softmax_scale=1.0, head_dim=spec.head_dim)
+        t_table = torch.zeros((1, 64), dtype=torch.int32, device=dev)
+        t_lens = torch.full((1,), 100, dtype=torch.int32, device=dev)
+        t_sel = torch.full((1, 64), -1, dtype=torch.int32, device=dev)
+        t_ssl = torch.zeros((1,), dtype=torch.int32, device=dev)
+        tiny_args = (tiny, t_table.data_ptr(), t_lens.data_ptr(), 1, t_sel.data_ptr(), t_ssl.data_ptr())
+        with torch.cuda.stream(side):
+            vb.vegas_extend_selection(*tiny_args, stream=side.cuda_stream)
+        torch.cuda.synchronize()
+        floor_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(floor_graph, stream=side):
+            for _ in range(200):
+                vb.vegas_extend_selection(*tiny_args, stream=side.cuda_stream)
+        torch.cuda.synchronize()
+        floor_graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            floor_graph.replay()
+        torch.cuda.synchronize()
+        floor_graph_us = (time.perf_counter() - t0) / (20 * 200) * 1e6
+        t0 = time.perf_counter()
+        for _ in range(2000):
+            vb.vegas_extend_selection(*tiny_args, stream=stream)
+        torch.cuda.synchronize()
+        floor_eager_us = (time.perf_counter() - t0) / 2000 * 1e6
         out["extras"] = {"iteration_us_p10": percentile(per, 0.1), "iteration_us_p50": percentile(per, 0.5),
                          "iteration_us_p90": percentile(per, 0.9), "iteration_us_warm_cache": warm_us,
-                         "iteration_us_hip_graph": graph_us}
+                         "iteration_us_hip_graph": graph_us,
+                         "launch_floor_us_graph_replay": floor_graph_us,
+                         "launch_floor_us_eager_through_binding": floor_eager_us}
 
     if not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0 and not token and not args.budget:
         out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens, workload)
