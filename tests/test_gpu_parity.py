@@ -391,6 +391,56 @@ def test_select_bit_exact_with_ties_and_budgets():
         assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
 
 
+SCORE_KINDS = ["uniform", "all_equal", "four_values", "signed", "clustered_1_percent", "denormal", "zeros_and_inf"]
+
+
+@pytest.mark.parametrize("pages", [65, 2048, 8193])
+@pytest.mark.parametrize("kind", SCORE_KINDS)
+def test_select_is_bit_exact_on_any_score_distribution(kind, pages):
+    """Selection is integer work on the score bits: whatever the scores look like -- ties everywhere, negative
+    values, scores that agree to a percent (the top two key bytes collide), denormals, zeros and infinities --
+    the result on identical fp32 scores is the oracle's, bit for bit, with and without per-sequence budgets."""
+    rng = np.random.default_rng(9100 + pages + len(kind))
+    B, G = 3, 5
+    lens = np.array([pages * PAGE - 2, (pages // 2) * PAGE + 9, 7], dtype=np.int32)
+    scores = np.zeros((B, pages), dtype=np.float32)
+    for b in range(B):
+        if kind == "uniform":
+            x = rng.random(pages)
+        elif kind == "all_equal":
+            x = np.full(pages, 0.25)
+        elif kind == "four_values":
+            x = rng.integers(0, 4, pages) * 0.125
+        elif kind == "signed":
+            x = rng.standard_normal(pages)
+        elif kind == "clustered_1_percent":
+            x = (1.0 + rng.random(pages) * 0.01) / pages
+        elif kind == "denormal":
+            x = rng.random(pages) * 1e-42
+        else:
+            x = rng.random(pages) ** 8
+            x[rng.integers(0, pages, size=pages // 4)] = 0.0
+            x[rng.integers(0, pages, size=3)] = np.inf
+        scores[b] = x.astype(np.float32)
+    table = np.stack([rng.permutation(pages + 7)[:pages] for _ in range(B)]).astype(np.int32)
+    dev = torch.device("cuda:0")
+    for budget, budgets in ((pages, None), (100, np.array([pages * 3, 1, 100], dtype=np.int32))):
+        kmax = (int(budgets.max()) if budgets is not None else budget) // PAGE + 1
+        msb = min(kmax, pages) + 2
+        desc = vb.make_desc(batch=B, num_q_heads=32, num_kv_heads=8, num_queries=G, max_blocks=pages,
+                            max_sel_blocks=msb, max_seq_len=pages * PAGE, num_pages=pages + 7, softmax_scale=0.1)
+        sel = torch.empty((B, msb), dtype=torch.int32, device=dev)
+        ssl = torch.empty((B,), dtype=torch.int32, device=dev)
+        print(f"[case] select {kind} pages={pages} budget={budget} per_sequence={budgets is not None}", flush=True)
+        vb.vegas_select_blocks(desc, torch.from_numpy(scores).to(dev), torch.from_numpy(table).to(dev),
+                               torch.from_numpy(lens).to(dev), budget, sel, ssl,
+                               budgets=None if budgets is None else torch.from_numpy(budgets).to(dev))
+        torch.cuda.synchronize()
+        ref_sel, ref_ssl, _ = O.select_blocks(scores, table, lens, G, budget, msb, budgets=budgets)
+        assert np.array_equal(sel.cpu().numpy(), ref_sel)
+        assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
+
+
 @pytest.mark.parametrize("pages", [9000, 16384, 20011])
 def test_select_long_sequences(pages):
     """Page counts above what the other cases reach: keys that fill the kernel's LDS budget and, past it,
