@@ -112,6 +112,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
     }
     // radix select (see the general path below for the early exit)
     uint32_t prefix = 0u, mask = 0u, need = static_cast<uint32_t>(kc);
+    // Scores cluster: the top byte of nearly all keys is the same, background pages often agree to a percent (two
+    // bytes), tie-heavy scores in every byte -- and per-lane atomics would then collide on one LDS address.  A pass
+    // whose predecessor left at least three quarters of its keys in one bin counts the lanes that share the first
+    // active lane's digit with ONE atomic (the others add themselves); otherwise digits are spread and every lane
+    // adds itself, which is fewer instructions.
+    bool clustered = true;
+    uint32_t active = static_cast<uint32_t>(f0);
 #pragma unroll 1
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
@@ -123,10 +130,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
         if (u >= rows) continue;
         const bool act = u * kSelectThreads + tid < f0 && (key[u] & mask) == prefix;
         const uint32_t d = (key[u] >> shift) & 255u;
-        if (pass <= 1) {
-          // the top two bytes: scores cluster (background pages agree to a percent or so), and per-lane atomics
-          // would collide on one address: the lanes that share the first active lane's digit are counted by
-          // one atomic, the others add themselves
+        if (clustered) {
           const uint64_t am = __builtin_amdgcn_ballot_w64(act);
           const int leader = am ? __builtin_ctzll(am) : 0;
           const uint32_t dl = __builtin_amdgcn_readlane(d, leader);
@@ -161,7 +165,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
       prefix = sh_prefix;
       need = sh_need;
       mask |= 255u << shift;
-      if (sh_count == need) break;             // the whole bin is taken: its lower digits do not matter
+      const uint32_t count = sh_count;         // keys in the chosen bin: the next pass's active keys
+      if (count == need) break;                // the whole bin is taken: its lower digits do not matter
+      clustered = 4u * count >= 3u * active;
+      active = count;
     }
     const uint32_t T = prefix, need_eq = need, kmask = mask;
     // compaction: per cell the keys above T and the ties; one wave turns the 128 counts into tie ranks and
