@@ -124,6 +124,12 @@ __global__ __launch_bounds__(kTokThreads) void token_select_hist(const TokenSele
   const int base = s * kTokSlice;
   if (!t.need_search || base >= t.p_len) return;
   const int nslices = (t.p_len + kTokSlice - 1) / kTokSlice;
+  // The thread's scores do not depend on the earlier passes: they are requested first (together, clamped indices,
+  // none behind a branch), so their round trip overlaps the one of the slices' histograms.
+  const float* scores = p.scores + static_cast<int64_t>(b) * p.max_blocks * kPage;
+  float sc[kTokSlice / kTokThreads];
+#pragma unroll
+  for (int it = 0; it < kTokSlice / kTokThreads; ++it) sc[it] = scores[min(base + it * kTokThreads + tid, t.p_len - 1)];
   uint32_t* h = hist[wave];
 #pragma unroll
   for (int i = 0; i < 4; ++i) h[lane + 64 * i] = 0u;
@@ -137,16 +143,11 @@ __global__ __launch_bounds__(kTokThreads) void token_select_hist(const TokenSele
   const uint32_t prefix = sh_prefix;
   const uint32_t mask = pass == 0 ? 0u : (0xFFFFFFFFu << (32 - 8 * pass));
   const int shift = 24 - 8 * pass;
-  const float* scores = p.scores + static_cast<int64_t>(b) * p.max_blocks * kPage;
 #pragma unroll
   for (int it = 0; it < kTokSlice / kTokThreads; ++it) {
     const int j = base + it * kTokThreads + tid;
-    uint32_t key = 0u;
-    bool act = false;
-    if (j < t.p_len) {
-      key = score_key(scores[j]);
-      act = (key & mask) == prefix;
-    }
+    const uint32_t key = score_key(sc[it]);
+    bool act = j < t.p_len && (key & mask) == prefix;
     const uint32_t d = (key >> shift) & 255u;
     // lanes that share the leader's digit are counted by one atomic; what is left after two rounds adds itself
 #pragma unroll
@@ -191,6 +192,21 @@ __global__ __launch_bounds__(kTokThreads) void token_select_write(const TokenSel
 
   const int base = s * kTokSlice;
   if (t.kc == 0 || base >= t.p_len) return;
+  // This thread's tokens (wave w owns tokens [base + 256 w, base + 256 (w + 1)), 64 per step, lane = token): their
+  // scores and the table entries of their pages are requested now, unconditionally and together, so that the
+  // round trip overlaps the one of the slices' histograms and no request waits behind a decision.
+  constexpr int kSteps = kTokSlice / kTokThreads;
+  const int w0 = base + wave * (64 * kSteps);
+  uint32_t key[kSteps];
+  int32_t page_of[kSteps];
+  bool valid[kSteps];
+#pragma unroll
+  for (int st = 0; st < kSteps; ++st) {
+    const int j = w0 + 64 * st + lane;
+    valid[st] = j < t.p_len;
+    key[st] = score_key(scores[min(j, t.p_len - 1)]);
+    page_of[st] = table[min(j, t.p_len - 1) >> 4];
+  }
   if (t.need_search) {
     const int nslices = (t.p_len + kTokSlice - 1) / kTokSlice;
     token_sum_hists(p, b, 4, nslices, s, sh_tot, sh_bef);
@@ -225,18 +241,8 @@ __global__ __launch_bounds__(kTokThreads) void token_select_write(const TokenSel
   const uint32_t slice_eq_before = all ? 0u : sh_eq_before;
   const uint32_t slice_pos_before = all ? static_cast<uint32_t>(base) : sh_pos_before;
 
-  // ---- ordered compaction: wave w owns tokens [base + 256 w, base + 256 (w + 1)), 64 per step (lane = token)
-  constexpr int kSteps = kTokSlice / kTokThreads;
-  const int w0 = base + wave * (64 * kSteps);
+  // ---- ordered compaction
   const uint64_t lt = (1ull << lane) - 1ull;
-  uint32_t key[kSteps];
-  bool valid[kSteps];
-#pragma unroll
-  for (int st = 0; st < kSteps; ++st) {
-    const int j = w0 + 64 * st + lane;
-    valid[st] = j < t.p_len;
-    key[st] = (valid[st] && !all) ? score_key(scores[j]) : 0u;
-  }
   uint32_t eq_wave = 0u;
 #pragma unroll
   for (int st = 0; st < kSteps; ++st) eq_wave += __popcll(__builtin_amdgcn_ballot_w64(valid[st] && !all && key[st] == T));
@@ -264,7 +270,7 @@ __global__ __launch_bounds__(kTokThreads) void token_select_write(const TokenSel
     const uint64_t btk = __builtin_amdgcn_ballot_w64(take[st]);
     if (take[st]) {
       const uint32_t pos = pos_run + __popcll(btk & lt);
-      if (pos < static_cast<uint32_t>(p.max_sel)) sel[pos] = slot_of(w0 + 64 * st + lane);
+      if (pos < static_cast<uint32_t>(p.max_sel)) sel[pos] = page_of[st] * kPage + ((w0 + 64 * st + lane) & 15);
     }
     pos_run += __popcll(btk);
   }
