@@ -227,13 +227,21 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
     const int cap = p.max_blocks * kPage;
     if (i0 >= cap) return;
     int n = p.lens[b];
+    // The heads' partial sums are requested eight at a time, unconditionally (clamped), before the length is needed.
+    const int iload = min(i0, p.lse_pages - 4);
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int h0 = 0; h0 < p.Hkv; h0 += 8) {
+      f32x4 part[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        part[u] = *reinterpret_cast<const f32x4*>(
+            p.page_lse + (static_cast<int64_t>(b) * p.Hkv + min(h0 + u, p.Hkv - 1)) * p.lse_pages + iload);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (h0 + u < p.Hkv) sum += part[u];
+    }
     n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
     const int p_len = max(n - p.G, 0);
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    if (i0 < p_len) {
-      for (int h = 0; h < p.Hkv; ++h)
-        sum += *reinterpret_cast<const f32x4*>(p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + i0);
-    }
     f32x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = (i0 + e < p_len) ? sum[e] * p.tok_norm : 0.f;
