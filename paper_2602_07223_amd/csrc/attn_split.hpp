@@ -74,16 +74,25 @@ __device__ __forceinline__ void load_queries_to_lds(unsigned char* qlds, const S
           p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
     }
     if (with_sums && row == valid) {
+      // sum over the collected rows (Eq. 2: all; Eq. 3: first draft row and bonus row) in ascending row order,
+      // eight requests in flight at a time
       float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int t = 0; t < p.G; ++t) {
-        if (p.collect_rows != 1 && t != 0 && t != p.G - 1) continue;       // Eq. 3: first draft row and bonus row
-        for (int j = 0; j < p.g; ++j) {
-          const u32x4 qv = *reinterpret_cast<const u32x4*>(
+      for (int c0 = 0; c0 < p.Rc; c0 += 8) {
+        u32x4 qv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int r = collected_row(min(c0 + u, p.Rc - 1), p.collect_rows, p.G, p.g);
+          const int t = r / p.g, j = r % p.g;
+          qv[u] = *reinterpret_cast<const u32x4*>(
               p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (c0 + u >= p.Rc) continue;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] & 0xFFFFu));
-            sum[2 * e + 1] += bf16_bits_to_float(static_cast<uint16_t>(qv[e] >> 16));
+            sum[2 * e] += bf16_bits_to_float(static_cast<uint16_t>(qv[u][e] & 0xFFFFu));
+            sum[2 * e + 1] += bf16_bits_to_float(static_cast<uint16_t>(qv[u][e] >> 16));
           }
         }
       }
