@@ -176,6 +176,24 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const FinalizePara
       int n = p.lens[b];
       n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
       const int ns = (n + cs.chunk - 1) / cs.chunk;
+      // The host's bound on the chunks of one sequence may be far above what this sequence has (balanced chunking
+      // bounds it by all the slots of a head): with few chunks the one-round-trip merge is taken after all.
+      if (ns <= 32) {
+        if (ns <= 16) {
+          RowMerge<16> rm;
+          rm.issue(ml, p.part_o + (pbase * p.R + r) * T, t128, p.R, cs.last, T);
+          o = rm.finish(ns);
+        } else {
+          RowMerge<32> rm;
+          rm.issue(ml, p.part_o + (pbase * p.R + r) * T, t128, p.R, cs.last, T);
+          o = rm.finish(ns);
+        }
+        if (valid) {
+          const int t = r / p.g, j = r % p.g;
+          p.out[((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * T + t128] = float_to_bf16_bits(o);
+        }
+        return;
+      }
       const float* po = p.part_o + (pbase * p.R + r) * T + t128;
       float* sw = smf + sub * T;
       float* sred = smf + 256 + sub * 4;
