@@ -147,6 +147,26 @@ def test_random_ragged_batches(i):
     run_chain(L, c["budget"], collect=c["collect"], name=f"random_batch{i}")
 
 
+LARGE_BATCHES = [
+    # name, B, Hq, Hkv, G, D, longest, budget
+    ("b300_short", 300, 32, 8, 5, 128, 200, 64),
+    ("b1000_tiny_hd64", 1000, 8, 2, 3, 64, 64, 32),
+    ("b130_two_row_blocks", 130, 64, 8, 5, 128, 400, 128),
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,G,D,longest,budget", LARGE_BATCHES, ids=[c[0] for c in LARGE_BATCHES])
+def test_large_batches_of_short_sequences(name, B, Hq, Hkv, G, D, longest, budget):
+    """Batches beyond what the per-sequence chunk plan serves (more than 64 sequences): sequences are a grid
+    dimension, most workgroups own a whole short sequence, some sequences are empty or shorter than the rows."""
+    rng = np.random.default_rng(77000 + B)
+    lens = [int(rng.integers(0, longest + 1)) if rng.random() < 0.9 else int(rng.integers(0, G + 1)) for _ in range(B)]
+    lens[0] = longest
+    L = synth.make_random_case(seed=8800 + B, batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=G,
+                               seq_lens=lens, head_dim=D, logit_std=1.0, value_std=1.0, outliers=1, outlier_logit=20.0)
+    run_chain(L, budget, name=name)
+
+
 @pytest.mark.parametrize("collect", [vb.COLLECT_FIRST_LAST, vb.COLLECT_ALL_ROWS])
 def test_collect_modes(collect):
     L = synth.make_random_case(seed=77, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=6,
