@@ -253,6 +253,17 @@ def test_token_chain_head_dim_64():
     run_token_chain(L, 257, collect=vb.COLLECT_ALL_ROWS, name="token_chain_hd64")
 
 
+def test_token_chain_large_batch():
+    """200 short sequences (some empty or shorter than the verification rows): the token variant's kernels take
+    sequences as a grid dimension too."""
+    rng = np.random.default_rng(4242)
+    lens = [int(rng.integers(0, 301)) if rng.random() < 0.9 else int(rng.integers(0, 6)) for _ in range(200)]
+    lens[0] = 300
+    L = synth.make_random_case(seed=613, batch=200, num_q_heads=32, num_kv_heads=8, num_queries=5, seq_lens=lens,
+                               logit_std=1.5, value_std=1.0, outliers=1, outlier_logit=20.0)
+    run_token_chain(L, 40, name="token_chain_b200")
+
+
 def random_token_case(i):
     """Shape i of a seeded sweep over KV heads, group sizes, rows, batch, head dimension, lengths, budgets."""
     rng = np.random.default_rng(77000 + i)
