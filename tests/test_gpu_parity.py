@@ -461,7 +461,7 @@ def test_select_is_bit_exact_on_any_score_distribution(kind, pages):
         assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
 
 
-@pytest.mark.parametrize("pages", [9000, 16384, 20011])
+@pytest.mark.parametrize("pages", [9000, 16384, 20011, 65537])
 def test_select_long_sequences(pages):
     """Page counts above what the other cases reach: keys that fill the kernel's LDS budget and, past it,
     the path that re-reads the scores; scores drawn like attention mass (a few large, most tiny, ties)."""
