@@ -42,7 +42,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the verification streaming kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9987 and 1.0).
-VERIFY_TRAFFIC_BYTES = 138529792   # (131403 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
+VERIFY_TRAFFIC_BYTES = {
+    "ctx32k": 138529792,       # (131403 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
+    "ragged16": 2431006310,    # (2307017 KiB fetched + 67013 KiB written), profiles/ragged16_hbm_traffic_pmc.md
+}
 DEFAULT_WORKLOAD = "ctx32k"
 ROTATE_BYTES = 1.2e9           # rotate cache copies up to about this much K+V in total
 
@@ -318,7 +321,7 @@ def main() -> int:
         desc.launch_stages = 0
         return e0.elapsed_ms(e1) / reps * 1e3
 
-    traffic = VERIFY_TRAFFIC_BYTES if workload == DEFAULT_WORKLOAD and args.verify_chunk == 0 and not token else None
+    traffic = VERIFY_TRAFFIC_BYTES.get(workload) if args.verify_chunk == 0 and not token else None
     rows_per_kv_head = G * (spec.num_q_heads // spec.num_kv_heads)
     vkernel = "attn_pair_kernel<collect>" if 32 < rows_per_kv_head <= 64 else "attn_split_kernel<causal, collect>"
     roofline = {"bound": "hbm", "kernel": vkernel + " (KV-streaming kernel of vegas_verify_attention)",
