@@ -67,7 +67,9 @@ enum {
 /* Kernels of an attention call, for vegas_desc.launch_stages. */
 enum {
   VEGAS_STAGE_STREAM = 1,  /* the KV-streaming kernel (reads the cache, writes chunk partials) */
-  VEGAS_STAGE_MERGE = 2    /* merge of the chunk partials, and the page scores for verification */
+  VEGAS_STAGE_MERGE = 2    /* merge of the chunk partials, and the page scores for verification; a draft call
+                              whose selection is short enough for one chunk per (sequence, KV head) has no such
+                              kernel: its streaming kernel writes `out` itself */
 };
 
 typedef struct vegas_desc {

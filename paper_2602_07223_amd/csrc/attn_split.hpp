@@ -218,7 +218,15 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
 
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
-  if (c0 >= n) return;                       // whole workgroup: nothing to do, no partial is read
+  if (c0 >= n) {                             // whole workgroup: nothing to do, no partial is read
+    if (p.out_direct != nullptr) {           // no merge kernel follows: the rows of an empty sequence are zeros
+      for (int e = tid; e < Rl * D; e += NW * 64) {
+        const int r = row0 + e / D;
+        p.out_direct[((static_cast<int64_t>(b) * p.G + r / p.g) * p.Hq + h * p.g + r % p.g) * D + e % D] = 0;
+      }
+    }
+    return;
+  }
   const int c1 = min(c0 + chunk_tokens, n);
   // Local masking: no row sees a token before lo_min; chunks and tiles wholly before it are skipped.
   const int lo_min = LOCAL ? max(n - p.G - p.window + 1, 0) : 0;
@@ -552,6 +560,23 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     }
   }
   __syncthreads();
+  if (p.out_direct != nullptr) {
+    // The only chunk of its (sequence, KV head): the workgroup's sums are the whole result, so it divides by the
+    // softmax denominator and writes the bf16 rows itself (Eq. 1); no partials, no merge kernel.
+    for (int e = tid; e < Rl * D; e += NW * 64) {
+      const int row = e / D, d = e % D;
+      float sum = 0.f, lw = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        sum += red[(w * Rl + row) * kRedPitch + d];
+        lw += sm_l[w * (NB * 32) + row];
+      }
+      const int r = row0 + row;
+      p.out_direct[((static_cast<int64_t>(b) * p.G + r / p.g) * p.Hq + h * p.g + r % p.g) * D + d] =
+          float_to_bf16_bits(lw > 0.f ? sum / lw : 0.f);
+    }
+    return;
+  }
   float* po = p.part_o + (pbase * p.R + row0) * D;
   for (int e = tid; e < Rl * D; e += NW * 64) {
     const int row = e / D, d = e % D;

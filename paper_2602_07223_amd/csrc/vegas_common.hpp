@@ -81,6 +81,8 @@ struct SplitParams {
   int32_t collect_rows;     // which verification rows are collected (1: all, 2: first and last)
   int32_t Rc;               // collected rows per KV head (collected_count)
   int32_t window;           // > 0: local masking, a row at position pos sees keys pos - window + 1 .. pos (causal calls)
+  uint16_t* out_direct;     // draft calls with one chunk per (sequence, KV head): the bf16 output [B, G, Hq, D], which
+                            // the streaming kernel then normalises and writes itself (nullptr: partials for a merge kernel)
   float* trash;             // attn_pair_kernel: a word of the workspace that takes the stores of invalid elements
   int2* plan;               // balanced chunking (or nullptr): [B] (first partial slot, chunk tokens) per sequence,
                             // computed by every workgroup from the lengths and written here by workgroup 0

@@ -148,3 +148,64 @@ def test_table5_shape_sampled_against_oracle(P):
     ref = O.draft_attention(q_bits[sample], kc, vc, ids[sample], ssl[sample], D ** -0.5)
     vmax = float(np.abs(O.decode_bf16(v_bits[:64])).max())
     U.check_out(f"table5_shape.P{P}", out[sample], ref, vmax)
+
+
+FINISH_CASES = [
+    # name, B, Hq, Hkv, D, P, lens
+    ("hd128_pages16", 3, 32, 8, 128, 16, [4000, 0, 700]),
+    ("hd64_pages16", 2, 32, 4, 64, 16, [2500, 37]),
+    ("three_row_blocks", 2, 80, 1, 128, 16, [1200, 5]),
+    ("one_token_pages", 3, 16, 2, 128, 1, [900, 0, 288]),
+    ("two_token_pages_hd64", 2, 8, 8, 64, 2, [300, 1]),
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,D,P,lens", FINISH_CASES, ids=[c[0] for c in FINISH_CASES])
+def test_short_selections_need_no_merge_kernel(name, B, Hq, Hkv, D, P, lens):
+    """At most 288 selected tokens and no chunk length passed: one workgroup per (sequence, KV head, row block)
+    streams the whole selection and writes the output rows itself.  Checked against the oracle, against the same
+    call cut into 64-token chunks with a merge kernel, and on empty sequences (rows of zeros)."""
+    rng = np.random.default_rng(len(name))
+    L = synth.make_random_case(seed=940 + len(name), batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=2,
+                               seq_lens=lens, head_dim=D, logit_std=1.5, value_std=1.0, outliers=2, outlier_logit=20.0)
+    budget_pages = 256 // P
+    rows, sl = [], []
+    for b in range(B):
+        n = int(L.seq_lens[b])
+        npg = (n + P - 1) // P
+        if npg == 0:
+            rows.append(np.zeros(0, dtype=np.int64)); sl.append(0); continue
+        k = min(budget_pages, npg)
+        logical = np.concatenate([np.sort(rng.choice(npg - 1, size=k - 1, replace=False)) if k > 1 else
+                                  np.zeros(0, np.int64), [npg - 1]]).astype(np.int64)
+        rows.append(L.block_table[b, (logical * P) // PAGE].astype(np.int64) * (PAGE // P) + ((logical * P) % PAGE) // P)
+        sl.append(P * (k - 1) + (n - P * (npg - 1)))
+    msb = budget_pages + 2 * (PAGE // P)                        # two 16-token pages of slack: 288 tokens at most
+    sel = np.full((B, msb), -1, dtype=np.int32)
+    for b, r in enumerate(rows):
+        sel[b, :len(r)] = r
+    ssl = np.array(sl, dtype=np.int32)
+    print(f"[case] merge-free draft {name} ssl={list(ssl)}", flush=True)
+    s = L.spec
+    desc = vb.make_desc(batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=1, max_blocks=msb, max_sel_blocks=msb,
+                        max_seq_len=msb * P, num_pages=L.num_pages * (PAGE // P), softmax_scale=L.softmax_scale,
+                        page_size=P, head_dim=D)
+    dev = torch.device("cuda:0")
+    args = (harness.bf16_to_device(L.q_draft[0], dev), harness.bf16_to_device(L.k_cache, dev),
+            harness.bf16_to_device(L.v_cache, dev), torch.from_numpy(sel).to(dev), torch.from_numpy(ssl).to(dev))
+    ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    ws.fill_(0xFF)
+    out = torch.full((B, Hq, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    desc.launch_stages = vb.STAGE_STREAM                        # the streaming kernel alone completes the call
+    vb.vegas_draft_attention(desc, *args, out, ws)
+    torch.cuda.synchronize()
+    kc = L.k_cache.reshape(-1, P, Hkv, D)
+    vc = L.v_cache.reshape(-1, P, Hkv, D)
+    ref = O.draft_attention(L.q_draft[0], kc, vc, sel, ssl, L.softmax_scale)
+    U.check_out(name + ".merge_free", out, ref, U.vmax_visible(L))
+    for b in range(B):
+        if ssl[b] == 0:
+            assert not out[b].float().abs().any(), "rows of an empty sequence must be zeros"
+    chunked = draft_small_pages(L, P, sel, ssl, step=0, chunk=64)
+    U.check_out(name + ".chunked", chunked, ref, U.vmax_visible(L))
+    assert (out.float() - chunked.float()).abs().max().item() <= 2e-3 * U.vmax_visible(L)
