@@ -240,9 +240,10 @@ def test_ragged_batch_one_row_block_full():
     run_chain(L, L.spec.budget_tokens, collect=vb.COLLECT_FIRST_LAST, name="ragged16_32heads")
 
 
-@pytest.mark.parametrize("layer", [0, 13, 31])
-def test_baseline_config5_sampled_layers(layer):
-    """The 32-layer stack is 32 independent single-layer calls; three layers are checked in full."""
+@pytest.mark.parametrize("layer", range(32))
+def test_baseline_config5_every_layer(layer):
+    """The 32-layer stack is 32 independent single-layer calls (own seed each); every layer is checked in full,
+    one at a time (generate, upload, run, oracle, compare, drop)."""
     L = synth.make_layer(synth.CONFIGS["stack32"], layer=layer)
     run_chain(L, L.spec.budget_tokens, name=f"stack32.layer{layer}")
 
