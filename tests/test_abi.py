@@ -169,3 +169,13 @@ def test_binding_refuses_tensors_smaller_than_the_descriptor():
                    kv_page_stride=view.stride(0), kv_token_stride=view.stride(1), kv_head_stride=view.stride(2))
     assert vb._avail_bytes(view) >= vb.cache_extent_bytes(dv)
     assert vb._avail_bytes(view[1:]) < vb.cache_extent_bytes(dv)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; bench.py says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and not r.stdout.strip()
