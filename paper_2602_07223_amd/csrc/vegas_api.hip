@@ -22,7 +22,9 @@ using namespace vegas;
 
 constexpr int kNumCU = 256;           // MI355X compute units
 constexpr size_t kAlign = 256;
-constexpr int kFinishTokens = 288;    // longest selection a draft call streams with one workgroup per (sequence, KV head)
+// longest selection a draft call streams with one workgroup per (sequence, KV head): 256 tokens at head dimension 128,
+// 384 at 64 (tiles of half the bytes), each plus the two pages of slack a selection table carries
+constexpr int kFinishTokens128 = 288, kFinishTokens64 = 416;
 
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -84,9 +86,11 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   // writes the output rows itself, so no merge kernel is launched.  Measured at 4K context, five draft calls per
   // iteration: 256 selected tokens (eight tiles, two per wave) 54.7 us against 59.3 us with three chunks and a merge;
   // 384 tokens 61.8 against 59.4; 512 tokens 67.2 against 59.8 -- a workgroup takes about 0.35 us per further tile,
-  // with four waves or with eight, so the merge launch is the cheaper price from nine or ten tiles on.  The bound is
-  // 256 tokens plus the two pages of slack a selection table carries.
-  const bool finish = may_finish && d->kv_chunk_tokens == 0 && max_len <= kFinishTokens &&
+  // with four waves or with eight, so the merge launch is the cheaper price from nine or ten tiles on.  At head
+  // dimension 64 (32K context, 64 query heads): 256 tokens 66.5 against 73.0 us, 384 tokens 71.4 against 73.0,
+  // 512 tokens 75.1 against 73.3.
+  const bool finish = may_finish && d->kv_chunk_tokens == 0 &&
+                      max_len <= (d->head_dim == 64 ? kFinishTokens64 : kFinishTokens128) &&
                       static_cast<int64_t>(d->batch) * d->num_kv_heads * pl->NB <= kNumCU;
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
