@@ -151,24 +151,26 @@ def test_table5_shape_sampled_against_oracle(P):
 
 
 FINISH_CASES = [
-    # name, B, Hq, Hkv, D, P, lens
-    ("hd128_pages16", 3, 32, 8, 128, 16, [4000, 0, 700]),
-    ("hd64_pages16", 2, 32, 4, 64, 16, [2500, 37]),
-    ("three_row_blocks", 2, 80, 1, 128, 16, [1200, 5]),
-    ("one_token_pages", 3, 16, 2, 128, 1, [900, 0, 288]),
-    ("two_token_pages_hd64", 2, 8, 8, 64, 2, [300, 1]),
+    # name, B, Hq, Hkv, D, P, lens, budget tokens
+    ("hd128_pages16", 3, 32, 8, 128, 16, [4000, 0, 700], 256),
+    ("hd64_pages16", 2, 32, 4, 64, 16, [2500, 37], 256),
+    ("hd64_384_tokens", 2, 64, 8, 64, 16, [3000, 390], 384),
+    ("three_row_blocks", 2, 80, 1, 128, 16, [1200, 5], 256),
+    ("one_token_pages", 3, 16, 2, 128, 1, [900, 0, 288], 256),
+    ("two_token_pages_hd64", 2, 8, 8, 64, 2, [300, 1], 256),
 ]
 
 
-@pytest.mark.parametrize("name,B,Hq,Hkv,D,P,lens", FINISH_CASES, ids=[c[0] for c in FINISH_CASES])
-def test_short_selections_need_no_merge_kernel(name, B, Hq, Hkv, D, P, lens):
-    """At most 288 selected tokens and no chunk length passed: one workgroup per (sequence, KV head, row block)
-    streams the whole selection and writes the output rows itself.  Checked against the oracle, against the same
-    call cut into 64-token chunks with a merge kernel, and on empty sequences (rows of zeros)."""
+@pytest.mark.parametrize("name,B,Hq,Hkv,D,P,lens,budget", FINISH_CASES, ids=[c[0] for c in FINISH_CASES])
+def test_short_selections_need_no_merge_kernel(name, B, Hq, Hkv, D, P, lens, budget):
+    """At most 256 selected tokens (384 at head dimension 64) plus two pages of slack, no chunk length passed: one
+    workgroup per (sequence, KV head, row block) streams the whole selection and writes the output rows itself.
+    Checked against the oracle, against the same call cut into 64-token chunks with a merge kernel, and on empty
+    sequences (rows of zeros)."""
     rng = np.random.default_rng(len(name))
     L = synth.make_random_case(seed=940 + len(name), batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=2,
                                seq_lens=lens, head_dim=D, logit_std=1.5, value_std=1.0, outliers=2, outlier_logit=20.0)
-    budget_pages = 256 // P
+    budget_pages = budget // P
     rows, sl = [], []
     for b in range(B):
         n = int(L.seq_lens[b])
@@ -180,7 +182,7 @@ def test_short_selections_need_no_merge_kernel(name, B, Hq, Hkv, D, P, lens):
                                   np.zeros(0, np.int64), [npg - 1]]).astype(np.int64)
         rows.append(L.block_table[b, (logical * P) // PAGE].astype(np.int64) * (PAGE // P) + ((logical * P) % PAGE) // P)
         sl.append(P * (k - 1) + (n - P * (npg - 1)))
-    msb = budget_pages + 2 * (PAGE // P)                        # two 16-token pages of slack: 288 tokens at most
+    msb = budget_pages + 2 * (PAGE // P)                        # two 16-token pages of slack
     sel = np.full((B, msb), -1, dtype=np.int32)
     for b, r in enumerate(rows):
         sel[b, :len(r)] = r
