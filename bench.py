@@ -121,17 +121,15 @@ def sweep_collect(args, torch, vb, harness, synth) -> int:
             path = harness.VegasPath.for_layer(L, collect_rows=mode, verify_chunk=args.verify_chunk)
 
             def leg(stages: int) -> float:
-                path.desc_verify.launch_stages = stages
                 e0, e1 = vb.HipEvent(), vb.HipEvent()
                 for i in range(5):
-                    path.verify(copies[i % len(copies)])
+                    path.verify(copies[i % len(copies)], stages=stages)
                 torch.cuda.synchronize()
                 e0.record(stream)
                 for i in range(K):
-                    path.verify(copies[i % len(copies)])
+                    path.verify(copies[i % len(copies)], stages=stages)
                 e1.record(stream)
                 e1.synchronize()
-                path.desc_verify.launch_stages = 0
                 return e0.elapsed_ms(e1) / K * 1e3
             call_us, stream_us = leg(0), leg(vb.STAGE_STREAM)
             entry[name] = {"call_us": call_us, "stream_kernel_us": stream_us,
@@ -196,22 +194,20 @@ def sweep_page_size(args, torch, vb) -> int:
         addr = dict(q=q.data_ptr(), k=k_pool.data_ptr(), v=v_pool.data_ptr(), ssl=ssl.data_ptr(), out=out.data_ptr(),
                     ws=ws.data_ptr(), t=[t.data_ptr() for t in tables])
 
-        def call(i: int) -> None:
+        def call(i: int, stages: int) -> None:
             vb.vegas_draft_attention(desc, addr["q"], addr["k"], addr["v"], addr["t"][i % 3], addr["ssl"], addr["out"],
-                                     addr["ws"], stream=stream, workspace_bytes=ws.numel())
+                                     addr["ws"], stream=stream, workspace_bytes=ws.numel(), stages=stages)
 
         def leg(stages: int) -> float:
-            desc.launch_stages = stages
             e0, e1 = vb.HipEvent(), vb.HipEvent()
             for i in range(5):
-                call(i)
+                call(i, stages)
             torch.cuda.synchronize()
             e0.record(stream)
             for i in range(K):
-                call(i)
+                call(i, stages)
             e1.record(stream)
             e1.synchronize()
-            desc.launch_stages = 0
             return e0.elapsed_ms(e1) / K * 1e3
         call_us, stream_us = leg(0), leg(vb.STAGE_STREAM)
         rows.append({"page_size": P, "call_us": call_us, "stream_kernel_us": stream_us,
@@ -241,7 +237,8 @@ def main() -> int:
     ap.add_argument("--verify-chunk", type=int, default=0)
     ap.add_argument("--draft-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--no-kernel-legs", action="store_true",
+                    help="skip the legs that time the KV-streaming kernels alone (counter runs want the plain iteration)")
     ap.add_argument("--extras", action="store_true")
     ap.add_argument("--variant", choices=["page", "token"], default="page",
                     help="page: 16-token pages scored by softmax weights (the default path); token: the paper's own "
@@ -305,10 +302,9 @@ def main() -> int:
     sel_tokens = int(path.sel_seq_lens.sum().item())
     draft_bytes = sel_tokens * bytes_per_token
 
-    def kernel_leg(call, desc, reps: int) -> float:
+    def kernel_leg(call, reps: int) -> float:
         """Average duration of one KV-streaming kernel: `reps` back-to-back launches of that kernel
-        alone (launch_stages = STREAM), bracketed by two HIP events on the launch stream."""
-        desc.launch_stages = vb.STAGE_STREAM
+        alone (the debug entry point with stages = STREAM), bracketed by two HIP events on the launch stream."""
         e0, e1 = vb.HipEvent(), vb.HipEvent()
         for i in range(5):
             call(i)
@@ -318,7 +314,6 @@ def main() -> int:
             call(i)
         e1.record(stream)
         e1.synchronize()
-        desc.launch_stages = 0
         return e0.elapsed_ms(e1) / reps * 1e3
 
     traffic = VERIFY_TRAFFIC_BYTES.get(workload) if args.verify_chunk == 0 and not token else None
@@ -328,12 +323,12 @@ def main() -> int:
                 "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": traffic,
                 "bytes_per_launch": verify_bytes}
     roofline_draft = None
-    if not args.no_kernel_events:
-        v_us = kernel_leg(lambda i: path.verify(copies[i % len(copies)]), path.desc_verify, K)
+    if not args.no_kernel_legs:
+        v_us = kernel_leg(lambda i: path.verify(copies[i % len(copies)], stages=vb.STAGE_STREAM), K)
         roofline["kernel_us"] = v_us
         roofline["achieved"] = verify_bytes / (v_us * 1e-6) / 1e9
         roofline["frac"] = roofline["achieved"] / HBM_PEAK_GBS
-        d_us = kernel_leg(lambda i: path.draft(copies[i % len(copies)], i % G), path.desc_draft, K)
+        d_us = kernel_leg(lambda i: path.draft(copies[i % len(copies)], i % G, stages=vb.STAGE_STREAM), K)
         roofline_draft = {"bound": "hbm", "kernel": "attn_split_kernel (KV-streaming kernel of vegas_draft_attention)",
                           "kernel_us": d_us, "achieved": draft_bytes / (d_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                           "unit": "GB/s", "frac": draft_bytes / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS,

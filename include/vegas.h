@@ -27,6 +27,11 @@
  *   - `workspace` is caller-owned device scratch of at least vegas_workspace_bytes(desc) bytes,
  *     256-byte aligned.  Its contents are meaningless between calls; calls that share a workspace
  *     must be ordered on one stream.
+ *   - vegas_init() is optional but recommended once per device before the first call: it does the
+ *     one-time, per-device set-up (compute-unit count, raised LDS limits of the large kernels) that
+ *     the calls otherwise do lazily on first use.  A caller that captures calls into a HIP graph
+ *     must either call vegas_init() first or run each call once outside capture: the lazy set-up
+ *     calls hipFuncSetAttribute, which does not belong inside a capture.
  */
 #ifndef VEGAS_H
 #define VEGAS_H
@@ -64,7 +69,7 @@ enum {
                                     [B, max_blocks * 16]; read by vegas_select_tokens */
 };
 
-/* Kernels of an attention call, for vegas_desc.launch_stages. */
+/* Kernels of an attention call, for the `stages` argument of the vegas_debug_*_stages calls. */
 enum {
   VEGAS_STAGE_STREAM = 1,  /* the KV-streaming kernel (reads the cache, writes chunk partials) */
   VEGAS_STAGE_MERGE = 2    /* merge of the chunk partials, and the page scores for verification; a draft call
@@ -90,8 +95,7 @@ typedef struct vegas_desc {
                               chooses: from batch, heads and max_seq_len on the host, or, for a verification call
                               on a batch of 2..64 sequences, per sequence on the GPU from seq_lens, so that all
                               workgroups stream about the same number of tokens however loose max_seq_len is */
-  int32_t launch_stages;   /* profiling aid: 0 = whole call; else VEGAS_STAGE_* bits to launch only
-                              those kernels of an attention call (outputs then incomplete) */
+  int32_t reserved;        /* must be 0 */
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
   int32_t score_metric;    /* VEGAS_METRIC_*: what vegas_verify_attention writes to block_scores */
   int32_t window;          /* vegas_verify_attention: > 0 = local ("sliding window") masking of a banded layer
@@ -105,12 +109,16 @@ typedef struct vegas_desc {
   int64_t kv_page_stride;  /* elements between pages */
   int64_t kv_token_stride; /* elements between slots of a page */
   int64_t kv_head_stride;  /* elements between KV heads of a slot */
-  void*   ev_kernel_begin; /* optional hipEvent_t recorded on the stream right before ... */
-  void*   ev_kernel_end;   /* ... and right after the call's KV-streaming kernel (timing hook) */
 } vegas_desc;
 
-/* Bytes of device scratch that any of the three calls may need for this descriptor.
- * Pure host function; returns 0 if the descriptor is invalid. */
+/* One-time set-up for the CURRENT device (hipSetDevice first): reads the device's compute-unit count
+ * and raises the dynamic-LDS limit of every kernel that needs more than the default, so that no later
+ * call touches a function attribute (see the conventions above for HIP graph capture).  Idempotent and
+ * thread-safe; allocates nothing.  Returns VEGAS_OK, or VEGAS_ERR_LAUNCH if the HIP runtime refuses. */
+int vegas_init(void);
+
+/* Bytes of device scratch that any of the calls may need for this descriptor (the upper bound
+ * max_seq_len travels in the descriptor).  Pure host function; returns 0 if the descriptor is invalid. */
 size_t vegas_workspace_bytes(const vegas_desc* desc);
 
 /*
@@ -142,10 +150,13 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
  *   budgets, App. C) else budget_tokens.
  *   sel_table    int32 [B, max_sel_blocks]  PHYSICAL page ids in ascending logical order, then -1
  *   sel_seq_lens int32 [B]                  tokens covered: 16*(k_b-1) + tokens in the last page
- * Integer work: for identical fp32 scores the result is defined bit for bit.
- * Returns VEGAS_ERR_SHAPE if max_sel_blocks < min(ceil(max budget/16), ceil(max_seq_len/16)) + 2
- * cannot be guaranteed to hold k_b (the host checks budget_tokens only when budgets == NULL; with
- * per-sequence budgets, k_b is clamped to max_sel_blocks on the device).
+ * Integer work: for identical fp32 scores the result is defined bit for bit.  A NaN score ranks
+ * below every number (and NaNs among themselves by logical index); -0 equals +0.
+ * Returns VEGAS_ERR_SHAPE if a row of sel_table cannot hold the largest k_b the call may produce:
+ * max_sel_blocks < max(min(ceil(budget/16), ceil(max_seq_len/16)), pages that G positions can touch),
+ * with budget = budget_tokens, or ceil(budget_ratio * max_seq_len) when the ratio is set.  The host
+ * checks this only when budgets == NULL; with per-sequence budgets k_b is clamped to max_sel_blocks on
+ * the device.
  */
 int vegas_select_blocks(const vegas_desc* desc, const float* block_scores,
                         const int32_t* block_table, const int32_t* seq_lens,
@@ -170,7 +181,8 @@ int vegas_select_blocks(const vegas_desc* desc, const float* block_scores,
  *                                           vegas_draft_attention with page_size = 1
  *   sel_seq_lens int32 [B]                  k_b
  * desc->page_size is 16 here (it describes block_table); desc->max_sel_blocks counts tokens.
- * Integer work: for identical fp32 scores the result is defined bit for bit.  Five short kernels
+ * Integer work: for identical fp32 scores the result is defined bit for bit (NaN ranks below every
+ * number, -0 equals +0, as for vegas_select_blocks).  Five short kernels
  * (four digit-histogram passes that meet in global memory, one ordered compaction); workspace from vegas_workspace_bytes.
  * Returns VEGAS_ERR_SHAPE if max_sel_blocks < max(min(budget_tokens, max_seq_len), min(G, max_seq_len))
  * (checked when budgets == NULL; per-sequence budgets are clamped on the device).
@@ -219,6 +231,20 @@ int vegas_extend_selection(const vegas_desc* desc, const int32_t* block_table, c
 int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                           const int32_t* sel_table, const int32_t* sel_seq_lens,
                           void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Profiling aids, not part of the method: the same calls restricted to some of their kernels.
+ * `stages` is a mask of VEGAS_STAGE_* bits (0 = the whole call); with anything but the whole call the
+ * outputs are incomplete.  The benchmark times the KV-streaming kernel alone through these.
+ */
+int vegas_debug_verify_attention_stages(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                        const int32_t* block_table, const int32_t* seq_lens,
+                                        void* out, float* block_scores,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream, int32_t stages);
+int vegas_debug_draft_attention_stages(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                       const int32_t* sel_table, const int32_t* sel_seq_lens,
+                                       void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                       int32_t stages);
 
 /* Static, human-readable text for a vegas_status. */
 const char* vegas_strerror(int status);

@@ -38,7 +38,7 @@ Readings taken where the paper is silent (each is also listed in the design note
   * a row with no visible key (only possible when seq_len < gamma+1) outputs 0 and
     contributes no weight.
 
-Pins (tests/test_oracle_*.py): token logit scores against scalar loops, the closed form
+Pins (tests/test_oracle_pins.py): token logit scores against scalar loops, the closed form
 k_i . mean(q) and the single-head ranking identity of App. B; token selection against exhaustive
 subset search for Eq. 3, numpy partition and hand-worked cases; draft attention over 1/2/4/8-token pages against library attention
 over the listed tokens, closed forms for uniform weights, one-hot dominance, the
@@ -165,7 +165,8 @@ def select_logical(scores_row: np.ndarray, n: int, num_queries: int, budget_toke
     """Selected logical page ids (ascending) of one sequence.
 
     k = min(ceil(budget/16), nblk), raised to the number of forced pages; forced pages first,
-    then the best remaining pages by (score descending, logical index ascending)."""
+    then the best remaining pages by (score descending, logical index ascending).  A NaN score is
+    no criticality at all: it ranks below every number (NumPy's sort order puts NaN last)."""
     if n <= 0:
         return np.zeros(0, dtype=np.int64)
     nblk = (n + PAGE - 1) // PAGE

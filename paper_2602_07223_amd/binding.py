@@ -31,8 +31,9 @@ METRIC_TOKEN_LOGITS = 1
 STAGE_STREAM = 1
 STAGE_MERGE = 2
 
-EXPORTS = ("vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks", "vegas_select_tokens",
-           "vegas_extend_selection", "vegas_draft_attention", "vegas_strerror")
+EXPORTS = ("vegas_init", "vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
+           "vegas_select_tokens", "vegas_extend_selection", "vegas_draft_attention",
+           "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_strerror")
 
 
 class VegasDesc(ctypes.Structure):
@@ -49,7 +50,7 @@ class VegasDesc(ctypes.Structure):
         ("max_seq_len", ctypes.c_int32),
         ("collect_rows", ctypes.c_int32),
         ("kv_chunk_tokens", ctypes.c_int32),
-        ("launch_stages", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
         ("score_metric", ctypes.c_int32),
         ("window", ctypes.c_int32),
@@ -58,8 +59,6 @@ class VegasDesc(ctypes.Structure):
         ("kv_page_stride", ctypes.c_int64),
         ("kv_token_stride", ctypes.c_int64),
         ("kv_head_stride", ctypes.c_int64),
-        ("ev_kernel_begin", ctypes.c_void_p),
-        ("ev_kernel_end", ctypes.c_void_p),
     ]
 
 
@@ -84,6 +83,8 @@ def load_library(path: Optional[str] = None):
     lib = ctypes.CDLL(path)
     P = ctypes.c_void_p
     D = ctypes.POINTER(VegasDesc)
+    lib.vegas_init.restype = ctypes.c_int
+    lib.vegas_init.argtypes = []
     lib.vegas_workspace_bytes.restype = ctypes.c_size_t
     lib.vegas_workspace_bytes.argtypes = [D]
     lib.vegas_verify_attention.restype = ctypes.c_int
@@ -96,6 +97,10 @@ def load_library(path: Optional[str] = None):
     lib.vegas_extend_selection.argtypes = [D, P, P, ctypes.c_int32, P, P, P]
     lib.vegas_draft_attention.restype = ctypes.c_int
     lib.vegas_draft_attention.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_debug_verify_attention_stages.restype = ctypes.c_int
+    lib.vegas_debug_verify_attention_stages.argtypes = [D, P, P, P, P, P, P, P, P, ctypes.c_size_t, P, ctypes.c_int32]
+    lib.vegas_debug_draft_attention_stages.restype = ctypes.c_int
+    lib.vegas_debug_draft_attention_stages.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P, ctypes.c_int32]
     lib.vegas_strerror.restype = ctypes.c_char_p
     lib.vegas_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -162,7 +167,7 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
     d.head_dim, d.page_size, d.num_queries = head_dim, page_size, num_queries
     d.max_blocks, d.max_sel_blocks, d.max_seq_len = max_blocks, max_sel_blocks, max_seq_len
     d.collect_rows, d.kv_chunk_tokens, d.softmax_scale = collect_rows, kv_chunk_tokens, softmax_scale
-    d.launch_stages = 0
+    d.reserved = 0
     d.score_metric = score_metric
     d.budget_ratio = budget_ratio
     d.window = window
@@ -170,8 +175,6 @@ def make_desc(*, batch: int, num_q_heads: int, num_kv_heads: int, num_queries: i
     d.kv_head_stride = kv_head_stride or head_dim
     d.kv_token_stride = kv_token_stride or num_kv_heads * head_dim
     d.kv_page_stride = kv_page_stride or page_size * num_kv_heads * head_dim
-    d.ev_kernel_begin = None
-    d.ev_kernel_end = None
     return d
 
 
@@ -179,8 +182,16 @@ def vegas_workspace_bytes(desc: VegasDesc) -> int:
     return int(load_library().vegas_workspace_bytes(ctypes.byref(desc)))
 
 
+def vegas_init() -> None:
+    """One-time set-up for the current device (see include/vegas.h); optional, the calls do it lazily otherwise."""
+    rc = load_library().vegas_init()
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_init")
+
+
 def vegas_verify_attention(desc: VegasDesc, q, k_cache, v_cache, block_table, seq_lens, out, block_scores,
-                           workspace, stream=None, workspace_bytes: Optional[int] = None) -> None:
+                           workspace, stream=None, workspace_bytes: Optional[int] = None, stages: int = 0) -> None:
+    """stages != 0: vegas_debug_verify_attention_stages (a profiling aid: only those kernels of the call)."""
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
     if not (isinstance(q, int) and isinstance(k_cache, int)):      # raw addresses: the caller has checked (harness)
         d = desc
@@ -191,9 +202,12 @@ def vegas_verify_attention(desc: VegasDesc, q, k_cache, v_cache, block_table, se
                        block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
                        block_scores=(block_scores if d.collect_rows != COLLECT_NONE else None,
                                      d.batch * d.max_blocks * per_page * 4))
-    rc = load_library().vegas_verify_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
-                                               _ptr(block_table), _ptr(seq_lens), _ptr(out), _ptr(block_scores),
-                                               _ptr(workspace), wb, _stream(stream))
+    args = (ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(seq_lens), _ptr(out),
+            _ptr(block_scores), _ptr(workspace), wb, _stream(stream))
+    if stages:
+        rc = load_library().vegas_debug_verify_attention_stages(*args, int(stages))
+    else:
+        rc = load_library().vegas_verify_attention(*args)
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_verify_attention")
 
@@ -244,7 +258,8 @@ def vegas_extend_selection(desc: VegasDesc, block_table, seq_lens, num_new: int,
 
 
 def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace,
-                          stream=None, workspace_bytes: Optional[int] = None) -> None:
+                          stream=None, workspace_bytes: Optional[int] = None, stages: int = 0) -> None:
+    """stages != 0: vegas_debug_draft_attention_stages (a profiling aid: only those kernels of the call)."""
     wb = workspace_bytes if workspace_bytes is not None else (_nbytes(workspace) if workspace is not None else 0)
     if not (isinstance(q, int) and isinstance(k_cache, int)):
         d = desc
@@ -252,15 +267,18 @@ def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_s
         _check_extents("vegas_draft_attention", q=(q, rows), out=(out, rows),
                        k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
                        sel_table=(sel_table, d.batch * d.max_sel_blocks * 4), sel_seq_lens=(sel_seq_lens, d.batch * 4))
-    rc = load_library().vegas_draft_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
-                                              _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out), _ptr(workspace),
-                                              wb, _stream(stream))
+    args = (ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out),
+            _ptr(workspace), wb, _stream(stream))
+    if stages:
+        rc = load_library().vegas_debug_draft_attention_stages(*args, int(stages))
+    else:
+        rc = load_library().vegas_draft_attention(*args)
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_draft_attention")
 
 
 # ---------------------------------------------------------------------------------------------
-# HIP events on a raw stream (timing plumbing for the benchmark's per-kernel hook)
+# HIP events on a raw stream (timing plumbing for the benchmark)
 # ---------------------------------------------------------------------------------------------
 
 _hip = None
@@ -286,7 +304,7 @@ def _hip_runtime():
 
 
 class HipEvent:
-    """A hipEvent_t usable as ``desc.ev_kernel_begin`` / ``desc.ev_kernel_end``."""
+    """A hipEvent_t recorded on a raw stream handle (the stream the library's kernels are launched on)."""
 
     def __init__(self):
         self.handle = ctypes.c_void_p()

@@ -29,10 +29,12 @@ __device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
   return static_cast<uint32_t>(v);
 }
 
-// Order-preserving key of a score (larger float <=> larger unsigned); -0 is folded onto +0.
+// Order-preserving key of a score (larger float <=> larger unsigned); -0 is folded onto +0 and every NaN onto
+// key 0, below -infinity: a NaN score ranks last, NaNs among themselves by index like any other tie.
 __device__ __forceinline__ uint32_t score_key(float s) {
   const uint32_t u = __float_as_uint(s + 0.0f);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  const uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return (s != s) ? 0u : key;
 }
 
 __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const SelectParams p) {

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <map>
 #include <mutex>
 #include <set>
 #include <utility>
@@ -20,8 +21,31 @@ namespace {
 
 using namespace vegas;
 
-constexpr int kNumCU = 256;           // MI355X compute units
+constexpr int kDefaultCU = 256;       // MI355X compute units: assumed where no device is visible
 constexpr size_t kAlign = 256;
+
+// Compute units of the current device, asked once per device.  The launch plans aim at one or two workgroups per
+// compute unit, and the workspace is sized from the same plans, so sizing and launching must see the same number:
+// without a visible device (the pure-host sizing call on a machine that has none) it is the MI355X's 256.
+int device_cu_count() {
+  static std::mutex mu;
+  static std::map<int, int> known;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return kDefaultCU;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  const auto it = known.find(dev);
+  if (it != known.end()) return it->second;
+  int n = 0;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();
+    n = kDefaultCU;
+  }
+  known[dev] = n;
+  return n;
+}
 // longest selection a draft call streams with one workgroup per (sequence, KV head): 256 tokens at head dimension 128,
 // 384 at 64 (tiles of half the bytes), each plus the two pages of slack a selection table carries
 constexpr int kFinishTokens128 = 288, kFinishTokens64 = 416;
@@ -57,7 +81,7 @@ int check_common(const vegas_desc* d) {
   if ((d->kv_head_stride % 8) || (d->kv_token_stride % 8) || (d->kv_page_stride % 8)) return VEGAS_ERR_ALIGN;
   if (d->kv_chunk_tokens < 0 || (d->kv_chunk_tokens % kTile) != 0) return VEGAS_ERR_SHAPE;
   if (!(d->softmax_scale > 0.f)) return VEGAS_ERR_SHAPE;
-  if (d->launch_stages < 0 || d->launch_stages > (VEGAS_STAGE_STREAM | VEGAS_STAGE_MERGE)) return VEGAS_ERR_SHAPE;
+  if (d->reserved != 0) return VEGAS_ERR_SHAPE;
   return VEGAS_OK;
 }
 
@@ -74,6 +98,7 @@ int check_paged16(const vegas_desc* d) {
 int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect, int wg_per_cu, SplitPlan* pl,
                bool may_pair = false, bool may_finish = false) {
   pl->R = rows_per_head;
+  const int num_cu = device_cu_count();
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
   if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
   pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks
@@ -91,7 +116,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   // 512 tokens 75.1 against 73.3.
   const bool finish = may_finish && d->kv_chunk_tokens == 0 &&
                       max_len <= (d->head_dim == 64 ? kFinishTokens64 : kFinishTokens128) &&
-                      static_cast<int64_t>(d->batch) * d->num_kv_heads * pl->NB <= kNumCU;
+                      static_cast<int64_t>(d->batch) * d->num_kv_heads * pl->NB <= num_cu;
   const int unit = kTile * pl->NW;
   int chunk = d->kv_chunk_tokens;
   if (finish) chunk = (max_len + unit - 1) / unit * unit;
@@ -100,7 +125,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     // beat 512); draft calls are latency-bound and like two small workgroups per CU.  With many
     // (sequence, head) columns, shorter chunks balance ragged lengths better.
     const int64_t columns = heads * (pl->pair ? 1 : pl->NB);
-    int64_t splits = static_cast<int64_t>(kNumCU) * wg_per_cu / columns;
+    int64_t splits = static_cast<int64_t>(num_cu) * wg_per_cu / columns;
     if (splits < 1) splits = 1;
     int64_t c = (max_len + splits - 1) / splits;
     {
@@ -108,7 +133,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
       // slack) would then double every wave's tiles -- a quarter more workgroups than planned is the better price.
       const int64_t up = (c + unit - 1) / unit * unit, down = c / unit * unit;
       c = up;
-      if (down >= unit && ((max_len + down - 1) / down) * columns * 4 <= static_cast<int64_t>(kNumCU) * wg_per_cu * 5) c = down;
+      if (down >= unit && ((max_len + down - 1) / down) * columns * 4 <= static_cast<int64_t>(num_cu) * wg_per_cu * 5) c = down;
     }
     if (pl->pair) {
       // the pair kernel likes two workgroups per CU once their chunks are long enough (one sequence of 128K tokens,
@@ -121,9 +146,9 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     // chunk that gives every CU exactly one workgroup is taken as it is while its LDS fits (batch 4 x 64K tokens:
     // 256 chunks of 8192 tokens reach 78 % of the HBM peak, 512 chunks of 4096 tokens 75 %); otherwise chunks are
     // capped so that two workgroups fit a CU.  (The pair kernel parks nothing per chunk: any chunk length.)
-    const int64_t cap = (columns >= kNumCU) ? 2048 : 4096;
+    const int64_t cap = (columns >= num_cu) ? 2048 : 4096;
     const int prows = rows_per_head < 32 ? rows_per_head : 32;
-    const bool fits_alone = columns * splits >= kNumCU / 2 &&
+    const bool fits_alone = columns * splits >= num_cu / 2 &&
                             split_lds_bytes(pl->NW, prows, collect, static_cast<int>(c), d->head_dim) <= 150 * 1024;
     if (!pl->pair && c > cap && !(wg_per_cu == 1 && fits_alone)) c = cap;
     chunk = static_cast<int>(c);
@@ -135,7 +160,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
   // against 68 % with the plan; and it sizes chunks for lengths that may never occur.)
   const int64_t per_head = static_cast<int64_t>(d->num_kv_heads) * (pl->pair ? 1 : pl->NB);   // workgroups per slot
   pl->balanced = may_pair && d->kv_chunk_tokens == 0 && d->batch >= 2 && d->batch <= 64 && max_len < (1 << 24) &&
-                 per_head <= kNumCU;
+                 per_head <= num_cu;
   pl->chunk = chunk;
   pl->nsplit = (max_len + chunk - 1) / chunk;
   size_t slots = static_cast<size_t>(heads) * pl->nsplit;       // chunk partials the workspace holds
@@ -144,7 +169,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
     if (pl->pair) {
       // one launch wave (two workgroups per CU) without collection; with it, shorter chunks in two waves were
       // measured faster (16 sequences of 8K..64K tokens, 40 rows: 505 us against 515 us).  Nothing is parked.
-      pl->J = pl->J2 = static_cast<int>((collect ? 4 : 2) * kNumCU / per_head);
+      pl->J = pl->J2 = static_cast<int>((collect ? 4 : 2) * num_cu / per_head);
       pl->cap_units = 1 << 20;
       pl->chunk = unit;                                         // (unused: every sequence has its own)
       most_chunks = pl->J;
@@ -152,7 +177,7 @@ int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect,
       // one workgroup per CU with chunks as long as its LDS can park (16 x 36864 tokens, 20 rows: 256 chunks of
       // 18432 tokens reach 80 % of the peak, 512 of 9216 75 %, 4096-token chunks 69 %); two waves when the
       // lengths are too ragged for one
-      pl->J = static_cast<int>(kNumCU / per_head);
+      pl->J = static_cast<int>(num_cu / per_head);
       // (slots no plan uses still cost a workgroup that works that out, at one workgroup per CU in a wave of their
       // own behind the others: a small batch, whose kernel is short, gets the one-wave plan only)
       pl->J2 = d->batch >= 8 ? 2 * pl->J : pl->J;
@@ -216,6 +241,7 @@ int plan_draft(const vegas_desc* d, SplitPlan* pl) {
 // A kernel whose static + dynamic LDS passes the default 64 KB limit needs its limit raised first: once
 // per (device, kernel function).  The table is keyed by the function's address because every
 // instantiation of the streaming kernel has the same C++ type.
+// (vegas_init raises every kernel's limit up front; this lazy path serves callers that never call it.)
 int ensure_dynamic_lds(const void* kern, size_t lds) {
   if (lds <= 32 * 1024) return VEGAS_OK;
   static std::mutex mu;
@@ -379,9 +405,54 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
+// Every kernel that is launched with dynamic LDS, for vegas_init: f(kernel address).
+template <typename F>
+int for_each_lds_kernel(F f) {
+  int rc = VEGAS_OK;
+  auto one = [&](auto kern) { if (rc == VEGAS_OK) rc = f(reinterpret_cast<const void*>(kern)); };
+  auto per_dim = [&](auto dtag) {
+    constexpr int D = decltype(dtag)::value;
+    one(attn_split_kernel<4, 2, false, 0, false, 0, false, D>);      // draft calls, page sizes 1, 2, 4, 8, 16
+    one(attn_split_kernel<4, 2, false, 0, false, 1, false, D>);
+    one(attn_split_kernel<4, 2, false, 0, false, 2, false, D>);
+    one(attn_split_kernel<4, 2, false, 0, false, 3, false, D>);
+    one(attn_split_kernel<4, 2, false, 0, false, 4, false, D>);
+    one(attn_split_kernel<4, 2, true, 0, true, 4, true, D>);         // verification of a banded layer
+    one(attn_split_kernel<4, 2, true, 0, false, 4, true, D>);
+    one(attn_split_kernel<4, 2, true, 0, true, 4, false, D>);        // verification: no collection / page weights / logits,
+    one(attn_split_kernel<4, 2, true, 0, false, 4, false, D>);       // one reader per line or sibling row blocks
+    one(attn_split_kernel<4, 2, true, 1, true, 4, false, D>);
+    one(attn_split_kernel<4, 2, true, 1, false, 4, false, D>);
+    one(attn_split_kernel<4, 2, true, 2, true, 4, false, D>);
+    one(attn_split_kernel<4, 2, true, 2, false, 4, false, D>);
+    one(attn_pair_kernel<0, D>);
+    one(attn_pair_kernel<1, D>);
+    one(attn_pair_kernel<2, D>);
+  };
+  per_dim(std::integral_constant<int, 128>{});
+  per_dim(std::integral_constant<int, 64>{});
+  one(verify_finalize_kernel<16, 0>); one(verify_finalize_kernel<32, 0>);
+  one(verify_finalize_kernel<64, 0>); one(verify_finalize_kernel<0, 0>);
+  one(verify_finalize_kernel<16, 1>); one(verify_finalize_kernel<32, 1>);
+  one(verify_finalize_kernel<64, 1>); one(verify_finalize_kernel<0, 1>);
+  one(select_blocks_kernel);
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
+
+int vegas_init(void) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return VEGAS_ERR_LAUNCH;
+  }
+  (void)device_cu_count();
+  return for_each_lds_kernel([](const void* kern) { return ensure_dynamic_lds(kern, 160 * 1024); });
+}
+
 
 size_t vegas_workspace_bytes(const vegas_desc* desc) {
   if (check_common(desc) != VEGAS_OK) return 0;
@@ -397,9 +468,10 @@ size_t vegas_workspace_bytes(const vegas_desc* desc) {
   return need;
 }
 
-int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
-                           const int32_t* block_table, const int32_t* seq_lens, void* out, float* block_scores,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int verify_impl(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                       const int32_t* block_table, const int32_t* seq_lens, void* out, float* block_scores,
+                       void* workspace, size_t workspace_bytes, void* hip_stream, int32_t stages) {
+  if (stages < 0 || stages > (VEGAS_STAGE_STREAM | VEGAS_STAGE_MERGE)) return VEGAS_ERR_SHAPE;
   int rc = check_common(desc);
   if (rc == VEGAS_OK) rc = check_paged16(desc);
   if (rc != VEGAS_OK) return rc;
@@ -423,15 +495,13 @@ int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_
   if (desc->window < 0) return VEGAS_ERR_SHAPE;
   if (desc->window > 0 && collect) return VEGAS_ERR_UNSUPPORTED;   // banded layers are not sparsified: nothing to score
   sp.window = desc->window;
-  const bool do_stream = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM);
-  const bool do_merge = desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_MERGE);
+  const bool do_stream = stages == 0 || (stages & VEGAS_STAGE_STREAM);
+  const bool do_merge = stages == 0 || (stages & VEGAS_STAGE_MERGE);
   if (do_stream) {
-    if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
     const int hd = desc->head_dim;
     rc = !collect ? launch_split<true, 0>(pl, sp, desc->batch, st, hd)
                   : (logits ? launch_split<true, 2>(pl, sp, desc->batch, st, hd)
                             : launch_split<true, 1>(pl, sp, desc->batch, st, hd));
-    if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }
   if (!do_merge) return VEGAS_OK;
@@ -600,9 +670,10 @@ int vegas_extend_selection(const vegas_desc* desc, const int32_t* block_table, c
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
-int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
-                          const int32_t* sel_table, const int32_t* sel_seq_lens, void* out, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+static int draft_impl(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                      const int32_t* sel_table, const int32_t* sel_seq_lens, void* out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream, int32_t stages) {
+  if (stages < 0 || stages > (VEGAS_STAGE_STREAM | VEGAS_STAGE_MERGE)) return VEGAS_ERR_SHAPE;
   int rc = check_common(desc);
   if (rc != VEGAS_OK) return rc;
   if (!q || !k_cache || !v_cache || !sel_table || !sel_seq_lens || !out) return VEGAS_ERR_NULL;
@@ -623,14 +694,40 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
   // One chunk per (sequence, KV head): the streaming kernel finishes the rows itself and no merge kernel is launched.
   const bool direct = pl.nsplit == 1;
   if (direct) sp.out_direct = static_cast<uint16_t*>(out);
-  if (desc->launch_stages == 0 || (desc->launch_stages & VEGAS_STAGE_STREAM)) {
-    if (desc->ev_kernel_begin) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_begin), st);
+  if (stages == 0 || (stages & VEGAS_STAGE_STREAM)) {
     rc = launch_split<false, 0>(pl, sp, desc->batch, st, desc->head_dim, desc->page_size);
-    if (desc->ev_kernel_end) (void)hipEventRecord(static_cast<hipEvent_t>(desc->ev_kernel_end), st);
     if (rc != VEGAS_OK) return rc;
   }
-  if (direct || (desc->launch_stages != 0 && !(desc->launch_stages & VEGAS_STAGE_MERGE))) return VEGAS_OK;
+  if (direct || (stages != 0 && !(stages & VEGAS_STAGE_MERGE))) return VEGAS_OK;
   return launch_combine(desc, pl, sp, out, st);
+}
+
+int vegas_verify_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* block_table, const int32_t* seq_lens, void* out, float* block_scores,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return verify_impl(desc, q, k_cache, v_cache, block_table, seq_lens, out, block_scores, workspace, workspace_bytes,
+                     hip_stream, 0);
+}
+
+int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* sel_table, const int32_t* sel_seq_lens, void* out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  return draft_impl(desc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace, workspace_bytes, hip_stream, 0);
+}
+
+int vegas_debug_verify_attention_stages(const vegas_desc* desc, const void* q, const void* k_cache,
+                                        const void* v_cache, const int32_t* block_table, const int32_t* seq_lens,
+                                        void* out, float* block_scores, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream, int32_t stages) {
+  return verify_impl(desc, q, k_cache, v_cache, block_table, seq_lens, out, block_scores, workspace, workspace_bytes,
+                     hip_stream, stages);
+}
+
+int vegas_debug_draft_attention_stages(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                       const int32_t* sel_table, const int32_t* sel_seq_lens, void* out,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream, int32_t stages) {
+  return draft_impl(desc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace, workspace_bytes, hip_stream,
+                    stages);
 }
 
 const char* vegas_strerror(int status) {

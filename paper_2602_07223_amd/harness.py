@@ -137,11 +137,11 @@ class VegasPath:
             self._own_addrs = o
         return o
 
-    def verify(self, dl: DeviceLayer, stream=None) -> None:
+    def verify(self, dl: DeviceLayer, stream=None, stages: int = 0) -> None:
         a, o = self._addrs(dl), self._own()
         vb.vegas_verify_attention(self.desc_verify, a["qv"], a["k"], a["v"], a["bt"], a["sl"], o["ov"], o["bs"],
                                   o["ws"], stream=self.stream() if stream is None else stream,
-                                  workspace_bytes=o["wsn"])
+                                  workspace_bytes=o["wsn"], stages=stages)
 
     def select(self, dl: DeviceLayer, block_scores: Optional[torch.Tensor] = None, budgets=None, stream=None) -> None:
         a, o = self._addrs(dl), self._own()
@@ -154,11 +154,11 @@ class VegasPath:
                                a["bt"], a["sl"], self.budget_tokens, o["st"], o["ssl"], budgets=budgets,
                                stream=self.stream() if stream is None else stream)
 
-    def draft(self, dl: DeviceLayer, step: int, stream=None) -> None:
+    def draft(self, dl: DeviceLayer, step: int, stream=None, stages: int = 0) -> None:
         a, o = self._addrs(dl), self._own()
         vb.vegas_draft_attention(self.desc_draft, a["qd"][step], a["k"], a["v"], o["st"], o["ssl"], o["od"][step],
                                  o["ws"], stream=self.stream() if stream is None else stream,
-                                 workspace_bytes=o["wsn"])
+                                 workspace_bytes=o["wsn"], stages=stages)
 
     def iteration(self, dl: DeviceLayer) -> None:
         """One decoding iteration's attention work for one layer: verify, select, G draft steps."""

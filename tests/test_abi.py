@@ -15,7 +15,11 @@ def good_desc(**over):
     kw = dict(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=5, max_blocks=2048, max_sel_blocks=130,
               max_seq_len=32768, num_pages=2048, softmax_scale=128 ** -0.5)
     kw.update(over)
-    return vb.make_desc(**kw)
+    fields = {k: kw.pop(k) for k in ("reserved",) if k in kw}       # descriptor fields make_desc has no argument for
+    d = vb.make_desc(**kw)
+    for k, v in fields.items():
+        setattr(d, k, v)
+    return d
 
 
 def test_library_exports_every_declared_symbol():
@@ -34,7 +38,56 @@ def test_desc_layout_matches_header():
     body = header[header.index("typedef struct vegas_desc {"):header.index("} vegas_desc;")]
     fields = re.findall(r"^\s*(?:int32_t|int64_t|float|void\*)\s+(\w+);", body, flags=re.M)
     assert fields == [f[0] for f in vb.VegasDesc._fields_]
-    assert ctypes.sizeof(vb.VegasDesc) == 16 * 4 + 4 * 8 + 2 * 8   # 16 x 4-byte fields
+    assert ctypes.sizeof(vb.VegasDesc) == 16 * 4 + 4 * 8           # 16 x 4-byte fields, 4 x 8-byte fields
+
+
+def test_header_compiles_as_c_and_a_c_program_links_against_the_library(tmp_path):
+    """include/vegas.h is a C header: a C11 compiler accepts it on its own, and a plain C program that includes it
+    can call the pure-host entry points of the built library (struct layout and prototypes as the C side sees them)."""
+    import shutil
+    import subprocess
+    cc = shutil.which("cc") or shutil.which("gcc")
+    assert cc, "no C compiler"
+    inc = os.path.join(ROOT, "include")
+    r = subprocess.run([cc, "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c",
+                        os.path.join(inc, "vegas.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    src = tmp_path / "use_vegas.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "vegas.h"
+int main(void) {
+  vegas_desc d;
+  memset(&d, 0, sizeof d);
+  d.batch = 1; d.num_q_heads = 32; d.num_kv_heads = 8; d.head_dim = 128; d.page_size = 16; d.num_queries = 5;
+  d.max_blocks = 2048; d.max_sel_blocks = 130; d.max_seq_len = 32768; d.collect_rows = VEGAS_COLLECT_ALL_ROWS;
+  d.softmax_scale = 0.08838834764831845f; d.score_metric = VEGAS_METRIC_PAGE_WEIGHTS;
+  d.num_pages = 2048; d.kv_head_stride = 128; d.kv_token_stride = 1024; d.kv_page_stride = 16384;
+  printf("%zu %zu\n", sizeof d, vegas_workspace_bytes(&d));
+  d.head_dim = 96;
+  printf("%zu\n", vegas_workspace_bytes(&d));
+  printf("%s|%s\n", vegas_strerror(VEGAS_OK), vegas_strerror(VEGAS_ERR_WORKSPACE));
+  /* argument validation comes before any launch: a NULL query is refused without touching a device */
+  d.head_dim = 128;
+  printf("%d\n", vegas_verify_attention(&d, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL));
+  return 0;
+}
+''')
+    exe = tmp_path / "use_vegas"
+    libdir = os.path.dirname(vb.LIB_PATH)
+    r = subprocess.run([cc, "-std=c11", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lvegas",
+                        "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    lines = r.stdout.split("\n")
+    size, ws = lines[0].split()
+    assert int(size) == ctypes.sizeof(vb.VegasDesc)
+    assert int(ws) == vb.vegas_workspace_bytes(good_desc())
+    assert lines[1] == "0"
+    assert lines[2] == "ok|workspace missing or too small"
+    assert int(lines[3]) == vb.VEGAS_ERR_NULL
 
 
 def test_workspace_bytes_is_a_pure_host_function():
@@ -68,6 +121,7 @@ A = 4096  # a 16-byte aligned fake device address: never dereferenced because va
     (dict(kv_token_stride=1028), vb.VEGAS_ERR_ALIGN),
     (dict(softmax_scale=0.0), vb.VEGAS_ERR_SHAPE),
     (dict(batch=65536), vb.VEGAS_ERR_UNSUPPORTED),             # sequences are a grid dimension
+    (dict(reserved=1), vb.VEGAS_ERR_SHAPE),
     (dict(max_seq_len=(1 << 30) + 16, max_blocks=(1 << 26) + 1), vb.VEGAS_ERR_UNSUPPORTED),
 ])
 def test_verify_rejects_bad_descriptors(over, status):

@@ -412,7 +412,8 @@ def test_select_bit_exact_with_ties_and_budgets():
         assert np.array_equal(ssl.cpu().numpy(), ref_ssl)
 
 
-SCORE_KINDS = ["uniform", "all_equal", "four_values", "signed", "clustered_1_percent", "denormal", "zeros_and_inf"]
+SCORE_KINDS = ["uniform", "all_equal", "four_values", "signed", "clustered_1_percent", "denormal", "zeros_and_inf",
+               "with_nan"]
 
 
 @pytest.mark.parametrize("pages", [65, 2048, 8193])
@@ -438,6 +439,12 @@ def test_select_is_bit_exact_on_any_score_distribution(kind, pages):
             x = (1.0 + rng.random(pages) * 0.01) / pages
         elif kind == "denormal":
             x = rng.random(pages) * 1e-42
+        elif kind == "with_nan":                          # NaN of either sign ranks below every number, -inf included
+            x = rng.standard_normal(pages).astype(np.float32)
+            x[rng.integers(0, pages, size=pages // 3)] = np.float32(np.nan)
+            neg = rng.integers(0, pages, size=pages // 8)
+            x[neg] = np.frombuffer(np.uint32(0xFFC00001).tobytes(), dtype=np.float32)[0]
+            x[rng.integers(0, pages, size=4)] = -np.inf
         else:
             x = rng.random(pages) ** 8
             x[rng.integers(0, pages, size=pages // 4)] = 0.0

@@ -198,8 +198,7 @@ def test_short_selections_need_no_merge_kernel(name, B, Hq, Hkv, D, P, lens, bud
     ws = torch.empty(vb.vegas_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     ws.fill_(0xFF)
     out = torch.full((B, Hq, D), float("nan"), dtype=torch.bfloat16, device=dev)
-    desc.launch_stages = vb.STAGE_STREAM                        # the streaming kernel alone completes the call
-    vb.vegas_draft_attention(desc, *args, out, ws)
+    vb.vegas_draft_attention(desc, *args, out, ws, stages=vb.STAGE_STREAM)   # the streaming kernel alone completes the call
     torch.cuda.synchronize()
     kc = L.k_cache.reshape(-1, P, Hkv, D)
     vc = L.v_cache.reshape(-1, P, Hkv, D)

@@ -303,7 +303,7 @@ def test_selection_matches_numpy_partition_on_distinct_scores():
         assert np.unique(scores).size == nblk
         budget = int(rng.integers(1, PAGE * nblk + 40))
         ids = O.select_logical(scores, n, G, budget)
-        forced = O.forced_pages(n, G)
+        forced = np.array(sorted({i // PAGE for i in range(max(n - G, 0), n)}))     # pages of the last G positions
         k = max(min(-(-budget // PAGE), nblk), forced.size)
         assert ids.size == k and np.all(np.diff(ids) > 0)
         assert np.isin(forced, ids).all()
@@ -313,6 +313,32 @@ def test_selection_matches_numpy_partition_on_distinct_scores():
             kth = np.sort(scores[others])[::-1][free.size - 1]
             assert np.all(scores[free] >= kth)
             assert np.all(scores[np.setdiff1d(others, free)] < kth)
+
+
+def test_nan_scores_rank_below_every_number():
+    """A NaN score (of either sign) is taken after every number, -inf included, and NaNs among themselves
+    by index: checked against a plain Python sort on the key (is NaN, -score, index)."""
+    rng = np.random.default_rng(77)
+    neg_nan = np.frombuffer(np.uint32(0xFFC00001).tobytes(), dtype=np.float32)[0]
+    for trial in range(30):
+        nblk = int(rng.integers(4, 120))
+        n = PAGE * nblk - int(rng.integers(0, PAGE))
+        G = int(rng.integers(1, 8))
+        scores = rng.standard_normal(nblk).astype(np.float32)
+        scores[rng.integers(0, nblk, size=nblk // 3)] = np.nan
+        scores[rng.integers(0, nblk, size=nblk // 6)] = neg_nan
+        scores[rng.integers(0, nblk, size=2)] = -np.inf
+        budget = int(rng.integers(1, PAGE * nblk + 40))
+        forced = sorted({i // PAGE for i in range(max(n - G, 0), n)})
+        k = max(min(-(-budget // PAGE), nblk), len(forced))
+        rest = [j for j in range(nblk) if j not in forced]
+        ranked = sorted(rest, key=lambda j: (bool(np.isnan(scores[j])), -float(scores[j]) if not np.isnan(scores[j]) else 0.0, j))
+        want = sorted(forced + ranked[:k - len(forced)])
+        assert list(O.select_logical(scores, n, G, budget)) == want
+        # tokens: the same rule at token granularity
+    tok = np.array([0.5, np.nan, -np.inf, 0.25, neg_nan, 0.75, 0.0, 0.0], dtype=np.float32)
+    assert list(O.select_tokens_logical(tok, n=10, num_queries=2, budget_tokens=5)) == [0, 3, 5, 8, 9]
+    assert list(O.select_tokens_logical(tok, n=10, num_queries=2, budget_tokens=9)) == [0, 1, 2, 3, 5, 6, 7, 8, 9]
 
 
 def test_planted_dominant_key_is_always_selected():
