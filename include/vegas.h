@@ -233,6 +233,27 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
                           void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * vegas_draft_attention for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results, but the chunk partials live in a scratch array inside the library's
+ * device image (vegas_static_scratch_bytes() bytes per device, held until the process ends) instead of a
+ * caller's workspace.  The call allocates nothing.
+ *   - Returns VEGAS_ERR_WORKSPACE, before anything is launched, when the descriptor needs more scratch
+ *     than that (compare vegas_workspace_bytes(desc), for a draft-only descriptor, with the limit).
+ *   - All calls on one device share the one array: calls that may overlap in time (different streams
+ *     without ordering, different threads) race on it and must be serialised by the caller.  Nothing
+ *     in the array has to survive between calls and nothing in it has to start at zero.
+ *   - The array's device address is looked up once per device (by vegas_init(), else by the first call
+ *     on that device), with that device current.
+ */
+int vegas_draft_attention_static(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                 const int32_t* sel_table, const int32_t* sel_seq_lens,
+                                 void* out, void* hip_stream);
+
+/* Size in bytes of the built-in scratch array that vegas_draft_attention_static uses. */
+size_t vegas_static_scratch_bytes(void);
+
+/*
  * Profiling aids, not part of the method: the same calls restricted to some of their kernels.
  * `stages` is a mask of VEGAS_STAGE_* bits (0 = the whole call); with anything but the whole call the
  * outputs are incomplete.  The benchmark times the KV-streaming kernel alone through these.

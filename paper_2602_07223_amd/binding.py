@@ -33,6 +33,7 @@ STAGE_MERGE = 2
 
 EXPORTS = ("vegas_init", "vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
            "vegas_select_tokens", "vegas_extend_selection", "vegas_draft_attention",
+           "vegas_draft_attention_static", "vegas_static_scratch_bytes",
            "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_strerror")
 
 
@@ -97,6 +98,10 @@ def load_library(path: Optional[str] = None):
     lib.vegas_extend_selection.argtypes = [D, P, P, ctypes.c_int32, P, P, P]
     lib.vegas_draft_attention.restype = ctypes.c_int
     lib.vegas_draft_attention.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P]
+    lib.vegas_draft_attention_static.restype = ctypes.c_int
+    lib.vegas_draft_attention_static.argtypes = [D, P, P, P, P, P, P, P]
+    lib.vegas_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.vegas_static_scratch_bytes.argtypes = []
     lib.vegas_debug_verify_attention_stages.restype = ctypes.c_int
     lib.vegas_debug_verify_attention_stages.argtypes = [D, P, P, P, P, P, P, P, P, ctypes.c_size_t, P, ctypes.c_int32]
     lib.vegas_debug_draft_attention_stages.restype = ctypes.c_int
@@ -275,6 +280,24 @@ def vegas_draft_attention(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_s
         rc = load_library().vegas_draft_attention(*args)
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_draft_attention")
+
+
+def vegas_static_scratch_bytes() -> int:
+    return int(load_library().vegas_static_scratch_bytes())
+
+
+def vegas_draft_attention_static(desc: VegasDesc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, stream=None) -> None:
+    """vegas_draft_attention without a workspace argument: the library's built-in scratch array is used."""
+    if not (isinstance(q, int) and isinstance(k_cache, int)):
+        d = desc
+        rows = d.batch * d.num_q_heads * d.head_dim * 2
+        _check_extents("vegas_draft_attention_static", q=(q, rows), out=(out, rows),
+                       k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
+                       sel_table=(sel_table, d.batch * d.max_sel_blocks * 4), sel_seq_lens=(sel_seq_lens, d.batch * 4))
+    rc = load_library().vegas_draft_attention_static(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                                     _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out), _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_draft_attention_static")
 
 
 # ---------------------------------------------------------------------------------------------

@@ -405,6 +405,37 @@ int launch_combine(const vegas_desc* d, const SplitPlan& pl, const SplitParams& 
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
+// Scratch of vegas_draft_attention_static: the chunk partials of one draft call, in the library's own device image
+// instead of a caller's workspace.  Every device the library runs on holds its own copy of the array at its own
+// address until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address it yields (per device, asked once with that device current) is what kernels and copies get.
+constexpr size_t kStaticScratchBytes = size_t(8) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch_address(void** out) {
+  static std::mutex mu;
+  static std::map<int, void*> known;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return VEGAS_ERR_LAUNCH;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  const auto it = known.find(dev);
+  if (it != known.end()) {
+    *out = it->second;
+    return VEGAS_OK;
+  }
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+    (void)hipGetLastError();
+    return VEGAS_ERR_LAUNCH;
+  }
+  known[dev] = ptr;
+  *out = ptr;
+  return VEGAS_OK;
+}
+
 // Every kernel that is launched with dynamic LDS, for vegas_init: f(kernel address).
 template <typename F>
 int for_each_lds_kernel(F f) {
@@ -450,9 +481,12 @@ int vegas_init(void) {
     return VEGAS_ERR_LAUNCH;
   }
   (void)device_cu_count();
+  void* ptr = nullptr;
+  if (int rc = static_scratch_address(&ptr)) return rc;
   return for_each_lds_kernel([](const void* kern) { return ensure_dynamic_lds(kern, 160 * 1024); });
 }
 
+size_t vegas_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 size_t vegas_workspace_bytes(const vegas_desc* desc) {
   if (check_common(desc) != VEGAS_OK) return 0;
@@ -713,6 +747,18 @@ int vegas_draft_attention(const vegas_desc* desc, const void* q, const void* k_c
                           const int32_t* sel_table, const int32_t* sel_seq_lens, void* out, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
   return draft_impl(desc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace, workspace_bytes, hip_stream, 0);
+}
+
+int vegas_draft_attention_static(const vegas_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                 const int32_t* sel_table, const int32_t* sel_seq_lens, void* out, void* hip_stream) {
+  const int rc = check_common(desc);
+  if (rc != VEGAS_OK) return rc;
+  SplitPlan pl;
+  if (int prc = plan_draft(desc, &pl)) return prc;
+  if (pl.total > kStaticScratchBytes) return VEGAS_ERR_WORKSPACE;      // the call needs more than the built-in scratch
+  void* ptr = nullptr;
+  if (int src = static_scratch_address(&ptr)) return src;
+  return draft_impl(desc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, ptr, kStaticScratchBytes, hip_stream, 0);
 }
 
 int vegas_debug_verify_attention_stages(const vegas_desc* desc, const void* q, const void* k_cache,

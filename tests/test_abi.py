@@ -172,6 +172,16 @@ def test_select_and_draft_reject_bad_arguments():
     assert e.value.status == vb.VEGAS_ERR_WORKSPACE
 
 
+def test_static_scratch_refuses_what_does_not_fit():
+    """A descriptor whose chunk partials exceed the built-in array is refused on the host, before any launch."""
+    desc = vb.make_desc(batch=4096, num_q_heads=64, num_kv_heads=8, num_queries=1, max_blocks=64, max_sel_blocks=64,
+                        max_seq_len=1024, num_pages=64, softmax_scale=0.1)
+    assert vb.vegas_workspace_bytes(desc) > vb.vegas_static_scratch_bytes()
+    with pytest.raises(vb.VegasError) as e:
+        vb.vegas_draft_attention_static(desc, A, A, A, A, A, A)
+    assert e.value.status == vb.VEGAS_ERR_WORKSPACE
+
+
 def test_product_path_does_not_touch_the_oracle():
     pkg = os.path.join(ROOT, "paper_2602_07223_amd")
     for dirpath, _, files in os.walk(pkg):
