@@ -267,6 +267,17 @@ int vegas_debug_draft_attention_stages(const vegas_desc* desc, const void* q, co
                                        void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
                                        int32_t stages);
 
+/*
+ * Measurement yardstick, not part of the method: one kernel that does nothing but read two device buffers of
+ * bytes_each bytes (a multiple of 16; 16-byte aligned) front to back, coalesced, with `workgroups` workgroups of
+ * 256 threads, each on a contiguous slice; non_temporal != 0 marks the loads as read-once, as the verification
+ * pass does.  `sink` receives workgroups * 256 32-bit words (their only purpose is to keep the loads alive).
+ * The benchmark times it over the same K and V caches the verification kernel streams: the rate it reaches is
+ * what the memory system gives a kernel of that footprint that computes nothing.
+ */
+int vegas_debug_stream_read(const void* a, const void* b, size_t bytes_each, int32_t workgroups, int32_t non_temporal,
+                            void* sink, void* hip_stream);
+
 /* Static, human-readable text for a vegas_status. */
 const char* vegas_strerror(int status);
 

@@ -34,7 +34,8 @@ STAGE_MERGE = 2
 EXPORTS = ("vegas_init", "vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
            "vegas_select_tokens", "vegas_extend_selection", "vegas_draft_attention",
            "vegas_draft_attention_static", "vegas_static_scratch_bytes",
-           "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_strerror")
+           "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_debug_stream_read",
+           "vegas_strerror")
 
 
 class VegasDesc(ctypes.Structure):
@@ -106,6 +107,8 @@ def load_library(path: Optional[str] = None):
     lib.vegas_debug_verify_attention_stages.argtypes = [D, P, P, P, P, P, P, P, P, ctypes.c_size_t, P, ctypes.c_int32]
     lib.vegas_debug_draft_attention_stages.restype = ctypes.c_int
     lib.vegas_debug_draft_attention_stages.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P, ctypes.c_int32]
+    lib.vegas_debug_stream_read.restype = ctypes.c_int
+    lib.vegas_debug_stream_read.argtypes = [P, P, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, P, P]
     lib.vegas_strerror.restype = ctypes.c_char_p
     lib.vegas_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -298,6 +301,16 @@ def vegas_draft_attention_static(desc: VegasDesc, q, k_cache, v_cache, sel_table
                                                      _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out), _stream(stream))
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_draft_attention_static")
+
+
+def vegas_debug_stream_read(a, b, bytes_each: int, workgroups: int, non_temporal: bool, sink, stream=None) -> None:
+    """The plain streaming read the benchmark uses as its yardstick (see include/vegas.h)."""
+    if not isinstance(a, int):
+        _check_extents("vegas_debug_stream_read", a=(a, bytes_each), b=(b, bytes_each), sink=(sink, workgroups * 256 * 4))
+    rc = load_library().vegas_debug_stream_read(_ptr(a), _ptr(b), int(bytes_each), int(workgroups), int(bool(non_temporal)),
+                                                _ptr(sink), _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_debug_stream_read")
 
 
 # ---------------------------------------------------------------------------------------------

@@ -42,5 +42,40 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
     return LIB_PATH
 
 
+def kernel_resource_usage() -> dict:
+    """Compiles the device code once more (nothing is written) with the compiler's resource report switched on and
+    returns {demangled kernel name: {"vgprs", "agprs", "sgprs", "scratch_bytes_per_lane", "lds_bytes", "occupancy"}}.
+    Used by the CPU tests to hold the streaming kernels to zero scratch (no register spills)."""
+    import re
+    build_flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc_path(), *build_flags, "-c", "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+           "-o", os.devnull] + [os.path.join(CSRC, s) for s in SOURCES]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    names, out, cur = [], {}, None
+    keys = {"VGPRs": "vgprs", "AGPRs": "agprs", "TotalSGPRs": "sgprs", "ScratchSize [bytes/lane]": "scratch_bytes_per_lane",
+            "LDS Size [bytes/block]": "lds_bytes", "Occupancy [waves/SIMD]": "occupancy"}
+    for line in res.stderr.splitlines():
+        m = re.search(r"remark: +(.*?)(?: \[-Rpass-analysis.*)?$", line)
+        if not m:
+            continue
+        text = m.group(1).strip()
+        if text.startswith("Function Name:"):
+            cur = text.split(":", 1)[1].strip()
+            names.append(cur)
+            out[cur] = {}
+            continue
+        for k, short in keys.items():
+            if cur is not None and text.startswith(k + ":"):
+                out[cur][short] = int(text.split(":", 1)[1].strip())
+    filt = shutil.which("llvm-cxxfilt") or "/opt/rocm/llvm/bin/llvm-cxxfilt"
+    if names and os.path.exists(filt):
+        dem = subprocess.run([filt], input="\n".join(names), capture_output=True, text=True).stdout.splitlines()
+        if len(dem) == len(names):
+            out = {d: out[n] for d, n in zip(dem, names)}
+    return out
+
+
 if __name__ == "__main__":
     print(build_library())

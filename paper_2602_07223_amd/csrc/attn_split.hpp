@@ -114,6 +114,37 @@ __device__ __forceinline__ void load_queries_to_lds(unsigned char* qlds, const S
   }
 }
 
+// The same copy in two phases, for the kernels' common case (no sum rows): the loads leave as soon as the workgroup
+// knows its sequence and head -- they depend on nothing else, so they travel together with the first page-table
+// request instead of after the first K/V requests -- and reach LDS later.  QI 16-byte pieces per thread.
+template <int D, int QI>
+__device__ __forceinline__ void issue_query_loads(u32x4 (&raw)[QI], const SplitParams& p, int b, int h, int rows, int row0,
+                                                  int valid, int tid, int threads) {
+  constexpr int CH = D / 8;
+#pragma unroll
+  for (int i = 0; i < QI; ++i) {
+    const int idx = tid + i * threads;
+    const int row = idx / CH, chunk = idx % CH;
+    raw[i] = u32x4{0u, 0u, 0u, 0u};
+    if (idx < rows * CH && row < valid) {
+      const int t = (row0 + row) / p.g, j = (row0 + row) % p.g;
+      raw[i] = *reinterpret_cast<const u32x4*>(
+          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
+    }
+  }
+}
+template <int D, int QI>
+__device__ __forceinline__ void store_queries_to_lds(unsigned char* qlds, const u32x4 (&raw)[QI], int rows, int tid,
+                                                     int threads) {
+  constexpr int CH = D / 8;
+  constexpr int pitch = row_pitch(D);
+#pragma unroll
+  for (int i = 0; i < QI; ++i) {
+    const int idx = tid + i * threads;
+    if (idx < rows * CH) *reinterpret_cast<u32x4*>(qlds + (idx / CH) * pitch + (idx % CH) * 16) = raw[i];
+  }
+}
+
 // NW: waves per workgroup; WPS: waves per SIMD the register budget is sized for (2 -> at most
 // 256 registers per lane).  One workgroup handles up to 32 query rows of one KV head.
 // NT_LOADS: K/V are read with the non-temporal hint -- right for the verification pass that streams
@@ -194,6 +225,10 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   // known (one memory round trip less at the head of the kernel): indices are clamped to the table
   // row, entries past the sequence's pages are read but never used.
   const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
+  // Query loads leave now (they depend on the sequence and the head only).
+  constexpr int QI = (32 * CH + NW * 64 - 1) / (NW * 64);
+  u32x4 qraw[QI];
+  if constexpr (COLLECT != 2) issue_query_loads<D, QI>(qraw, p, b, h, NB * 32, row0, Rl, tid, NW * 64);
   const int c0 = split * chunk_tokens;
   const int tile_first = c0 / kTile + wave;
   int pagevec = 0;
@@ -319,7 +354,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   // ---- query rows -> LDS [row][CH chunks of 16 B], padded rows; rows past R are zero
   // COLLECT == 2: the last row block carries the sum of the collected query rows in rows Rl (high part) and Rl + 1 (low part)
   const bool has_extra = COLLECT == 2 && rb == p.row_blocks - 1;
-  load_queries_to_lds<D>(qlds, p, b, h, NB * 32, row0, Rl, has_extra, tid, NW * 64);
+  if constexpr (COLLECT == 2) load_queries_to_lds<D>(qlds, p, b, h, NB * 32, row0, Rl, has_extra, tid, NW * 64);
+  else store_queries_to_lds<D, QI>(qlds, qraw, NB * 32, tid, NW * 64);
   int limit[NB];                             // last visible token of this lane's row
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {

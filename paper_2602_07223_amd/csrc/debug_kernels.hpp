@@ -1,0 +1,46 @@
+// Measurement aids that are not part of the method: a plain streaming read of two buffers, the yardstick the
+// KV-streaming kernels are held against (what the memory system delivers to a kernel that does nothing else).
+#pragma once
+#include "vegas_common.hpp"
+
+namespace vegas {
+
+struct StreamReadParams {
+  const u32x4* a;          // two buffers of `vecs` 16-byte vectors each (a K cache and a V cache, say)
+  const u32x4* b;
+  uint64_t vecs;
+  uint32_t* sink;          // [workgroups * 256]: what keeps the loads alive
+};
+
+// Every workgroup reads one contiguous slice of each buffer: 256 threads x 16 bytes per instruction (4 KB, fully
+// coalesced), eight instructions per buffer in flight per thread (64 KB per workgroup and buffer), the shape of the
+// streaming kernels' K loads.  Indices past the end are clamped to the last vector (re-read, never out of bounds).
+template <bool NT>
+__global__ __launch_bounds__(256) void stream_read_kernel(const StreamReadParams p) {
+  constexpr uint64_t kStep = 256 * 8;
+  const uint64_t per_wg = (p.vecs + gridDim.x - 1) / gridDim.x;
+  const uint64_t span = (per_wg + kStep - 1) / kStep * kStep;
+  const uint64_t begin = static_cast<uint64_t>(blockIdx.x) * span;
+  const uint64_t end = begin + span < p.vecs ? begin + span : p.vecs;
+  const uint64_t last = p.vecs - 1;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (uint64_t i = begin + threadIdx.x; i < end; i += kStep) {
+    u32x4 x[8], y[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint64_t j = i + 256u * u < last ? i + 256u * u : last;
+      if constexpr (NT) {
+        x[u] = __builtin_nontemporal_load(p.a + j);
+        y[u] = __builtin_nontemporal_load(p.b + j);
+      } else {
+        x[u] = p.a[j];
+        y[u] = p.b[j];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= x[u] ^ y[u];
+  }
+  p.sink[blockIdx.x * 256 + threadIdx.x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+}
+
+}  // namespace vegas

@@ -13,6 +13,7 @@
 #include "attn_finalize.hpp"
 #include "attn_pair.hpp"
 #include "attn_split.hpp"
+#include "debug_kernels.hpp"
 #include "select_blocks.hpp"
 #include "select_tokens.hpp"
 #include "vegas_common.hpp"
@@ -774,6 +775,22 @@ int vegas_debug_draft_attention_stages(const vegas_desc* desc, const void* q, co
                                        void* workspace, size_t workspace_bytes, void* hip_stream, int32_t stages) {
   return draft_impl(desc, q, k_cache, v_cache, sel_table, sel_seq_lens, out, workspace, workspace_bytes, hip_stream,
                     stages);
+}
+
+int vegas_debug_stream_read(const void* a, const void* b, size_t bytes_each, int32_t workgroups, int32_t non_temporal,
+                            void* sink, void* hip_stream) {
+  if (!a || !b || !sink) return VEGAS_ERR_NULL;
+  if (bytes_each < 16 || (bytes_each % 16) != 0 || workgroups <= 0 || workgroups > (1 << 20)) return VEGAS_ERR_SHAPE;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(sink)) return VEGAS_ERR_ALIGN;
+  StreamReadParams rp;
+  rp.a = static_cast<const u32x4*>(a);
+  rp.b = static_cast<const u32x4*>(b);
+  rp.vecs = bytes_each / 16;
+  rp.sink = static_cast<uint32_t*>(sink);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (non_temporal) hipLaunchKernelGGL(stream_read_kernel<true>, dim3(workgroups), dim3(256), 0, st, rp);
+  else hipLaunchKernelGGL(stream_read_kernel<false>, dim3(workgroups), dim3(256), 0, st, rp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
 const char* vegas_strerror(int status) {
