@@ -86,7 +86,8 @@ def device_copies(harness, base, want: int):
     for _ in range(want - 1):
         copies.append(harness.DeviceLayer(q_verify=base.q_verify, q_draft=base.q_draft,
                                           k_cache=base.k_cache.clone(), v_cache=base.v_cache.clone(),
-                                          block_table=base.block_table, seq_lens=base.seq_lens))
+                                          block_table=base.block_table, seq_lens=base.seq_lens,
+                                          k_new=base.k_new, v_new=base.v_new, seq_lens_live=base.seq_lens_live))
     return copies
 
 
@@ -244,6 +245,10 @@ def main() -> int:
                     help="page: 16-token pages scored by softmax weights (the default path); token: the paper's own "
                          "variant -- averaged logits per token (Eq. 3 rows), top-k over tokens, one-token pages")
     ap.add_argument("--budget", type=int, default=0, help="KV budget in tokens (0: the workload's)")
+    ap.add_argument("--live", action="store_true",
+                    help="a live drafting phase: before each draft call the drafted token's K/V is appended to the cache "
+                         "(vegas_append_kv) and the selection grows by it (vegas_extend_selection); the step then is "
+                         "verify + select + G x (append + extend + draft) + one small copy that rewinds the lengths")
     ap.add_argument("--sweep", choices=["collect", "page_size"], default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -270,6 +275,8 @@ def main() -> int:
     workload = args.workload
     spec = all_workloads(synth)[workload]
     L = synth.make_layer(spec, args.layer)
+    if args.live:
+        L = synth.with_growth(L, spec.num_queries)
     dev = torch.device("cuda:0")
     base = harness.DeviceLayer.upload(L, dev)
     copies = device_copies(harness, base, copies_for(base, args.copies))
@@ -277,6 +284,7 @@ def main() -> int:
     budget = args.budget or spec.budget_tokens
     path = harness.VegasPath.for_layer(L, budget_tokens=budget, verify_chunk=args.verify_chunk,
                                        draft_chunk=args.draft_chunk, token_granular=token,
+                                       growth=spec.num_queries if args.live else 0,
                                        collect_rows=vb.COLLECT_FIRST_LAST if token else vb.COLLECT_ALL_ROWS)
     G = spec.num_queries
     stream = int(torch.cuda.current_stream(dev).cuda_stream)
@@ -284,7 +292,10 @@ def main() -> int:
     K, W = args.steps, args.warmup
 
     def step(i: int) -> None:
-        path.iteration(copies[i % len(copies)])
+        if args.live:
+            path.live_iteration(copies[i % len(copies)])
+        else:
+            path.iteration(copies[i % len(copies)])
 
     for i in range(W):
         step(i)
@@ -362,6 +373,7 @@ def main() -> int:
                    "num_q_heads": spec.num_q_heads, "num_kv_heads": spec.num_kv_heads,
                    "head_dim": spec.head_dim, "page_size": 16, "gamma": spec.gamma,
                    "kv_budget_tokens": budget, "draft_steps": G, "variant": args.variant,
+                   "live_drafting": bool(args.live),
                    "kv_cache_copies_rotated": len(copies)},
         "iteration_kv_bytes": iter_bytes,
         "iteration_gbps": iter_bytes / (us_per_step * 1e-6) / 1e9,
@@ -448,7 +460,8 @@ def main() -> int:
                          "launch_floor_us_graph_replay": floor_graph_us,
                          "launch_floor_us_eager_through_binding": floor_eager_us}
 
-    if not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0 and not token and not args.budget:
+    if (not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0 and not token and not args.budget
+            and not args.live):
         out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens, workload)
     print(json.dumps(out), flush=True)
     return 0

@@ -194,6 +194,23 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The K/V write between two draft steps (Sec. 2.3: tokens are drafted one after the other, each attending to its
+ * predecessors).  Every sequence takes num_new more tokens: token t of sequence b is stored at position
+ * seq_lens[b] + t, i.e. in page block_table[b][(seq_lens[b] + t) / 16], slot (seq_lens[b] + t) % 16, for every KV
+ * head (the cache layout of App. D with the descriptor's strides), and seq_lens[b] is advanced by num_new.
+ *   k_new / v_new  bf16 [B, num_new, H_kv, D]  the new tokens' keys and values (num_new at most 4096)
+ *   block_table    int32 [B, max_blocks]       must already name a page for every new position (allocating
+ *                                              pages is the caller's business)
+ *   seq_lens       int32 [B]                   lengths BEFORE the append on entry, AFTER it on return
+ *   k_cache / v_cache                          written in place
+ * A sequence for which seq_lens[b] + num_new would pass min(max_seq_len, 16 * max_blocks) takes nothing and keeps
+ * its length.  Follow with vegas_extend_selection(desc, ..., num_new, ...) so that the next draft call sees the
+ * new tokens.  One small kernel (one workgroup per sequence); no workspace.  desc->page_size is 16.
+ */
+int vegas_append_kv(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
+                    const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache, void* hip_stream);
+
+/*
  * Growth of a selection while drafting (Sec. 3.2, last sentence: tokens after the prefix are kept).
  * Each draft step appends one token's K/V to the cache; the next draft step must see it.  Call this
  * after the caller has written the new K/V and increased seq_lens: for every sequence it adds the

@@ -322,6 +322,33 @@ def extend_selection(sel_table: np.ndarray, sel_seq_lens: np.ndarray, block_tabl
     return sel, ssl
 
 
+def append_kv(k_cache: np.ndarray, v_cache: np.ndarray, k_new: np.ndarray, v_new: np.ndarray,
+              block_table: np.ndarray, seq_lens: np.ndarray, max_seq_len: Optional[int] = None):
+    """The cache after every sequence has taken T more tokens (the drafted tokens of Sec. 2.3, whose
+    K/V the draft steps that follow must see).  Token t of sequence b becomes position n_b + t: page
+    block_table[b][(n_b + t) // 16], slot (n_b + t) % 16, all KV heads (the paged layout of App. D:
+    [page, slot, KV head, dim]).  k_new / v_new uint16 [B, T, H_kv, D].  A sequence that would pass
+    max_seq_len (default: what its table row can address) takes nothing.  Returns copies of both
+    caches and the new lengths (n_b + T for the sequences that took the tokens)."""
+    kc = np.array(k_cache, copy=True)
+    vc = np.array(v_cache, copy=True)
+    lens = np.array(seq_lens, copy=True)
+    B, T = k_new.shape[0], k_new.shape[1]
+    cap = block_table.shape[1] * PAGE if max_seq_len is None else min(int(max_seq_len), block_table.shape[1] * PAGE)
+    for b in range(B):
+        n = int(seq_lens[b])
+        if n < 0 or n + T > cap:
+            continue
+        for t in range(T):
+            i = n + t
+            page = int(block_table[b, i // PAGE])
+            for h in range(kc.shape[2]):
+                kc[page, i % PAGE, h, :] = k_new[b, t, h, :]
+                vc[page, i % PAGE, h, :] = v_new[b, t, h, :]
+        lens[b] = n + T
+    return kc, vc, lens
+
+
 def draft_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
                     sel_table: np.ndarray, sel_seq_lens: np.ndarray, scale: float) -> np.ndarray:
     """One draft query per sequence attends over exactly the tokens of the selected pages.

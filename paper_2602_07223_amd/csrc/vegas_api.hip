@@ -14,6 +14,7 @@
 #include "attn_pair.hpp"
 #include "attn_split.hpp"
 #include "debug_kernels.hpp"
+#include "kv_append.hpp"
 #include "select_blocks.hpp"
 #include "select_tokens.hpp"
 #include "vegas_common.hpp"
@@ -680,6 +681,34 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores, const
   for (int pass = 0; pass < 4; ++pass)
     hipLaunchKernelGGL(token_select_hist, grid, dim3(kTokThreads), 0, st, tp, pass);
   hipLaunchKernelGGL(token_select_write, grid, dim3(kTokThreads), 0, st, tp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+int vegas_append_kv(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
+                    const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache, void* hip_stream) {
+  int rc = check_common(desc);
+  if (rc == VEGAS_OK) rc = check_paged16(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (!k_new || !v_new || !block_table || !seq_lens || !k_cache || !v_cache) return VEGAS_ERR_NULL;
+  if (num_new <= 0 || num_new > 4096) return VEGAS_ERR_SHAPE;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return VEGAS_ERR_ALIGN;
+  AppendParams ap;
+  ap.k_new = static_cast<const uint16_t*>(k_new);
+  ap.v_new = static_cast<const uint16_t*>(v_new);
+  ap.k_cache = static_cast<uint16_t*>(k_cache);
+  ap.v_cache = static_cast<uint16_t*>(v_cache);
+  ap.block_table = block_table;
+  ap.seq_lens = seq_lens;
+  ap.T = num_new;
+  ap.Hkv = desc->num_kv_heads;
+  ap.D = desc->head_dim;
+  ap.max_blocks = desc->max_blocks;
+  ap.max_tokens = desc->max_seq_len;
+  ap.page_stride = desc->kv_page_stride;
+  ap.token_stride = desc->kv_token_stride;
+  ap.head_stride = desc->kv_head_stride;
+  ap.num_pages = desc->num_pages;
+  hipLaunchKernelGGL(append_kv_kernel, dim3(desc->batch), dim3(256), 0, static_cast<hipStream_t>(hip_stream), ap);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 

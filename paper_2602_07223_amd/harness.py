@@ -35,13 +35,20 @@ class DeviceLayer:
     v_cache: torch.Tensor
     block_table: torch.Tensor   # int32 [B, max_blocks]
     seq_lens: torch.Tensor      # int32 [B]
+    k_new: Optional[torch.Tensor] = None     # bf16 [steps, B, 1, Hkv, D]: rows the live drafting phase appends
+    v_new: Optional[torch.Tensor] = None
+    seq_lens_live: Optional[torch.Tensor] = None   # int32 [B]: the lengths the live drafting phase advances
 
     @staticmethod
     def upload(L: LayerInputs, device="cuda:0") -> "DeviceLayer":
-        return DeviceLayer(
+        dl = DeviceLayer(
             q_verify=bf16_to_device(L.q_verify, device), q_draft=bf16_to_device(L.q_draft, device),
             k_cache=bf16_to_device(L.k_cache, device), v_cache=bf16_to_device(L.v_cache, device),
             block_table=torch.from_numpy(L.block_table).to(device), seq_lens=torch.from_numpy(L.seq_lens).to(device))
+        if L.k_new is not None:
+            dl.k_new, dl.v_new = bf16_to_device(L.k_new, device), bf16_to_device(L.v_new, device)
+            dl.seq_lens_live = dl.seq_lens.clone()
+        return dl
 
 
 class VegasPath:
@@ -51,7 +58,8 @@ class VegasPath:
                  max_seq_len: int, num_pages: int, budget_tokens: int, softmax_scale: float,
                  collect_rows: int = vb.COLLECT_ALL_ROWS, head_dim: int = 128, device="cuda:0",
                  verify_chunk: int = 0, draft_chunk: int = 0, max_sel_blocks: int = 0,
-                 score_metric: int = vb.METRIC_PAGE_WEIGHTS, token_granular: bool = False, window: int = 0):
+                 score_metric: int = vb.METRIC_PAGE_WEIGHTS, token_granular: bool = False, window: int = 0,
+                 growth: int = 0):
         """token_granular: the paper's own variant -- verification collects averaged logits per token,
         selection picks single tokens, drafting walks one-token pages (Sec. 3.3, Sec. 4).
         window > 0: verification of a banded layer (local masking; needs collect_rows = COLLECT_NONE)."""
@@ -65,7 +73,8 @@ class VegasPath:
         want = max(min((budget_tokens + PAGE - 1) // PAGE, max_pages), (num_queries + PAGE - 2) // PAGE + 1)
         if token_granular:                                   # sel_table rows hold token slots
             want = min(max(budget_tokens, num_queries), max_seq_len)
-        self.max_sel_blocks = max_sel_blocks or (want + 2)
+        # two entries of slack; a row of token slots also needs room for the tokens a live drafting phase appends
+        self.max_sel_blocks = max_sel_blocks or (want + 2 + (growth if token_granular else 0))
         common = dict(batch=batch, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads, num_queries=num_queries,
                       max_blocks=max_blocks, max_sel_blocks=self.max_sel_blocks, num_pages=num_pages,
                       softmax_scale=softmax_scale, head_dim=head_dim)
@@ -91,6 +100,14 @@ class VegasPath:
         self.sel_table = torch.empty((batch, self.max_sel_blocks), dtype=torch.int32, device=dev)
         self.sel_seq_lens = torch.empty((batch,), dtype=torch.int32, device=dev)
         self.out_draft = torch.empty((num_queries, batch, num_q_heads, head_dim), dtype=torch.bfloat16, device=dev)
+
+        # the K/V append of a live drafting phase may take every sequence up to `growth` tokens past max_seq_len
+        self.desc_append = vb.make_desc(max_seq_len=min(max_seq_len + growth, max_blocks * PAGE),
+                                        collect_rows=vb.COLLECT_NONE, **common)
+        # growing the selection: the block table's geometry with the selection's page size
+        ext = dict(common, num_pages=num_pages * PAGE) if token_granular else common
+        self.desc_extend = vb.make_desc(max_seq_len=min(max_seq_len + growth, max_blocks * PAGE),
+                                        collect_rows=vb.COLLECT_NONE, page_size=1 if token_granular else PAGE, **ext)
 
     @classmethod
     def for_layer(cls, L: LayerInputs, budget_tokens: Optional[int] = None, **kw) -> "VegasPath":
@@ -159,6 +176,24 @@ class VegasPath:
         vb.vegas_draft_attention(self.desc_draft, a["qd"][step], a["k"], a["v"], o["st"], o["ssl"], o["od"][step],
                                  o["ws"], stream=self.stream() if stream is None else stream,
                                  workspace_bytes=o["wsn"], stages=stages)
+
+    def live_iteration(self, dl: DeviceLayer) -> None:
+        """One decoding iteration with a live drafting phase (Sec. 2.3): verify and select at the layer's lengths,
+        then per draft step the new token's K/V is appended, the selection grows by it (Sec. 3.2, last sentence)
+        and the draft call attends over the grown selection.  The live lengths are rewound first (one small device
+        copy), so every iteration starts from the same state; the appended slots are simply overwritten."""
+        st = self.stream()
+        a, o = self._addrs(dl), self._own()
+        dl.seq_lens_live.copy_(dl.seq_lens)
+        self.verify(dl, st)
+        self.select(dl, stream=st)
+        sll = dl.seq_lens_live.data_ptr()
+        row = dl.k_new[0].numel() * dl.k_new.element_size()
+        for s in range(self.G):
+            vb.vegas_append_kv(self.desc_append, dl.k_new.data_ptr() + s * row, dl.v_new.data_ptr() + s * row, 1,
+                               a["bt"], sll, a["k"], a["v"], stream=st)
+            vb.vegas_extend_selection(self.desc_extend, a["bt"], sll, 1, o["st"], o["ssl"], stream=st)
+            self.draft(dl, s, st)
 
     def iteration(self, dl: DeviceLayer) -> None:
         """One decoding iteration's attention work for one layer: verify, select, G draft steps."""

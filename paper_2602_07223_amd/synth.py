@@ -138,6 +138,8 @@ class LayerInputs:
     sinks: List[np.ndarray]           # per sequence: planted sink positions
     hitters: List[np.ndarray]         # per sequence: hitter positions the verify queries align with
     draft_hitters: List[np.ndarray]   # per sequence: positions the draft queries align with
+    k_new: Optional[np.ndarray] = None    # uint16 [steps, B, 1, H_kv, D]: the K row each draft step appends (with_growth)
+    v_new: Optional[np.ndarray] = None
 
     @property
     def num_pages(self) -> int:
@@ -146,6 +148,33 @@ class LayerInputs:
     @property
     def max_blocks(self) -> int:
         return int(self.block_table.shape[1])
+
+
+def with_growth(L: "LayerInputs", steps: int) -> "LayerInputs":
+    """A copy of ``L`` prepared for a live drafting phase of ``steps`` appended tokens per sequence: the pool gets
+    the extra pages the new positions need (NaN-filled until written), the block table is widened where necessary
+    and names them, and k_new / v_new hold the rows each step appends -- N(0, std^2) like the rest of the cache,
+    drawn from stream 2 of the layer's seed.  Inputs only: nothing of the method is computed here."""
+    B = L.block_table.shape[0]
+    Hkv, D = L.k_cache.shape[2], L.k_cache.shape[3]
+    nblk = (L.seq_lens.astype(np.int64) + PAGE - 1) // PAGE
+    need = (L.seq_lens.astype(np.int64) + steps + PAGE - 1) // PAGE
+    extra = (need - nblk).astype(np.int64)
+    mb = max(L.max_blocks, int(need.max()))
+    table = np.full((B, mb), -1, dtype=np.int32)
+    table[:, :L.max_blocks] = L.block_table
+    first_new = L.num_pages
+    nxt = first_new
+    for b in range(B):
+        for j in range(int(extra[b])):
+            table[b, nblk[b] + j] = nxt
+            nxt += 1
+    pad = np.full((nxt - first_new, PAGE, Hkv, D), BF16_NAN, dtype=np.uint16)
+    std = L.spec.tensor_scale if L.spec.tensor_scale > 0 else 1.0 / np.sqrt(D)
+    k_new = normal_pool_bf16(L.seed, 2, (steps * B, 1, Hkv, D), std).reshape(steps, B, 1, Hkv, D)
+    v_new = normal_pool_bf16(L.seed, 3, (steps * B, 1, Hkv, D), std).reshape(steps, B, 1, Hkv, D)
+    return dataclasses.replace(L, k_cache=np.concatenate([L.k_cache, pad]), v_cache=np.concatenate([L.v_cache, pad]),
+                               block_table=table, k_new=k_new, v_new=v_new)
 
 
 _POOL_CHUNK_PAGES = 1024

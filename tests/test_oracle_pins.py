@@ -613,6 +613,48 @@ def test_extended_selection_covers_old_selection_and_new_tokens(P, n_old, num_ne
     np.testing.assert_allclose(out[0], ref, atol=1e-12)
 
 
+def test_append_kv_places_tokens_where_the_layout_says():
+    """append_kv against the layout definition (App. D: [page, slot, KV head, dim], 4096 bytes of K+V per token at
+    8 KV heads x 128 dims): the flat element offset of a token's row is worked out by hand here, sequences read
+    back through the (separately pinned) page gather equal old tokens followed by the new ones, nothing else in
+    the pool changes, and a sequence without room takes nothing."""
+    rng = np.random.default_rng(31)
+    Hkv, D, T = 8, 128, 3
+    num_pages, mb = 12, 4
+    kc = rng.integers(0, 1 << 16, size=(num_pages, PAGE, Hkv, D), dtype=np.uint16)
+    vc = rng.integers(0, 1 << 16, size=(num_pages, PAGE, Hkv, D), dtype=np.uint16)
+    table = np.array([[7, 2, 9, -1], [4, 11, 0, 5], [1, 3, 6, 8]], dtype=np.int32)
+    lens = np.array([30, 15, 62], dtype=np.int32)          # the third has room for two more tokens only
+    k_new = rng.integers(0, 1 << 16, size=(3, T, Hkv, D), dtype=np.uint16)
+    v_new = rng.integers(0, 1 << 16, size=(3, T, Hkv, D), dtype=np.uint16)
+    kc2, vc2, lens2 = O.append_kv(kc, vc, k_new, v_new, table, lens)
+    assert list(lens2) == [33, 18, 62]
+    # hand arithmetic: sequence 0, token 2 -> position 32 -> logical page 2 (physical 9), slot 0, head 5
+    flat = kc2.reshape(-1)
+    off = ((9 * PAGE + 0) * Hkv + 5) * D
+    assert off * 2 == 9 * 16 * 2048 + 5 * 256                # bytes: 2 KB of K per token, 256 B per head row
+    assert np.array_equal(flat[off:off + D], k_new[0, 2, 5])
+    # sequence 1, token 0 -> position 15 -> physical page 4, slot 15; token 1 -> position 16 -> physical page 11, slot 0
+    assert np.array_equal(vc2[4, 15], v_new[1, 0]) and np.array_equal(vc2[11, 0], v_new[1, 1])
+    for b in (0, 1):
+        for h in (0, 7):
+            old = O.gather_sequence(kc, table[b], int(lens[b]), h)
+            new = O.gather_sequence(kc2, table[b], int(lens2[b]), h)
+            assert np.array_equal(new[:lens[b]], old, equal_nan=True)       # (random bit patterns include NaNs)
+            assert np.array_equal(new[lens[b]:], O.decode_bf16(k_new[b, :, h, :]), equal_nan=True)
+    # everything that is not one of the six written slots is untouched, in both caches
+    touched = {(9, 0), (2, 14), (2, 15), (4, 15), (11, 0), (11, 1)}
+    for page in range(num_pages):
+        for slot in range(PAGE):
+            if (page, slot) not in touched:
+                assert np.array_equal(kc2[page, slot], kc[page, slot]) and np.array_equal(vc2[page, slot], vc[page, slot])
+            else:
+                assert not np.array_equal(kc2[page, slot], kc[page, slot])
+    # an explicit bound below the table's capacity
+    _, _, lens3 = O.append_kv(kc, vc, k_new, v_new, table, lens, max_seq_len=32)
+    assert list(lens3) == [30, 18, 62]
+
+
 def test_extend_selection_leaves_full_rows_and_empty_selections_alone():
     table = np.arange(8, dtype=np.int32)[None, :].repeat(2, axis=0)
     sel = np.array([[0, 1, 2, 3], [-1, -1, -1, -1]], dtype=np.int32)
