@@ -154,7 +154,10 @@ __device__ __forceinline__ void store_queries_to_lds(unsigned char* qlds, const 
 // 2 the paper's own metric (Sec. 3.2 footnote, App. B): per-token sums of the collected rows' LOGITS.
 // A sum of logits is linear in the query, sum_r q_r . k = (sum_r q_r) . k, so the sum of the collected
 // query rows of this KV head rides along as two spare rows of the query tile (a bf16 high part and a
-// bf16 low part, together good to 2^-17) and the first MFMA delivers the token sums for free.
+// bf16 low part, together good to 2^-17) and the first MFMA delivers the token sums for free.  The host puts
+// them in the last row block of the KV head; when that block is full (or one row short of full) the last
+// row block is one that holds nothing but those two rows (Rl = 0: it streams K like its siblings, parks the
+// token sums, and writes no partial output).
 // PS: log2 of the tokens per page of the table the kernel walks.  4 (16-token pages) is the path
 // described above; 0..3 (1, 2, 4, 8-token pages: Sec. 4 drafts with one-token pages, App. D sweeps
 // 1..16) is for draft calls only: a tile then spans 32 >> PS pages, every lane looks up the page of
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   }
   const int row0 = rb * 32;                  // first query row (of this KV head) handled here
   int* ids_lds = reinterpret_cast<int*>(sm_l + NW * NB * 32) + wave * 64;   // [2 tiles][32 page ids] of this wave
-  const int Rl = min(32, p.R - row0);        // valid rows in this block
+  const int Rl = max(min(32, p.R - row0), 0);   // valid rows in this block (none in a block that only carries the sum rows)
 
   // Physical page ids of the wave's next 32 tiles live in one register: lane (k, half) holds the id of
   // page `half` of tile tile_first + k*NW.  They are read back with readlane, so the streaming loop

@@ -97,17 +97,18 @@ int check_paged16(const vegas_desc* d) {
 // Rows stacked on one KV head decide the kernel variant; the chunk size decides the grid.
 // max_len bounds the lengths the call may see; small problems get small workgroups.
 // collect: 0 nothing, 1 page log-sum-exps [pages x rows], 2 token sums [padded tokens] per (sequence, KV head)
+// sum_block: the logit metric's two query-sum rows get a row block of their own (no spare rows in the last real one)
 int plan_split(const vegas_desc* d, int rows_per_head, int max_len, int collect, int wg_per_cu, SplitPlan* pl,
-               bool may_pair = false, bool may_finish = false) {
+               bool may_pair = false, bool may_finish = false, bool sum_block = false) {
   pl->R = rows_per_head;
   const int num_cu = device_cu_count();
   const int64_t heads = static_cast<int64_t>(d->batch) * d->num_kv_heads;
   if (rows_per_head > 128) return VEGAS_ERR_UNSUPPORTED;
-  pl->NB = (rows_per_head + 31) / 32;                // 32-row blocks
+  pl->NB = (rows_per_head + 31) / 32 + (sum_block ? 1 : 0);   // 32-row blocks
   pl->NW = 4;                                        // measured: 4-wave groups match or beat 8-wave groups everywhere
   // Two row blocks: one workgroup per chunk reads K/V once for both (attn_pair_kernel) when the chunk holds an even
   // number of tiles; otherwise (and for 3 or 4 blocks) sibling workgroups, one per block, share an XCD's L2.
-  pl->pair = may_pair && pl->NB == 2;
+  pl->pair = may_pair && !sum_block && pl->NB == 2;
   if (pl->pair && d->kv_chunk_tokens != 0 && d->kv_chunk_tokens % (kTile * kPairs) != 0) pl->pair = false;
   // A draft call over a short selection (may_finish): one workgroup per (sequence, KV head) streams all of it and
   // writes the output rows itself, so no merge kernel is launched.  Measured at 4K context, five draft calls per
@@ -230,9 +231,11 @@ int plan_verify(const vegas_desc* d, SplitPlan* pl) {
     return VEGAS_ERR_SHAPE;
   const int R = d->num_queries * g;
   const int collect = d->collect_rows == 0 ? 0 : (d->score_metric == VEGAS_METRIC_TOKEN_LOGITS ? 2 : 1);
-  // the logit metric needs two spare rows in the last 32-row block of a KV head
-  if (collect == 2 && (R % 32 == 0 || R % 32 > 30)) return VEGAS_ERR_UNSUPPORTED;
-  return plan_split(d, R, d->max_seq_len, collect, 1, pl, d->window == 0);
+  // The logit metric's two query-sum rows ride in spare rows of the last 32-row block of a KV head; where that block
+  // has fewer than two (R = 31, 32, 63, 64, ... rows) they get a sibling row block of their own, which streams K
+  // alongside the others (same XCD, served by its L2) and writes no output rows.
+  const bool sum_block = collect == 2 && (R % 32 == 0 || R % 32 == 31);
+  return plan_split(d, R, d->max_seq_len, collect, 1, pl, d->window == 0, false, sum_block);
 }
 
 int plan_draft(const vegas_desc* d, SplitPlan* pl) {

@@ -75,6 +75,15 @@ CASES = [
     ("group8_long_chunk_rings", 2, 64, 8, 5, [9000, 4100], 4096),
     ("single_row", 1, 32, 8, 1, [777], 0),
     ("mha_like", 1, 8, 8, 3, [900], 0),
+    # row counts whose last 32-row block has no two spare rows: the query-sum rows get a row block of their own
+    ("rows32_gamma7_group4", 1, 32, 8, 8, [3000], 0),              # gamma = 7 with a 4-head group (Table 1's gamma)
+    ("rows32_ragged_batch", 3, 32, 8, 8, [700, 2049, 5], 256),
+    ("rows64_gamma15_group4", 2, 32, 8, 16, [1500, 640], 0),
+    ("rows31", 1, 31, 1, 1, [900], 0),
+    ("rows63", 2, 63, 1, 1, [1300, 77], 128),
+    ("rows64_group8", 1, 64, 8, 8, [2100], 512),
+    ("rows96_group8", 1, 64, 8, 12, [1100], 0),
+    ("rows128", 1, 64, 4, 8, [1000], 0),
 ]
 
 
@@ -100,15 +109,26 @@ def test_token_logit_scores_ctx32k_full():
     assert set(map(int, L.hitters[0])).issubset(set(map(int, top)))
 
 
-def test_rows_without_spare_columns_are_refused():
-    """32 rows per KV head leave no room for the two query-sum rows: the descriptor is rejected, nothing runs."""
-    desc = vb.make_desc(batch=1, num_q_heads=32, num_kv_heads=8, num_queries=8, max_blocks=64, max_sel_blocks=64,
-                        max_seq_len=1024, num_pages=64, softmax_scale=0.1, score_metric=vb.METRIC_TOKEN_LOGITS)
-    dev = torch.device("cuda:0")
-    z = torch.zeros(1 << 19, dtype=torch.int32, device=dev)
-    with pytest.raises(vb.VegasError) as e:
-        vb.vegas_verify_attention(desc, z, z, z, z, z, z, z.view(torch.float32), z)
-    assert e.value.status == vb.VEGAS_ERR_UNSUPPORTED
+def test_chain_with_32_rows_per_kv_head():
+    """gamma = 7 with a 4-head GQA group (32 rows per KV head), the whole token-granular chain: logit scores,
+    token selection from them, drafting over the selected one-token pages."""
+    L = synth.make_random_case(seed=7032, batch=2, num_q_heads=32, num_kv_heads=8, num_queries=8, seq_lens=[2500, 900],
+                               logit_std=2.0, value_std=1.0, outliers=3, outlier_logit=30.0)
+    G, budget = 8, 256
+    dl = harness.DeviceLayer.upload(L)
+    path = harness.VegasPath.for_layer(L, budget_tokens=budget, token_granular=True, collect_rows=vb.COLLECT_FIRST_LAST)
+    path.iteration(dl)
+    torch.cuda.synchronize()
+    ref, got = check_token_scores("rows32.chain", L, path, vb.COLLECT_FIRST_LAST)
+    sel, ssl = path.sel_table.cpu().numpy(), path.sel_seq_lens.cpu().numpy()
+    ref_sel, ref_ssl, _ = O.select_tokens(path.block_scores.cpu().numpy(), L.block_table, L.seq_lens, G, budget,
+                                          path.max_sel_blocks)
+    assert np.array_equal(sel, ref_sel) and np.array_equal(ssl, ref_ssl)
+    kc = L.k_cache.reshape(-1, 1, 8, 128)
+    vc = L.v_cache.reshape(-1, 1, 8, 128)
+    for s in range(G):
+        ref_d = O.draft_attention(L.q_draft[s], kc, vc, sel, ssl, L.softmax_scale)
+        U.check_out(f"rows32.chain.draft{s}", path.out_draft[s], ref_d, U.vmax_visible(L))
 
 
 # ----------------------------------------------------------------------------------------------
