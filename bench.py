@@ -80,6 +80,131 @@ def cpu_baseline(L, budget: int, workload: str, target_seconds: float = 12.0):
                       f"{L.spec.num_queries} draft steps), float64 NumPy oracle, mean"}
 
 
+def oracle_iteration_us(L, budget: int, threads: int = 0) -> dict:
+    """One whole iteration of the oracle on the host (as it stands), timed once; threads > 0 limits the BLAS pool."""
+    from oracle import vegas_oracle as O
+    max_sel = (budget + 15) // 16 + 2
+
+    def one():
+        t0 = time.perf_counter()
+        O.decoding_iteration(L.q_verify, L.q_draft, L.k_cache, L.v_cache, L.block_table, L.seq_lens,
+                             L.softmax_scale, budget, max_sel)
+        return (time.perf_counter() - t0) * 1e6
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        if threads > 0:
+            with threadpool_limits(limits=threads):
+                return {"us": one(), "threads": threads}
+        used = max([int(p.get("num_threads", 1)) for p in threadpool_info()] or [1])
+        return {"us": one(), "threads": used}
+    except ImportError:
+        return {"us": one(), "threads": os.cpu_count() or 1}
+
+
+def compact_workload(name: str, args, torch, vb, harness, synth, with_oracle: bool) -> dict:
+    """One workload through the same protocol as the headline one (cold rotating caches, whole iterations, then the
+    two KV-streaming kernels alone), as one compact record for the `workloads` array."""
+    spec = all_workloads(synth)[name]
+    L = synth.make_layer(spec, 0)
+    dev = torch.device("cuda:0")
+    base = harness.DeviceLayer.upload(L, dev)
+    copies = device_copies(harness, base, copies_for(base, args.copies))
+    path = harness.VegasPath.for_layer(L)
+    G = spec.num_queries
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
+    n_tokens = int(L.seq_lens.sum())
+    bpt = 2 * spec.num_kv_heads * spec.head_dim * 2
+    big = n_tokens * bpt > 1e9
+    K, W = (20, 3) if big else (100, 10)
+
+    def timed(fn, reps, warm):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = vb.HipEvent(), vb.HipEvent()
+        e0.record(stream)
+        for i in range(reps):
+            fn(i)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_ms(e1) / reps * 1e3
+    for i in range(W):
+        path.iteration(copies[i % len(copies)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        path.iteration(copies[i % len(copies)])
+    torch.cuda.synchronize()
+    it_us = (time.perf_counter() - t0) / K * 1e6
+    v_us = timed(lambda i: path.verify(copies[i % len(copies)], stages=vb.STAGE_STREAM), K, 3)
+    d_us = timed(lambda i: path.draft(copies[i % len(copies)], i % G, stages=vb.STAGE_STREAM), K, 3)
+    verify_bytes = n_tokens * bpt
+    draft_bytes = int(path.sel_seq_lens.sum().item()) * bpt
+    rec = {"workload": name, "batch": spec.batch, "context_tokens_total": n_tokens, "draft_steps": G,
+           "kv_budget_tokens": spec.budget_tokens, "steps": K, "us_per_iteration": it_us,
+           "iteration_gbps": (verify_bytes + G * draft_bytes) / (it_us * 1e-6) / 1e9,
+           "verify_kernel_us": v_us, "verify_frac_of_peak": verify_bytes / (v_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+           "draft_kernel_us": d_us, "draft_frac_of_peak": draft_bytes / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    if spec.layers > 1:
+        rec["note"] = f"one of {spec.layers} independent layers (layer 0); --all-layers times the whole stack"
+    del copies, base, path
+    torch.cuda.empty_cache()
+    if with_oracle:
+        o = oracle_iteration_us(L, spec.budget_tokens)
+        rec["cpu_oracle_us"], rec["cpu_oracle_threads"] = o["us"], o["threads"]
+        if spec.config_id in (1, 2):
+            rec["cpu_oracle_us_single_thread"] = oracle_iteration_us(L, spec.budget_tokens, threads=1)["us"]
+    return rec
+
+
+def all_layers(args, torch, vb, harness, synth) -> int:
+    """The multi-layer workload as its definition reads: every layer's K/V resident at once (32 x 1.07 GB), one
+    iteration = layers x (verify + select + G draft calls), each layer on its own cache.  Prints one JSON line."""
+    spec = all_workloads(synth)[args.workload]
+    dev = torch.device("cuda:0")
+    layers = []
+    t0 = time.perf_counter()
+    for l in range(spec.layers):
+        L = synth.make_layer(spec, l)
+        layers.append(harness.DeviceLayer.upload(L, dev))
+        if l == 0:
+            path = harness.VegasPath.for_layer(L)
+            n_tokens = int(L.seq_lens.sum())
+        print(f"layer {l} resident ({time.perf_counter() - t0:.0f} s)", file=sys.stderr, flush=True)
+        del L
+    G = spec.num_queries
+    K, W = args.steps, args.warmup
+
+    def iteration():
+        for dl in layers:
+            path.iteration(dl)
+    for _ in range(W):
+        iteration()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        iteration()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / K * 1e6
+    bpt = 2 * spec.num_kv_heads * spec.head_dim * 2
+    resident = sum(2 * dl.k_cache.numel() * dl.k_cache.element_size() for dl in layers)
+    it_bytes = spec.layers * (n_tokens + G * int(path.sel_seq_lens.sum().item())) * bpt
+    print(json.dumps({
+        "metric": "us_per_verify_select_draft_iteration", "value": us, "unit": "us", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": us / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": spec.layers, "all_layers_resident": True, "batch": spec.batch,
+                   "context": spec.seq_len, "num_q_heads": spec.num_q_heads, "num_kv_heads": spec.num_kv_heads,
+                   "head_dim": spec.head_dim, "page_size": 16, "gamma": spec.gamma,
+                   "kv_budget_tokens": spec.budget_tokens, "draft_steps": G,
+                   "step": f"{spec.layers} x (verify + select + {G} draft calls), one layer after the other"},
+        "kv_bytes_resident": resident, "iteration_kv_bytes": it_bytes,
+        "iteration_gbps": it_bytes / (us * 1e-6) / 1e9,
+        "iteration_frac_of_hbm_peak": it_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        "us_per_layer": us / spec.layers}), flush=True)
+    return 0
+
+
 def device_copies(harness, base, want: int):
     """`want` device layers that share queries and tables with `base` but own their K/V caches."""
     copies = [base]
@@ -249,6 +374,11 @@ def main() -> int:
                     help="a live drafting phase: before each draft call the drafted token's K/V is appended to the cache "
                          "(vegas_append_kv) and the selection grows by it (vegas_extend_selection); the step then is "
                          "verify + select + G x (append + extend + draft) + one small copy that rewinds the lengths")
+    ap.add_argument("--all-layers", action="store_true",
+                    help="a multi-layer workload (stack32) as its definition reads: all layers resident, one step = "
+                         "layers x (verify + select + G draft calls); takes a few minutes of host time to generate")
+    ap.add_argument("--no-all-workloads", action="store_true",
+                    help="skip the compact records of the other workloads that the default run appends")
     ap.add_argument("--sweep", choices=["collect", "page_size"], default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -271,6 +401,11 @@ def main() -> int:
         return sweep_collect(args, torch, vb, harness, synth)
     if args.sweep == "page_size":
         return sweep_page_size(args, torch, vb)
+
+    if args.all_layers:
+        if args.steps == 200:
+            args.steps, args.warmup = 5, 1
+        return all_layers(args, torch, vb, harness, synth)
 
     workload = args.workload
     spec = all_workloads(synth)[workload]
@@ -460,9 +595,25 @@ def main() -> int:
                          "launch_floor_us_graph_replay": floor_graph_us,
                          "launch_floor_us_eager_through_binding": floor_eager_us}
 
-    if (not args.no_cpu_baseline and workload == DEFAULT_WORKLOAD and args.layer == 0 and not token and not args.budget
-            and not args.live):
+    default_run = (workload == DEFAULT_WORKLOAD and args.layer == 0 and not token and not args.budget and not args.live
+                   and args.verify_chunk == 0 and args.draft_chunk == 0)
+    if not args.no_cpu_baseline and default_run:
         out["cpu_baseline"] = cpu_baseline(L, spec.budget_tokens, workload)
+        out["cpu_baseline"]["us_single_thread"] = oracle_iteration_us(L, spec.budget_tokens, threads=1)["us"]
+    if default_run and not args.no_all_workloads:
+        # The other baseline configurations (and the two extra shapes) through the same door, one compact record each;
+        # a failure there is reported in its record and never costs the headline line.
+        del copies, base, path
+        torch.cuda.empty_cache()
+        out["workloads"] = []
+        for name in all_workloads(synth):
+            if name == workload:
+                continue
+            try:
+                out["workloads"].append(compact_workload(name, args, torch, vb, harness, synth,
+                                                         with_oracle=not args.no_cpu_baseline and name in synth.CONFIGS))
+            except Exception as exc:                     # noqa: BLE001 (reported, not hidden)
+                out["workloads"].append({"workload": name, "error": f"{type(exc).__name__}: {exc}"})
     print(json.dumps(out), flush=True)
     return 0
 

@@ -57,9 +57,20 @@ def check_scores(name, got: torch.Tensor, ref: np.ndarray):
     return float((np.abs(g - ref) / np.maximum(np.abs(ref), 1e-30)).max())
 
 
+def inputs_sha256(L) -> str:
+    """SHA-256 over a layer's generated inputs (queries, caches, table, lengths, in that order): what the five
+    baseline configurations log, so that two runs can be seen to have judged the same bytes."""
+    import hashlib
+    h = hashlib.sha256()
+    for a in (L.q_verify, L.q_draft, L.k_cache, L.v_cache, L.block_table, L.seq_lens):
+        h.update(memoryview(np.ascontiguousarray(a)).cast("B"))
+    return h.hexdigest()
+
+
 def check_selection(name, sel_gpu: np.ndarray, ssl_gpu: np.ndarray, L, ref_scores: np.ndarray,
                     ref_logical, G: int, budget: int):
-    """GPU selection (from GPU scores) vs oracle selection (from oracle scores)."""
+    """GPU selection (from GPU scores) vs oracle selection (from oracle scores).  Returns the number of sequences
+    whose selected set is exactly the oracle's (the others differ only inside the tie band)."""
     exact = 0
     for b in range(L.block_table.shape[0]):
         n = int(L.seq_lens[b])

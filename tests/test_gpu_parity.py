@@ -13,10 +13,15 @@ pytestmark = pytest.mark.gpu
 PAGE = 16
 
 
-def run_chain(L, budget, collect=vb.COLLECT_ALL_ROWS, verify_chunk=0, draft_chunk=0, name="case", vscale=None):
-    """verify -> select -> G draft steps on the GPU, each stage compared with the oracle."""
+def run_chain(L, budget, collect=vb.COLLECT_ALL_ROWS, verify_chunk=0, draft_chunk=0, name="case", vscale=None,
+              log_inputs=False):
+    """verify -> select -> G draft steps on the GPU, each stage compared with the oracle.
+    log_inputs (the baseline configurations): prints the SHA-256 of the generated inputs and how many sequences'
+    selections are exactly the oracle's set."""
     print(f"[case] {name} B={L.spec.batch} Hq={L.spec.num_q_heads} G={L.spec.num_queries} "
           f"lens={list(map(int, L.seq_lens[:8]))} budget={budget} collect={collect}", flush=True)
+    if log_inputs:
+        print(f"[inputs] {name} seed={L.seed} sha256={U.inputs_sha256(L)}", flush=True)
     dl = harness.DeviceLayer.upload(L)
     path = harness.VegasPath.for_layer(L, budget_tokens=budget, collect_rows=collect,
                                        verify_chunk=verify_chunk, draft_chunk=draft_chunk)
@@ -36,7 +41,10 @@ def run_chain(L, budget, collect=vb.COLLECT_ALL_ROWS, verify_chunk=0, draft_chun
     sel = path.sel_table.cpu().numpy()
     ssl = path.sel_seq_lens.cpu().numpy()
     _, ref_ssl, ref_logical = O.select_blocks(ref_scores, L.block_table, L.seq_lens, G, budget, path.max_sel_blocks)
-    U.check_selection(name + ".select", sel, ssl, L, ref_scores, ref_logical, G, budget)
+    exact = U.check_selection(name + ".select", sel, ssl, L, ref_scores, ref_logical, G, budget)
+    if log_inputs:
+        print(f"[selection] {name}: exact-set match {exact} of {L.spec.batch} sequences "
+              f"(the rest differ only inside the {U.TIE_BAND:g} tie band)", flush=True)
     # select on identical fp32 scores must agree bit for bit
     s32 = ref_scores.astype(np.float32)
     path.select(dl, block_scores=torch.from_numpy(s32).to(path.device))
@@ -201,12 +209,12 @@ def test_collect_none_leaves_scores_untouched_and_out_correct():
 
 def test_baseline_config1_full():
     L = synth.make_layer(synth.CONFIGS["ctx4k"])
-    run_chain(L, L.spec.budget_tokens, name="ctx4k")
+    run_chain(L, L.spec.budget_tokens, name="ctx4k", log_inputs=True)
 
 
 def test_baseline_config2_full():
     L = synth.make_layer(synth.CONFIGS["ctx32k"])
-    path, _, ref_scores = run_chain(L, L.spec.budget_tokens, name="ctx32k")
+    path, _, ref_scores = run_chain(L, L.spec.budget_tokens, name="ctx32k", log_inputs=True)
     sel = path.sel_table.cpu().numpy()[0]
     inv = {int(p): j for j, p in enumerate(L.block_table[0])}
     ids = {inv[int(p)] for p in sel if p >= 0}
@@ -217,7 +225,7 @@ def test_baseline_config2_full():
 def test_baseline_config3_full():
     """128K context, gamma = 6, heavy hitters drifting between verify and draft queries."""
     L = synth.make_layer(synth.CONFIGS["ctx128k_drift"])
-    path, _, _ = run_chain(L, L.spec.budget_tokens, name="ctx128k_drift")
+    path, _, _ = run_chain(L, L.spec.budget_tokens, name="ctx128k_drift", log_inputs=True)
     sel = path.sel_table.cpu().numpy()[0]
     inv = {int(p): j for j, p in enumerate(L.block_table[0])}
     ids = {inv[int(p)] for p in sel if p >= 0}
@@ -230,7 +238,7 @@ def test_baseline_config4_full():
     NaN poison in spare pages and in the slack of partial last pages."""
     L = synth.make_layer(synth.CONFIGS["ragged16"])
     assert len(set(int(x) % PAGE for x in L.seq_lens)) > 1            # partial last pages occur
-    run_chain(L, L.spec.budget_tokens, name="ragged16")
+    run_chain(L, L.spec.budget_tokens, name="ragged16", log_inputs=True)
 
 
 def test_ragged_batch_one_row_block_full():
@@ -245,7 +253,7 @@ def test_baseline_config5_every_layer(layer):
     """The 32-layer stack is 32 independent single-layer calls (own seed each); every layer is checked in full,
     one at a time (generate, upload, run, oracle, compare, drop)."""
     L = synth.make_layer(synth.CONFIGS["stack32"], layer=layer)
-    run_chain(L, L.spec.budget_tokens, name=f"stack32.layer{layer}")
+    run_chain(L, L.spec.budget_tokens, name=f"stack32.layer{layer}", log_inputs=True)
 
 
 def test_long_chunk_reloads_the_page_id_batch():
