@@ -102,7 +102,12 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   const int c1 = min(c0 + chunk_tokens, n);
   const int nblk = (n + kPage - 1) / kPage;
   const int tile_end = (c1 + kTile - 1) / kTile;
-  const int T = (tile_end - tile0 + NP - 1) / NP;      // steps of every pair (>= 1)
+  // Steps of every pair, rounded up to an even number: the streaming loop below works on two register sets in turn,
+  // and one loop shape (pairs of steps, the last pair without loads) keeps the kernel inside its register budget.  A
+  // chunk that is a multiple of four tiles has an even count by itself; otherwise (the ragged end of a sequence, a
+  // caller's chunk length) the extra step sees a tile past the chunk's end, which is masked out like any other token
+  // the rows may not see.
+  const int T = ((tile_end - tile0 + NP - 1) / NP + 1) & ~1;
 
   // ---- per-lane constants
   const int64_t head_off = static_cast<int64_t>(h) * p.head_stride;
@@ -141,7 +146,8 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   load_queries_to_lds<D>(qlds, p, b, h, 64, 0, p.R, COLLECT == 2, tid, NW * 64);
   const int xr = p.R - row0;                 // COLLECT 2: column of the high-part sum row inside block 1
   const bool has_extra = COLLECT == 2 && role == 1;
-  const int limit = n - p.G + ((l32 < Rl) ? (row0 + l32) / p.g : 0);   // last visible token of this lane's row
+  // last visible token of this lane's row: the causal bound, and nothing past this workgroup's chunk
+  const int limit = min(n - p.G + ((l32 < Rl) ? (row0 + l32) / p.g : 0), c1 - 1);
   // (the first barrier of the first step also publishes the queries)
 
   // ---- collection: the element of a step's collected values this thread stores (elements repeat when there are
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
       }
     }
 
-    const bool tail = (tok0 + kTile > n) || (tok0 + kTile - 1 > n - p.G);
+    const bool tail = (tok0 + kTile > c1) || (tok0 + kTile - 1 > n - p.G);
     if (tail) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -276,7 +282,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
     // What the step collected leaves now (nobody writes the LDS values again before the next step's first barrier,
     // which no wave passes before every wave has read its element here).
     if constexpr (COLLECT == 1) {
-      const bool ok = c0 / kPage + 4 * k + col_page < nblk;
+      const bool ok = c0 / kPage + 4 * k + col_page < min(nblk, (c1 + kPage - 1) / kPage);
       float* dst = ok ? col_dst + static_cast<int64_t>(k) * (4 * p.Rc) : p.trash;
       *dst = lse_lds[col_elem];
     }
@@ -287,27 +293,17 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
     }
   };
 
-  // ---- stream the chunk: T steps, slots alternate; the last two steps issue no loads
+  // ---- stream the chunk: T steps (even), the two register sets in turn; the last two steps issue no loads
   {
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     int k = 0;
-    while (k + 3 < T) {
+    for (; k + 2 < T; k += 2) {
       step(k, kr0, vr0, yes{});
       step(k + 1, kr1, vr1, yes{});
-      k += 2;
     }
-    const int left = T - k;                  // 1, 2 or 3
-    if (left == 3) {
-      step(k, kr0, vr0, yes{});
-      step(k + 1, kr1, vr1, no{});
-      step(k + 2, kr0, vr0, no{});
-    } else if (left == 2) {
-      step(k, kr0, vr0, no{});
-      step(k + 1, kr1, vr1, no{});
-    } else {
-      step(k, kr0, vr0, no{});               // (tile 1 was requested and is dropped)
-    }
+    step(k, kr0, vr0, no{});
+    step(k + 1, kr1, vr1, no{});
   }
 
   // ---- merge the two pairs, one row block after the other (the merge buffer aliases the tiles and the parked

@@ -434,7 +434,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     }
 
     const bool tail = (tok0 + kTile > n) || (CAUSAL && (tok0 + kTile - 1 > n - p.G)) ||
-                      (LOCAL && tok0 < n - p.window);               // tiles the largest lower bound cuts into
+                      (LOCAL && (tok0 < n - p.window || tok0 + kTile > c1));   // tiles the largest lower bound cuts into
     bf16x8 pb[NB][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -442,7 +442,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int tok = tok0 + 8 * (i >> 2) + 4 * half + (i & 3);
-          if (tok > limit[nb] || (LOCAL && tok <= limit[nb] - p.window)) st[nb][i] = -INFINITY;
+          // (the local variant may step on a tile past its chunk, see below: nothing there is visible)
+          if (tok > limit[nb] || (LOCAL && (tok <= limit[nb] - p.window || tok >= c1))) st[nb][i] = -INFINITY;
         }
       }
       float tmax = st[nb][0];
@@ -527,16 +528,31 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
         issue_v(k, va);
       }
     }
-    while (k + 2 < ntiles) {
-      step(k, va, vb, yes{});
-      step(k + 1, vb, va, yes{});
-      k += 2;
-    }
-    if (k + 1 < ntiles) {
-      step(k, va, vb, yes{});
-      step(k + 1, vb, va, no{});
-    } else if (!LOCAL || k < ntiles) {       // (local masking may leave this wave without a tile)
-      step(k, va, vb, no{});
+    if constexpr (LOCAL) {
+      // (Local masking may leave this wave without a tile.)  This variant always steps two tiles at a time, the last
+      // one possibly past the chunk's end, where every token is masked out: one loop shape less keeps it inside its
+      // register budget.
+      if (k < ntiles) {
+        const int stop = k + ((ntiles - k + 1) & ~1);
+        for (; k + 2 < stop; k += 2) {
+          step(k, va, vb, yes{});
+          step(k + 1, vb, va, yes{});
+        }
+        step(k, va, vb, yes{});
+        step(k + 1, vb, va, no{});
+      }
+    } else {
+      while (k + 2 < ntiles) {
+        step(k, va, vb, yes{});
+        step(k + 1, vb, va, yes{});
+        k += 2;
+      }
+      if (k + 1 < ntiles) {
+        step(k, va, vb, yes{});
+        step(k + 1, vb, va, no{});
+      } else {
+        step(k, va, vb, no{});
+      }
     }
   }
 
