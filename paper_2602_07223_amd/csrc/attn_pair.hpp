@@ -152,15 +152,22 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
 
   // ---- collection: the element of a step's collected values this thread stores (elements repeat when there are
   //      fewer than threads: the same value goes to the same address twice), and where step 0's copy goes
+  // (Threads beyond the step's element count have nothing to store: their store goes to the workgroup's scratch word
+  //  too.  Repeating elements instead -- the same value to the same address from a second thread -- costs real write
+  //  requests: a step's values then leave in 256 stores instead of 160, or of 64.)
   int col_elem = 0, col_page = 0;
-  float* col_dst = p.trash;
+  float* const trash = p.trash + (blockIdx.x & 63);        // one of 64 words: workgroups do not all share one
+  float* col_dst = trash;
+  bool col_active = false;
   if constexpr (COLLECT == 1) {
+    col_active = tid < 4 * p.Rc;
     const int e = tid % (4 * p.Rc);            // [page of the step][collected row]
     col_page = e / p.Rc;
     col_elem = col_page * p.R + collected_row(e % p.Rc, p.collect_rows, p.G, p.g);   // where it sits in LDS
     col_dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0 / kPage) * p.Rc + e;
   }
   if constexpr (COLLECT == 2) {
+    col_active = tid < kTile * NP;
     col_elem = tid % (kTile * NP);             // token of the step
     col_dst = p.page_lse + (static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + c0 + col_elem;
   }
@@ -282,13 +289,13 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
     // What the step collected leaves now (nobody writes the LDS values again before the next step's first barrier,
     // which no wave passes before every wave has read its element here).
     if constexpr (COLLECT == 1) {
-      const bool ok = c0 / kPage + 4 * k + col_page < min(nblk, (c1 + kPage - 1) / kPage);
-      float* dst = ok ? col_dst + static_cast<int64_t>(k) * (4 * p.Rc) : p.trash;
+      const bool ok = col_active && c0 / kPage + 4 * k + col_page < min(nblk, (c1 + kPage - 1) / kPage);
+      float* dst = ok ? col_dst + static_cast<int64_t>(k) * (4 * p.Rc) : trash;
       *dst = lse_lds[col_elem];
     }
     if constexpr (COLLECT == 2) {
-      const bool ok = c0 + (kTile * NP) * k + col_elem < c1;
-      float* dst = ok ? col_dst + k * (kTile * NP) : p.trash;
+      const bool ok = col_active && c0 + (kTile * NP) * k + col_elem < c1;
+      float* dst = ok ? col_dst + k * (kTile * NP) : trash;
       *dst = tok_lds[col_elem] + tok_lds[kTile * NP + col_elem];
     }
   };
