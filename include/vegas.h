@@ -285,6 +285,31 @@ int vegas_debug_draft_attention_stages(const vegas_desc* desc, const void* q, co
                                        int32_t stages);
 
 /*
+ * Debugging aid for the data-dependent errors that the calls do not report: in normal operation a page id outside
+ * the pool or a length outside its bounds is clamped on the device (no fault, unspecified results).  This call
+ * checks the same inputs and ORs what it finds into a device word, which the caller clears beforehand and reads
+ * back whenever it likes (the library never synchronises):
+ *   VEGAS_CHECK_LENGTH_RANGE            a length is negative or above desc->max_seq_len
+ *   VEGAS_CHECK_LENGTH_EXCEEDS_TABLE    a length needs more pages than a row of the table holds
+ *   VEGAS_CHECK_PAGE_ID                 a page id that the length makes the calls read is outside [0, num_pages)
+ *   VEGAS_CHECK_SHORTER_THAN_QUERIES    (block tables) 0 < length < num_queries: defined behaviour -- rows with no
+ *                                       visible key give 0 -- but hardly what a caller meant
+ * `which` says what `table` and `lens` are: VEGAS_TABLE_BLOCKS = block_table / seq_lens of verification and
+ * selection (row stride max_blocks, 16-token pages), VEGAS_TABLE_SELECTION = sel_table / sel_seq_lens of a draft
+ * call (row stride max_sel_blocks, pages of desc->page_size tokens, num_pages counted in such pages).
+ * One small kernel, one workgroup per sequence.
+ */
+enum { VEGAS_TABLE_BLOCKS = 0, VEGAS_TABLE_SELECTION = 1 };
+enum {
+  VEGAS_CHECK_LENGTH_RANGE = 1,
+  VEGAS_CHECK_LENGTH_EXCEEDS_TABLE = 2,
+  VEGAS_CHECK_PAGE_ID = 4,
+  VEGAS_CHECK_SHORTER_THAN_QUERIES = 8
+};
+int vegas_debug_check_tables(const vegas_desc* desc, int32_t which, const int32_t* table, const int32_t* lens,
+                             int32_t* error_word, void* hip_stream);
+
+/*
  * Measurement yardstick, not part of the method: one kernel that does nothing but read two device buffers of
  * bytes_each bytes (a multiple of 16; 16-byte aligned) front to back, coalesced, with `workgroups` workgroups of
  * 256 threads, each on a contiguous slice; non_temporal != 0 marks the loads as read-once, as the verification

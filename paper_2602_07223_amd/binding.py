@@ -28,6 +28,13 @@ COLLECT_FIRST_LAST = 2
 METRIC_PAGE_WEIGHTS = 0
 METRIC_TOKEN_LOGITS = 1
 
+TABLE_BLOCKS = 0
+TABLE_SELECTION = 1
+CHECK_LENGTH_RANGE = 1
+CHECK_LENGTH_EXCEEDS_TABLE = 2
+CHECK_PAGE_ID = 4
+CHECK_SHORTER_THAN_QUERIES = 8
+
 STAGE_STREAM = 1
 STAGE_MERGE = 2
 
@@ -35,7 +42,7 @@ EXPORTS = ("vegas_init", "vegas_workspace_bytes", "vegas_verify_attention", "veg
            "vegas_select_tokens", "vegas_append_kv", "vegas_extend_selection", "vegas_draft_attention",
            "vegas_draft_attention_static", "vegas_static_scratch_bytes",
            "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_debug_stream_read",
-           "vegas_strerror")
+           "vegas_debug_check_tables", "vegas_strerror")
 
 
 class VegasDesc(ctypes.Structure):
@@ -111,6 +118,8 @@ def load_library(path: Optional[str] = None):
     lib.vegas_debug_draft_attention_stages.argtypes = [D, P, P, P, P, P, P, P, ctypes.c_size_t, P, ctypes.c_int32]
     lib.vegas_debug_stream_read.restype = ctypes.c_int
     lib.vegas_debug_stream_read.argtypes = [P, P, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, P, P]
+    lib.vegas_debug_check_tables.restype = ctypes.c_int
+    lib.vegas_debug_check_tables.argtypes = [D, ctypes.c_int32, P, P, P, P]
     lib.vegas_strerror.restype = ctypes.c_char_p
     lib.vegas_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -317,6 +326,18 @@ def vegas_draft_attention_static(desc: VegasDesc, q, k_cache, v_cache, sel_table
                                                      _ptr(sel_table), _ptr(sel_seq_lens), _ptr(out), _stream(stream))
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_draft_attention_static")
+
+
+def vegas_debug_check_tables(desc: VegasDesc, which: int, table, lens, error_word, stream=None) -> None:
+    """ORs VEGAS_CHECK_* bits for out-of-range lengths and page ids into the device word (see include/vegas.h)."""
+    if not isinstance(table, int):
+        stride = desc.max_blocks if which == TABLE_BLOCKS else desc.max_sel_blocks
+        _check_extents("vegas_debug_check_tables", table=(table, desc.batch * stride * 4), lens=(lens, desc.batch * 4),
+                       error_word=(error_word, 4))
+    rc = load_library().vegas_debug_check_tables(ctypes.byref(desc), int(which), _ptr(table), _ptr(lens),
+                                                 _ptr(error_word), _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_debug_check_tables")
 
 
 def vegas_debug_stream_read(a, b, bytes_each: int, workgroups: int, non_temporal: bool, sink, stream=None) -> None:

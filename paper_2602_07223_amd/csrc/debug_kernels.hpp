@@ -43,4 +43,34 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const StreamReadParams
   p.sink[blockIdx.x * 256 + threadIdx.x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
 }
 
+// Validation of the data-dependent inputs the calls otherwise clamp silently: lengths and page ids.
+struct CheckParams {
+  const int32_t* table;     // [B, stride] page ids
+  const int32_t* lens;      // [B]
+  int32_t* error_word;      // bits are OR-ed in, never cleared
+  int32_t batch, stride, page_size, max_tokens, num_queries;
+  int64_t num_pages;
+};
+constexpr int kCheckLengthRange = 1, kCheckLengthExceedsTable = 2, kCheckPageId = 4, kCheckShorterThanQueries = 8;
+
+// One workgroup per sequence: its length against the descriptor's bounds, and every page id the length makes the
+// calls read against the pool.
+__global__ __launch_bounds__(256) void check_tables_kernel(const CheckParams p) {
+  const int b = blockIdx.x;
+  const int n = p.lens[b];
+  int bits = 0;
+  if (n < 0 || n > p.max_tokens) bits |= kCheckLengthRange;
+  const int64_t cap = static_cast<int64_t>(p.stride) * p.page_size;
+  if (n > cap) bits |= kCheckLengthExceedsTable;
+  if (p.num_queries > 0 && n > 0 && n < p.num_queries) bits |= kCheckShorterThanQueries;
+  const int64_t nn = n < 0 ? 0 : (n > cap ? cap : n);
+  const int pages = static_cast<int>((nn + p.page_size - 1) / p.page_size);
+  const int32_t* row = p.table + static_cast<int64_t>(b) * p.stride;
+  for (int j = threadIdx.x; j < pages; j += 256) {
+    const int64_t id = row[j];
+    if (id < 0 || id >= p.num_pages) bits |= kCheckPageId;
+  }
+  if (bits) atomicOr(p.error_word, bits);
+}
+
 }  // namespace vegas

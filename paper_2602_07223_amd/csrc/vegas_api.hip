@@ -825,6 +825,33 @@ int vegas_debug_stream_read(const void* a, const void* b, size_t bytes_each, int
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
+int vegas_debug_check_tables(const vegas_desc* desc, int32_t which, const int32_t* table, const int32_t* lens,
+                             int32_t* error_word, void* hip_stream) {
+  const int rc = check_common(desc);
+  if (rc != VEGAS_OK) return rc;
+  if (!table || !lens || !error_word) return VEGAS_ERR_NULL;
+  if (which != VEGAS_TABLE_BLOCKS && which != VEGAS_TABLE_SELECTION) return VEGAS_ERR_SHAPE;
+  CheckParams cp;
+  cp.table = table;
+  cp.lens = lens;
+  cp.error_word = error_word;
+  cp.batch = desc->batch;
+  cp.max_tokens = desc->max_seq_len;
+  cp.num_pages = desc->num_pages;
+  if (which == VEGAS_TABLE_BLOCKS) {
+    cp.stride = desc->max_blocks;
+    cp.page_size = kPage;
+    cp.num_queries = desc->num_queries;
+  } else {
+    if (desc->max_sel_blocks <= 0) return VEGAS_ERR_SHAPE;
+    cp.stride = desc->max_sel_blocks;
+    cp.page_size = desc->page_size;
+    cp.num_queries = 0;
+  }
+  hipLaunchKernelGGL(check_tables_kernel, dim3(desc->batch), dim3(256), 0, static_cast<hipStream_t>(hip_stream), cp);
+  return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
 const char* vegas_strerror(int status) {
   switch (status) {
     case VEGAS_OK: return "ok";
