@@ -205,6 +205,69 @@ def all_layers(args, torch, vb, harness, synth) -> int:
     return 0
 
 
+TIMELINE_EVENTS = ["wave entry", "length known", "first tile's loads issued", "queries in LDS (first barrier passed)",
+                   "first tile done", "last tile done", "merge barrier passed", "partial stored (exit)"]
+
+
+def timeline_table(buf, label: str) -> dict:
+    """Per-phase summary of one launch's stamps ([records][8] uint64 at 100 MHz; records never written stay zero):
+    event times relative to the first wave's entry, and per-wave phase durations, in microseconds."""
+    import numpy as np
+    rec = buf.cpu().numpy().view(np.uint64).reshape(-1, 8)
+    rec = rec[rec[:, 0] > 0].astype(np.float64)
+    if rec.shape[0] == 0:
+        return {"kernel": label, "waves": 0}
+    t0 = rec[:, 0].min()
+    rel = (rec - t0) / 100.0
+
+    def summary(col):
+        c = np.sort(col)
+        return {"min": float(c[0]), "p50": float(c[len(c) // 2]), "p90": float(c[int(0.9 * (len(c) - 1))]), "max": float(c[-1])}
+    events = {name: summary(rel[:, i]) for i, name in enumerate(TIMELINE_EVENTS)}
+    phases = {f"{TIMELINE_EVENTS[i]} -> {TIMELINE_EVENTS[i + 1]}": summary(rel[:, i + 1] - rel[:, i]) for i in range(7)}
+    return {"kernel": label, "waves": int(rec.shape[0]), "unit": "us",
+            "events_after_first_entry": events, "phase_durations_per_wave": phases}
+
+
+def run_timeline(args, torch, vb, harness, synth) -> int:
+    """Per-wave phase timeline of the two KV-streaming kernels on the workload (profiling build of the library)."""
+    spec = all_workloads(synth)[args.workload]
+    L = synth.make_layer(spec, args.layer)
+    dev = torch.device("cuda:0")
+    base = harness.DeviceLayer.upload(L, dev)
+    copies = device_copies(harness, base, copies_for(base, args.copies))
+    path = harness.VegasPath.for_layer(L, verify_chunk=args.verify_chunk, draft_chunk=args.draft_chunk)
+    G = spec.num_queries
+    buf = torch.zeros(4 << 20, dtype=torch.int64, device=dev)              # 32 MiB: 65536 workgroups of 4 waves
+    out = {"timeline": True, "workload": args.workload, "clock": "100 MHz wall clock (10 ns steps)", "kernels": []}
+    for i in range(6):                                                     # cold caches as in the timed runs
+        path.iteration(copies[i % len(copies)])
+    torch.cuda.synchronize()
+    vb.vegas_debug_set_timeline(buf)
+    path.verify(copies[6 % len(copies)], stages=vb.STAGE_STREAM)
+    torch.cuda.synchronize()
+    vb.vegas_debug_set_timeline(None)
+    out["kernels"].append(timeline_table(buf, "KV-streaming kernel of vegas_verify_attention"))
+    path.iteration(copies[7 % len(copies)])                                # the selection a draft call walks
+    path.draft(copies[7 % len(copies)], 0)
+    torch.cuda.synchronize()
+    buf.zero_()
+    torch.cuda.synchronize()
+    vb.vegas_debug_set_timeline(buf)
+    path.draft(copies[7 % len(copies)], 1 % G, stages=vb.STAGE_STREAM)     # a second draft step, as in an iteration
+    torch.cuda.synchronize()
+    vb.vegas_debug_set_timeline(None)
+    out["kernels"].append(timeline_table(buf, "KV-streaming kernel of vegas_draft_attention (second draft step)"))
+    for k in out["kernels"]:
+        print(f"== {k['kernel']}: {k['waves']} waves", file=sys.stderr)
+        for name, v in k.get("events_after_first_entry", {}).items():
+            print(f"   at   {name:40s} min {v['min']:6.2f}  p50 {v['p50']:6.2f}  p90 {v['p90']:6.2f}  max {v['max']:6.2f}", file=sys.stderr)
+        for name, v in k.get("phase_durations_per_wave", {}).items():
+            print(f"   took {name:80s} p50 {v['p50']:6.2f}  p90 {v['p90']:6.2f}  max {v['max']:6.2f}", file=sys.stderr)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def device_copies(harness, base, want: int):
     """`want` device layers that share queries and tables with `base` but own their K/V caches."""
     copies = [base]
@@ -379,6 +442,9 @@ def main() -> int:
                          "layers x (verify + select + G draft calls); takes a few minutes of host time to generate")
     ap.add_argument("--no-all-workloads", action="store_true",
                     help="skip the compact records of the other workloads that the default run appends")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-wave phase timeline of the two KV-streaming kernels; needs the profiling build "
+                         "(python -m paper_2602_07223_amd.build --timeline), which this option loads")
     ap.add_argument("--sweep", choices=["collect", "page_size"], default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -393,10 +459,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.timeline:
+        from paper_2602_07223_amd import build as vbuild
+        vb.load_library(vbuild.TIMELINE_LIB_PATH)       # the profiling build; raises if it has not been built
     vb.load_library()                                   # fail loudly if the HIP library is not built
     if args.workload not in all_workloads(synth):
         print(f"bench.py: unknown workload {args.workload!r}; one of {sorted(all_workloads(synth))}", file=sys.stderr)
         return 2
+    if args.timeline:
+        return run_timeline(args, torch, vb, harness, synth)
     if args.sweep == "collect":
         return sweep_collect(args, torch, vb, harness, synth)
     if args.sweep == "page_size":

@@ -310,6 +310,17 @@ int vegas_debug_check_tables(const vegas_desc* desc, int32_t which, const int32_
                              int32_t* error_word, void* hip_stream);
 
 /*
+ * Profiling builds only (the library compiled with -DVEGAS_TIMELINE; an ordinary build returns
+ * VEGAS_ERR_UNSUPPORTED and its kernels carry no such code).  Registers a device buffer into which every wave of
+ * the KV-streaming kernels launched from now on stores eight 64-bit wall-clock stamps (100 MHz) when it exits:
+ * [workgroup (x + grid_x * y)][wave][event], events in program order: wave entry, length known, first tile's loads
+ * issued, queries in LDS, first tile done, last tile done, merge barrier passed, partial stored.  A launch that
+ * needs more than `bytes` writes nothing; NULL switches the stamps off.  Process-wide, not thread-safe: a tool for
+ * one profiling run (bench.py --timeline prints the per-phase table from it).
+ */
+int vegas_debug_set_timeline(void* buffer, size_t bytes);
+
+/*
  * Measurement yardstick, not part of the method: one kernel that does nothing but read two device buffers of
  * bytes_each bytes (a multiple of 16; 16-byte aligned) front to back, coalesced, with `workgroups` workgroups of
  * 256 threads, each on a contiguous slice; non_temporal != 0 marks the loads as read-once, as the verification

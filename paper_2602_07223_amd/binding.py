@@ -42,7 +42,7 @@ EXPORTS = ("vegas_init", "vegas_workspace_bytes", "vegas_verify_attention", "veg
            "vegas_select_tokens", "vegas_append_kv", "vegas_extend_selection", "vegas_draft_attention",
            "vegas_draft_attention_static", "vegas_static_scratch_bytes",
            "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_debug_stream_read",
-           "vegas_debug_check_tables", "vegas_strerror")
+           "vegas_debug_check_tables", "vegas_debug_set_timeline", "vegas_strerror")
 
 
 class VegasDesc(ctypes.Structure):
@@ -120,6 +120,8 @@ def load_library(path: Optional[str] = None):
     lib.vegas_debug_stream_read.argtypes = [P, P, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, P, P]
     lib.vegas_debug_check_tables.restype = ctypes.c_int
     lib.vegas_debug_check_tables.argtypes = [D, ctypes.c_int32, P, P, P, P]
+    lib.vegas_debug_set_timeline.restype = ctypes.c_int
+    lib.vegas_debug_set_timeline.argtypes = [P, ctypes.c_size_t]
     lib.vegas_strerror.restype = ctypes.c_char_p
     lib.vegas_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -338,6 +340,14 @@ def vegas_debug_check_tables(desc: VegasDesc, which: int, table, lens, error_wor
                                                  _ptr(error_word), _stream(stream))
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_debug_check_tables")
+
+
+def vegas_debug_set_timeline(buffer, nbytes: Optional[int] = None) -> None:
+    """Profiling builds only: register (or, with None, drop) the buffer for the streaming kernels' phase stamps."""
+    nb = 0 if buffer is None else (nbytes if nbytes is not None else _nbytes(buffer))
+    rc = load_library().vegas_debug_set_timeline(_ptr(buffer), nb)
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_debug_set_timeline")
 
 
 def vegas_debug_stream_read(a, b, bytes_each: int, workgroups: int, non_temporal: bool, sink, stream=None) -> None:

@@ -27,9 +27,17 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
-    """Compile every HIP source into paper_2602_07223_amd/libvegas.so; returns its path."""
-    cmd = [hipcc_path(), *FLAGS, *extra_flags, "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
+TIMELINE_LIB_PATH = os.path.join(HERE, "libvegas_timeline.so")
+
+
+def build_library(verbose: bool = True, extra_flags=(), timeline: bool = False) -> str:
+    """Compile every HIP source into paper_2602_07223_amd/libvegas.so; returns its path.
+    timeline=True builds the profiling variant instead (libvegas_timeline.so: the same code with -DVEGAS_TIMELINE,
+    whose streaming kernels note per-wave phase times; bench.py --timeline loads it)."""
+    out = TIMELINE_LIB_PATH if timeline else LIB_PATH
+    if timeline:
+        extra_flags = (*extra_flags, "-DVEGAS_TIMELINE")
+    cmd = [hipcc_path(), *FLAGS, *extra_flags, "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -39,7 +47,7 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB_PATH
+    return out
 
 
 def kernel_resource_usage() -> dict:
@@ -78,4 +86,4 @@ def kernel_resource_usage() -> dict:
 
 
 if __name__ == "__main__":
-    print(build_library())
+    print(build_library(timeline="--timeline" in sys.argv[1:]))

@@ -170,11 +170,12 @@ template <int NW, int WPS, bool CAUSAL, int COLLECT, bool NT_LOADS, int PS = 4, 
 __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HOT_PARAMS, const SplitParams pfull) {
   // What the first memory requests need arrives in scalar registers with the wave (kernel-argument preloading)
   // instead of through a load of the argument block: one dependent round trip less at the head of the kernel.
+  VEGAS_TL_DECL;
+  VEGAS_TL(kTlEntry);
   SplitParams p = pfull;
   VEGAS_SPLIT_HOT_ASSIGN(p);
   static_assert(PS == 4 || (!CAUSAL && COLLECT == 0 && !NT_LOADS), "small pages: draft calls only");
   static_assert(!LOCAL || (CAUSAL && COLLECT == 0), "local masking: verification without collection only");
-  // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   static_assert(D == 128 || D == 64, "head dimension");
   constexpr int NB = 1;                      // one 32-row block per workgroup
@@ -186,14 +187,6 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   constexpr int kRedPitch = red_pitch(D);
   using VReg = typename std::conditional<D == 128, u32x2, uint32_t>::type;   // NBLK head dims of one token
   constexpr int TP = 32 >> (PS < 4 ? PS : 0);   // pages per tile on the small-page path
-  unsigned char* qlds = smem + p.lds_q_off;
-  float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
-  float* sm_l = sm_m + NW * NB * 32;
-  // [pages of the chunk][Rl] page log-sum-exp (COLLECT only): behind the K tiles; the merge buffer may
-  // overlap it because it is flushed (and a barrier passed) before the merge starts.
-  float* lse_lds = reinterpret_cast<float*>(smem + NW * 32 * kRowPitch);
-  float* tok_lds = lse_lds;                  // COLLECT == 2: [2][chunk tokens] high-part and low-part token sums
-
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -204,7 +197,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   int split = blockIdx.x / (p.Hkv * p.row_blocks);
   int b = blockIdx.y;
   int chunk_tokens = p.chunk_tokens;
-  int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot
+  bool planned = false;                      // balanced chunking: the partial slot is the plan's
   if constexpr (CAUSAL && PS == 4 && !LOCAL) {
     if (p.plan) {                            // balanced chunking: slot j of this head -> (sequence, chunk)
       const int j = split;
@@ -215,11 +208,11 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
       b = bs.b;
       split = bs.split;
       chunk_tokens = bs.chunk;
-      pbase = static_cast<int64_t>(h) * p.slots_total + j;
+      planned = true;
     }
   }
+  const int slot_j = blockIdx.x / (p.Hkv * p.row_blocks);
   const int row0 = rb * 32;                  // first query row (of this KV head) handled here
-  int* ids_lds = reinterpret_cast<int*>(sm_l + NW * NB * 32) + wave * 64;   // [2 tiles][32 page ids] of this wave
   const int Rl = max(min(32, p.R - row0), 0);   // valid rows in this block (none in a block that only carries the sum rows)
 
   // Physical page ids of the wave's next 32 tiles live in one register: lane (k, half) holds the id of
@@ -228,33 +221,64 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   // known (one memory round trip less at the head of the kernel): indices are clamped to the table
   // row, entries past the sequence's pages are read but never used.
   const int32_t* table = p.table + static_cast<int64_t>(b) * p.table_stride;
+  const int c0 = split * chunk_tokens;
+  const int tile_first = c0 / kTile + wave;
+  int pagevec = 0;
+  auto table_entry = [&](int kbase) -> int {           // (raw: clamped into the pool by the caller)
+    int page = 2 * (tile_first + (kbase + l32) * NW) + half;
+    page = page < p.table_stride ? page : p.table_stride - 1;
+    return table[page];
+  };
+  auto into_pool = [&](int raw) -> int {
+    const int64_t ph = raw;
+    return static_cast<int>(ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph));
+  };
+  auto load_pagevec = [&](int kbase) { pagevec = into_pool(table_entry(kbase)); };
+  // Small pages: ids of the TP pages of this wave's tile k, lane e (mod TP) -> page e of the tile.
+  auto ids_entry = [&](int k) -> int {
+    int page = (tile_first + k * NW) * TP + (lane & (TP - 1));
+    page = page < p.table_stride ? page : p.table_stride - 1;
+    return table[page];
+  };
+  auto load_ids = [&](int k) -> int { return into_pool(ids_entry(k)); };
+
+  // ---- The head of the kernel is a chain of memory round trips (arguments -> table and length -> K/V), each about
+  //      a microsecond after a kernel boundary, in a kernel that runs for a few; so everything that can be asked for
+  //      at once is.  (1) The first page-table request and the length need only the preloaded arguments: they leave
+  //      first.  (2) The rest of the argument block is pulled into registers in one go while those two are in flight
+  //      (left to itself the compiler fetches it piecemeal, each piece with a wait of its own, several of them between
+  //      the table's arrival and the first K/V request).  (3) The query loads follow.  (4) Only then is the table
+  //      entry waited for -- pinned here, or the compiler sinks the request below the length's early exit and turns
+  //      two parallel trips into two consecutive ones.
+  int first_entry = 0;
+  if constexpr (PS == 4) first_entry = table_entry(0);
+  else first_entry = ids_entry(0);
+  int n = p.lens[b];
   // Query loads leave now (they depend on the sequence and the head only).
   constexpr int QI = (32 * CH + NW * 64 - 1) / (NW * 64);
   u32x4 qraw[QI];
   if constexpr (COLLECT != 2) issue_query_loads<D, QI>(qraw, p, b, h, NB * 32, row0, Rl, tid, NW * 64);
-  const int c0 = split * chunk_tokens;
-  const int tile_first = c0 / kTile + wave;
-  int pagevec = 0;
-  auto load_pagevec = [&](int kbase) {
-    int page = 2 * (tile_first + (kbase + l32) * NW) + half;
-    page = page < p.table_stride ? page : p.table_stride - 1;
-    int64_t ph = table[page];
-    ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
-    pagevec = static_cast<int>(ph);
-  };
-  // Small pages: ids of the TP pages of this wave's tile k, lane e (mod TP) -> page e of the tile.
-  auto load_ids = [&](int k) -> int {
-    int page = (tile_first + k * NW) * TP + (lane & (TP - 1));
-    page = page < p.table_stride ? page : p.table_stride - 1;
-    int64_t ph = table[page];
-    ph = ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph);
-    return static_cast<int>(ph);
-  };
+  asm volatile("" : "+s"(p.k), "+s"(p.v), "+s"(p.page_stride), "+s"(p.token_stride), "+s"(p.head_stride),
+               "+s"(p.num_pages), "+s"(p.out_direct));
+  asm volatile("" : "+s"(p.max_tokens), "+s"(p.lds_q_off), "+s"(p.nsplit), "+s"(p.scale_log2e), "+s"(p.part_o),
+               "+s"(p.part_ml));
+  asm volatile("" : "+v"(first_entry));
+  // Dynamic LDS: [K staging, NW tiles + page lse | merge buffer NW x R rows][queries][row maxima][row sums][page-id ring]
+  unsigned char* qlds = smem + p.lds_q_off;
+  float* sm_m = reinterpret_cast<float*>(qlds + NB * 32 * kRowPitch);
+  float* sm_l = sm_m + NW * NB * 32;
+  // [pages of the chunk][Rl] page log-sum-exp (COLLECT only): behind the K tiles; the merge buffer may
+  // overlap it because it is flushed (and a barrier passed) before the merge starts.
+  float* lse_lds = reinterpret_cast<float*>(smem + NW * 32 * kRowPitch);
+  float* tok_lds = lse_lds;                  // COLLECT == 2: [2][chunk tokens] high-part and low-part token sums
+  int* ids_lds = reinterpret_cast<int*>(sm_l + NW * NB * 32) + wave * 64;   // [2 tiles][32 page ids] of this wave
+  // this workgroup's partial slot
+  const int64_t pbase = planned ? static_cast<int64_t>(h) * p.slots_total + slot_j
+                                : (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;
   int ids_pending = 0;
-  if constexpr (PS == 4) load_pagevec(0);
-  else ids_pending = load_ids(0);
+  if constexpr (PS == 4) pagevec = into_pool(first_entry);
+  else ids_pending = into_pool(first_entry);
 
-  int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   if (c0 >= n) {                             // whole workgroup: nothing to do, no partial is read
     if (p.out_direct != nullptr) {           // no merge kernel follows: the rows of an empty sequence are zeros
@@ -265,6 +289,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     }
     return;
   }
+  VEGAS_TL(kTlLength);
   const int c1 = min(c0 + chunk_tokens, n);
   // Local masking: no row sees a token before lo_min; chunks and tiles wholly before it are skipped.
   const int lo_min = LOCAL ? max(n - p.G - p.window + 1, 0) : 0;
@@ -353,6 +378,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     issue_k(0, kr);
     issue_v(0, va);
   }
+  VEGAS_TL(kTlLoadsIssued);
 
   // ---- query rows -> LDS [row][CH chunks of 16 B], padded rows; rows past R are zero
   // COLLECT == 2: the last row block carries the sum of the collected query rows in rows Rl (high part) and Rl + 1 (low part)
@@ -366,6 +392,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     limit[nb] = CAUSAL ? (n - p.G + t) : (n - 1);
   }
   __syncthreads();
+  VEGAS_TL(kTlQueries);
 
   // ---- running state: lane (row, half) keeps the row max m (same in both halves), its half's
   //      partial sum l, and O^T accumulators acc[nb][blk][i] = O[row][NBLK*(8(i/4) + 4half + i%4) + blk]
@@ -511,6 +538,9 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
           acc[nb][blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[nb][s2], acc[nb][blk], 0, 0, 0);
       }
     }
+#ifdef VEGAS_TIMELINE
+    if (tl_stamps[kTlFirstTile] == 0) VEGAS_TL(kTlFirstTile);
+#endif
   };
 
   // ---- stream the chunk's tiles
@@ -559,11 +589,13 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   // ---- merge the NW waves: exchange row maxima, rescale, park the valid rows of every wave's
   //      accumulators in LDS as [wave][row][d], then all threads add across waves and write the
   //      workgroup's partial result with consecutive threads on consecutive addresses.
+  VEGAS_TL(kTlStreamed);
   if (half == 0) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) sm_m[wave * (NB * 32) + nb * 32 + l32] = m_run[nb];
   }
   __syncthreads();                                       // also: every wave is done with its K tile
+  VEGAS_TL(kTlMerged);
   if constexpr (COLLECT == 2) {
     // The chunk's token sums (high + low part) leave in one coalesced write; positions at or past the
     // end of the sequence are never read.
@@ -579,7 +611,12 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     const int pg0 = c0 / kPage;
     const int npg = min(nblk, (c1 + kPage - 1) / kPage) - pg0;
     float* dst = p.page_lse + ((static_cast<int64_t>(b) * p.Hkv + h) * p.lse_pages + pg0) * p.Rc;
-    if (Rl == p.R && p.Rc == p.R) {
+    if (Rl == p.R && p.Rc == p.R && (Rl & 3) == 0) {         // 16 bytes per thread and trip (rows of 4 k floats stay aligned)
+      const f32x4* src4 = reinterpret_cast<const f32x4*>(lse_lds);
+      f32x4* dst4 = reinterpret_cast<f32x4*>(dst);
+#pragma unroll 2
+      for (int e = tid; e < npg * (Rl >> 2); e += NW * 64) dst4[e] = src4[e];
+    } else if (Rl == p.R && p.Rc == p.R) {
       for (int e = tid; e < npg * Rl; e += NW * 64) dst[e] = lse_lds[e];
     } else {                                 // only the collected rows, and of those the ones in this row block
       for (int e = tid; e < npg * p.Rc; e += NW * 64) {
@@ -615,30 +652,54 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     }
   }
   __syncthreads();
+  // The workgroup's rows: every thread adds the waves' copies of four neighbouring head dims (16-byte LDS reads, all
+  // of a thread's reads issued before the first is used) -- the tail of a kernel this short is worth its microsecond.
+  constexpr int V4 = D / 4;
+  constexpr int kSumTrips = (32 * V4 + NW * 64 - 1) / (NW * 64);
+  f32x4 sums[kSumTrips];
+  const int sum_trips = (Rl * V4 + NW * 64 - 1) / (NW * 64);       // (few rows: the later trips have nothing to do)
+#pragma unroll
+  for (int it = 0; it < kSumTrips; ++it) {
+    if (it < sum_trips) {
+      const int e = min(tid + it * NW * 64, Rl * V4 - 1);
+      const float* src = red + (e / V4) * kRedPitch + 4 * (e % V4);
+      f32x4 acc4 = *reinterpret_cast<const f32x4*>(src);
+#pragma unroll
+      for (int w = 1; w < NW; ++w) acc4 += *reinterpret_cast<const f32x4*>(src + w * Rl * kRedPitch);
+      sums[it] = acc4;
+    }
+  }
   if (p.out_direct != nullptr) {
     // The only chunk of its (sequence, KV head): the workgroup's sums are the whole result, so it divides by the
     // softmax denominator and writes the bf16 rows itself (Eq. 1); no partials, no merge kernel.
-    for (int e = tid; e < Rl * D; e += NW * 64) {
-      const int row = e / D, d = e % D;
-      float sum = 0.f, lw = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        sum += red[(w * Rl + row) * kRedPitch + d];
-        lw += sm_l[w * (NB * 32) + row];
+    for (int it = 0; it < kSumTrips; ++it) {
+      const int e = tid + it * NW * 64;
+      if (e < Rl * V4) {
+        const int row = e / V4, d = 4 * (e % V4);
+        float lw = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) lw += sm_l[w * (NB * 32) + row];
+        const int r = row0 + row;
+        const float inv = lw > 0.f ? 1.0f / lw : 0.f;       // (a row with no visible key: zeros)
+        u32x2 packed;
+        packed[0] = static_cast<uint32_t>(float_to_bf16_bits(sums[it][0] * inv)) |
+                    (static_cast<uint32_t>(float_to_bf16_bits(sums[it][1] * inv)) << 16);
+        packed[1] = static_cast<uint32_t>(float_to_bf16_bits(sums[it][2] * inv)) |
+                    (static_cast<uint32_t>(float_to_bf16_bits(sums[it][3] * inv)) << 16);
+        *reinterpret_cast<u32x2*>(
+            p.out_direct + ((static_cast<int64_t>(b) * p.G + r / p.g) * p.Hq + h * p.g + r % p.g) * D + d) = packed;
       }
-      const int r = row0 + row;
-      p.out_direct[((static_cast<int64_t>(b) * p.G + r / p.g) * p.Hq + h * p.g + r % p.g) * D + d] =
-          float_to_bf16_bits(lw > 0.f ? sum / lw : 0.f);
     }
+    VEGAS_TL(kTlExit);
+    VEGAS_TL_FLUSH(p.timeline, NW);
     return;
   }
   float* po = p.part_o + (pbase * p.R + row0) * D;
-  for (int e = tid; e < Rl * D; e += NW * 64) {
-    const int row = e / D, d = e % D;
-    float sum = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) sum += red[(w * Rl + row) * kRedPitch + d];
-    po[e] = sum;
+  for (int it = 0; it < kSumTrips; ++it) {
+    const int e = tid + it * NW * 64;
+    if (e < Rl * V4) *reinterpret_cast<f32x4*>(po + 4 * e) = sums[it];
   }
   if (tid < Rl) {
     float mw = -INFINITY, lw = 0.f;
@@ -649,6 +710,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
     }
     p.part_ml[pbase * p.R + row0 + tid] = make_float2(mw, lw);
   }
+  VEGAS_TL(kTlExit);
+  VEGAS_TL_FLUSH(p.timeline, NW);
 }
 
 // Dynamic LDS bytes of attn_split_kernel<NW, ...> when a workgroup holds up to `rows` (<= 32) valid rows.

@@ -265,9 +265,16 @@ int ensure_dynamic_lds(const void* kern, size_t lds) {
   return VEGAS_OK;
 }
 
+// Profiling builds (-DVEGAS_TIMELINE): the buffer that vegas_debug_set_timeline registered receives the phase stamps of
+// the next streaming kernels (if it is large enough for the launch); ordinary builds have no such buffer.
+unsigned long long* g_timeline = nullptr;
+size_t g_timeline_bytes = 0;
+
 template <typename Kern>
-int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, const SplitParams& sp) {
+int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, SplitParams sp) {
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds)) return rc;
+  const size_t tl_need = static_cast<size_t>(grid.x) * grid.y * (block.x / 64) * kTimelineEvents * sizeof(unsigned long long);
+  sp.timeline = (g_timeline != nullptr && tl_need <= g_timeline_bytes) ? g_timeline : nullptr;
   hipLaunchKernelGGL(kern, grid, block, lds, st, VEGAS_SPLIT_HOT_ARGS(sp), sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
@@ -357,6 +364,7 @@ void fill_split_params(const vegas_desc* d, const SplitPlan& pl, int G, const vo
   sp->head_stride = d->kv_head_stride;
   sp->num_pages = d->num_pages;
   sp->scale_log2e = d->softmax_scale * 1.4426950408889634f;
+  sp->timeline = nullptr;
 }
 
 // Scratch of vegas_select_tokens: digit histograms [B, 4 passes, slices, 256].
@@ -850,6 +858,18 @@ int vegas_debug_check_tables(const vegas_desc* desc, int32_t which, const int32_
   }
   hipLaunchKernelGGL(check_tables_kernel, dim3(desc->batch), dim3(256), 0, static_cast<hipStream_t>(hip_stream), cp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+int vegas_debug_set_timeline(void* buffer, size_t bytes) {
+#ifdef VEGAS_TIMELINE
+  g_timeline = static_cast<unsigned long long*>(buffer);
+  g_timeline_bytes = buffer ? bytes : 0;
+  return VEGAS_OK;
+#else
+  (void)buffer;
+  (void)bytes;
+  return VEGAS_ERR_UNSUPPORTED;
+#endif
 }
 
 const char* vegas_strerror(int status) {

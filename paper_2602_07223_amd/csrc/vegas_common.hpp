@@ -94,27 +94,71 @@ struct SplitParams {
   int32_t chunk_unit;       // chunk lengths are multiples of this many tokens
   int64_t page_stride, token_stride, head_stride, num_pages;
   float scale_log2e;
+  unsigned long long* timeline;   // profiling builds: where the waves' phase stamps go (nullptr: nowhere)
 };
 
+// ---- per-wave phase timeline (builds with -DVEGAS_TIMELINE only: a profiling build, never the product) ----
+// Every wave of a streaming kernel notes the wall clock (100 MHz, the same on all compute units) at a few fixed
+// program points and stores the notes when it exits: [workgroup][wave][kTimelineEvents] 64-bit stamps in a buffer
+// the caller registers with vegas_debug_set_timeline.  In ordinary builds the macros expand to nothing.
+constexpr int kTimelineEvents = 8;
+enum {
+  kTlEntry = 0,        // first instruction of the wave
+  kTlLength = 1,       // sequence length known (past the early exit)
+  kTlLoadsIssued = 2,  // the first tile's K/V requests are out
+  kTlQueries = 3,      // queries in LDS, workgroup past its first barrier
+  kTlFirstTile = 4,    // first tile's arithmetic done
+  kTlStreamed = 5,     // last tile's arithmetic done
+  kTlMerged = 6,       // row maxima exchanged: past the merge's first barrier
+  kTlExit = 7          // partial result stored
+};
+#ifdef VEGAS_TIMELINE
+#define VEGAS_TL_DECL unsigned long long tl_stamps[kTimelineEvents] = {0, 0, 0, 0, 0, 0, 0, 0}
+// (the empty asm statements keep the compiler from moving memory operations across a stamp)
+#define VEGAS_TL(ev)                                       \
+  do {                                                     \
+    asm volatile("" ::: "memory");                         \
+    tl_stamps[ev] = __builtin_amdgcn_s_memrealtime();      \
+    asm volatile("" ::: "memory");                         \
+  } while (0)
+#define VEGAS_TL_FLUSH(buf, waves)                                                                              \
+  do {                                                                                                          \
+    if ((buf) != nullptr && (threadIdx.x & 63) == 0) {                                                          \
+      const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;                                                 \
+      unsigned long long* tl_dst = (buf) + (static_cast<size_t>(lin) * (waves) + (threadIdx.x >> 6)) * kTimelineEvents; \
+      for (int tl_i = 0; tl_i < kTimelineEvents; ++tl_i) tl_dst[tl_i] = tl_stamps[tl_i];                        \
+    }                                                                                                           \
+  } while (0)
+#else
+#define VEGAS_TL_DECL
+#define VEGAS_TL(ev)
+#define VEGAS_TL_FLUSH(buf, waves)
+#endif
+
 // Leading kernel arguments of the streaming kernels: the fields of SplitParams that the first memory requests (page
-// ids, sequence length) depend on.  Leading scalar arguments are preloaded into scalar registers when a wave starts
+// ids, sequence length, query rows) depend on -- 14 dwords, all that can be preloaded.  Leading scalar arguments are preloaded into scalar registers when a wave starts
 // (the library is built with kernel-argument preloading); the copies inside SplitParams are then not read.
 #define VEGAS_SPLIT_HOT_PARAMS                                                                                     \
-  const int32_t *hot_table, const int32_t *hot_lens, int2 *hot_plan, int32_t hot_table_stride, int32_t hot_chunk_tokens, \
-      int32_t hot_Hkv, int32_t hot_row_blocks, int32_t hot_nsplit
+  const int32_t *hot_table, const int32_t *hot_lens, int2 *hot_plan, const uint16_t *hot_q, int32_t hot_table_stride, \
+      int32_t hot_chunk_tokens, int32_t hot_Hkv, int32_t hot_row_blocks, int32_t hot_G, int32_t hot_Hq
 #define VEGAS_SPLIT_HOT_ASSIGN(p)            \
   do {                                       \
     (p).table = hot_table;                   \
     (p).lens = hot_lens;                     \
     (p).plan = hot_plan;                     \
+    (p).q = hot_q;                           \
     (p).table_stride = hot_table_stride;     \
     (p).chunk_tokens = hot_chunk_tokens;     \
     (p).Hkv = hot_Hkv;                       \
     (p).row_blocks = hot_row_blocks;         \
-    (p).nsplit = hot_nsplit;                 \
+    (p).G = hot_G;                           \
+    (p).Hq = hot_Hq;                         \
+    (p).g = hot_Hq / hot_Hkv;                \
+    (p).R = hot_G * (p).g;                   \
   } while (0)
-#define VEGAS_SPLIT_HOT_ARGS(sp) \
-  (sp).table, (sp).lens, (sp).plan, (sp).table_stride, (sp).chunk_tokens, (sp).Hkv, (sp).row_blocks, (sp).nsplit
+#define VEGAS_SPLIT_HOT_ARGS(sp)                                                                                   \
+  (sp).table, (sp).lens, (sp).plan, (sp).q, (sp).table_stride, (sp).chunk_tokens, (sp).Hkv, (sp).row_blocks, (sp).G, \
+      (sp).Hq
 
 struct CombineParams {
   const float* part_o;
