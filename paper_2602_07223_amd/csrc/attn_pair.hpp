@@ -62,16 +62,16 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   const int pr = wave >> 1, role = wave & 1;
   const int half = lane >> 5;
   const int l32 = lane & 31;
-  const int h = blockIdx.x % p.Hkv;
-  int split = blockIdx.x / p.Hkv;
-  int b = blockIdx.y;
+  const int h = blockIdx.x;                  // grid (KV head, chunk, sequence): see attn_split_kernel
+  int split = blockIdx.y;
+  int b = blockIdx.z;
   int chunk_tokens = p.chunk_tokens;
   int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot
   if (p.plan) {                              // balanced chunking: slot j of this head -> (sequence, chunk)
     const int j = split;
     const BalancedSlot bs = balanced_slot(p.lens, p.batch, p.max_tokens, p.slots_target, p.slots_target2,
                                           p.chunk_cap_units, p.chunk_unit, j,
-                                          (blockIdx.x == 0 && wave == 0) ? p.plan : nullptr);
+                                          ((blockIdx.x | blockIdx.y) == 0 && wave == 0) ? p.plan : nullptr);
     if (bs.b < 0) return;
     b = bs.b;
     split = bs.split;
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   //  too.  Repeating elements instead -- the same value to the same address from a second thread -- costs real write
   //  requests: a step's values then leave in 256 stores instead of 160, or of 64.)
   int col_elem = 0, col_page = 0;
-  float* const trash = p.trash + (blockIdx.x & 63);        // one of 64 words: workgroups do not all share one
+  float* const trash = p.trash + ((blockIdx.x + 8 * blockIdx.y) & 63);        // one of 64 words: workgroups do not all share one
   float* col_dst = trash;
   bool col_active = false;
   if constexpr (COLLECT == 1) {
@@ -239,13 +239,14 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
 #pragma unroll
     for (int i = 0; i < 8; ++i) { ps0 += pw[i]; ps1 += pw[8 + i]; }
     l_run = l_run * alpha + (ps0 + ps1);
+    const float m_before = m_run;
     m_run = m_new;
     if (COLLECT == 1) {
       const float f0 = half_sum(ps0);
       const float f1 = half_sum(ps1);                    // page 2 pr + half of the step
       if (l32 < Rl) lse_lds[(2 * pr + half) * p.R + row0 + l32] = m_use + fast_log2(half ? f1 : f0);
     }
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f && m_before != -INFINITY) != 0) {   // (no key seen yet: sums still zero)
 #pragma unroll
       for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll

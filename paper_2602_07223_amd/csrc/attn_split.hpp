@@ -121,15 +121,21 @@ template <int D, int QI>
 __device__ __forceinline__ void issue_query_loads(u32x4 (&raw)[QI], const SplitParams& p, int b, int h, int rows, int row0,
                                                   int valid, int tid, int threads) {
   constexpr int CH = D / 8;
+  // Row r of the KV head is token t = r / g, head j = r % g of the group.  r < 128, so the quotient comes exactly
+  // from one reciprocal (a hardware integer division is two dozen instructions); the address is a wave-uniform
+  // 64-bit base (sequence, KV head) plus a 32-bit lane offset.
+  const float rcp_g = __builtin_amdgcn_rcpf(static_cast<float>(p.g));
+  const unsigned char* base = uniform_ptr(reinterpret_cast<const unsigned char*>(
+      p.q + (static_cast<int64_t>(b) * p.G * p.Hq + h * p.g) * D));
 #pragma unroll
   for (int i = 0; i < QI; ++i) {
     const int idx = tid + i * threads;
     const int row = idx / CH, chunk = idx % CH;
     raw[i] = u32x4{0u, 0u, 0u, 0u};
     if (idx < rows * CH && row < valid) {
-      const int t = (row0 + row) / p.g, j = (row0 + row) % p.g;
-      raw[i] = *reinterpret_cast<const u32x4*>(
-          p.q + ((static_cast<int64_t>(b) * p.G + t) * p.Hq + h * p.g + j) * D + chunk * 8);
+      const int r = row0 + row;
+      const int t = static_cast<int>((static_cast<float>(r) + 0.5f) * rcp_g), j = r - t * p.g;
+      raw[i] = gload<u32x4, false>(base, static_cast<uint32_t>((t * p.Hq + j) * D + chunk * 8) * 2u);
     }
   }
 }
@@ -192,10 +198,13 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int half = lane >> 5;
   const int l32 = lane & 31;
-  const int h = blockIdx.x % p.Hkv;
-  const int rb = (blockIdx.x / p.Hkv) % p.row_blocks;
-  int split = blockIdx.x / (p.Hkv * p.row_blocks);
-  int b = blockIdx.y;
+  // Grid (KV head, row block + row_blocks * chunk, sequence): the indices come without a division (a few dozen
+  // instructions each at the head of a kernel whose waves are issue-bound), and linear workgroup ids stay
+  // head-fastest, so the 8 KV heads of a chunk still land on the 8 XCDs and sibling row blocks share one.
+  const int h = blockIdx.x;
+  const int rb = p.row_blocks == 1 ? 0 : static_cast<int>(blockIdx.y) % p.row_blocks;
+  int split = p.row_blocks == 1 ? static_cast<int>(blockIdx.y) : static_cast<int>(blockIdx.y) / p.row_blocks;
+  int b = blockIdx.z;
   int chunk_tokens = p.chunk_tokens;
   bool planned = false;                      // balanced chunking: the partial slot is the plan's
   if constexpr (CAUSAL && PS == 4 && !LOCAL) {
@@ -203,7 +212,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
       const int j = split;
       const BalancedSlot bs = balanced_slot(p.lens, p.batch, p.max_tokens, p.slots_target, p.slots_target2,
                                             p.chunk_cap_units, p.chunk_unit, j,
-                                            (blockIdx.x == 0 && wave == 0) ? p.plan : nullptr);
+                                            ((blockIdx.x | blockIdx.y) == 0 && wave == 0) ? p.plan : nullptr);
       if (bs.b < 0) return;
       b = bs.b;
       split = bs.split;
@@ -211,7 +220,7 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
       planned = true;
     }
   }
-  const int slot_j = blockIdx.x / (p.Hkv * p.row_blocks);
+  const int slot_j = p.row_blocks == 1 ? static_cast<int>(blockIdx.y) : static_cast<int>(blockIdx.y) / p.row_blocks;
   const int row0 = rb * 32;                  // first query row (of this KV head) handled here
   const int Rl = max(min(32, p.R - row0), 0);   // valid rows in this block (none in a block that only carries the sum rows)
 
@@ -487,6 +496,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
 #pragma unroll
       for (int i = 0; i < 8; ++i) { ps0 += pr[i]; ps1 += pr[8 + i]; }
       l_run[nb] = l_run[nb] * alpha + (ps0 + ps1);
+      float m_run_before[NB];
+      m_run_before[nb] = m_run[nb];
       m_run[nb] = m_new;
       if (COLLECT == 1) {
         const float f0 = half_sum(ps0);
@@ -494,7 +505,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
         const int page = cur * 2 + half;                 // parked in LDS, written out in bulk at the end
         if (l32 < Rl && page < nblk) lse_lds[(page - c0 / kPage) * Rl + l32] = m_use + fast_log2(half ? f1 : f0);
       }
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+      // (nothing to rescale where the row had seen no key yet: its sums are still zero)
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f && m_run_before[nb] != -INFINITY) != 0) {
 #pragma unroll
         for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll

@@ -273,7 +273,7 @@ size_t g_timeline_bytes = 0;
 template <typename Kern>
 int launch_one(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, SplitParams sp) {
   if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds)) return rc;
-  const size_t tl_need = static_cast<size_t>(grid.x) * grid.y * (block.x / 64) * kTimelineEvents * sizeof(unsigned long long);
+  const size_t tl_need = static_cast<size_t>(grid.x) * grid.y * grid.z * (block.x / 64) * kTimelineEvents * sizeof(unsigned long long);
   sp.timeline = (g_timeline != nullptr && tl_need <= g_timeline_bytes) ? g_timeline : nullptr;
   hipLaunchKernelGGL(kern, grid, block, lds, st, VEGAS_SPLIT_HOT_ARGS(sp), sp);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
@@ -283,8 +283,8 @@ template <bool CAUSAL, int COLLECT, int D>
 int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size) {
   if constexpr (CAUSAL) {
     if (pl.pair) {                                  // both row blocks from one read of K/V
-      const dim3 pgrid = pl.balanced ? dim3(static_cast<unsigned>(sp.Hkv) * pl.JS, 1)
-                                     : dim3(static_cast<unsigned>(sp.Hkv) * pl.nsplit, batch);
+      const dim3 pgrid = pl.balanced ? dim3(sp.Hkv, pl.JS, 1) : dim3(sp.Hkv, pl.nsplit, batch);
+      if (pgrid.y > 65535u) return VEGAS_ERR_UNSUPPORTED;
       const size_t plds = pair_lds_bytes(pl.R, COLLECT, D);
       sp.lds_q_off = static_cast<int32_t>(plds - pair_lds_tail_bytes(D));
       sp.row_blocks = 1;
@@ -292,8 +292,10 @@ int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t s
       return launch_one(attn_pair_kernel<COLLECT, D>, pgrid, dim3(kPairWaves * 64), plds, st, sp);
     }
   }
-  const dim3 grid = pl.balanced ? dim3(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.JS, 1)
-                                : dim3(static_cast<unsigned>(sp.Hkv) * pl.NB * pl.nsplit, batch);
+  // (KV head, row block + NB * chunk, sequence): the kernels read their indices off the grid without a division
+  const dim3 grid = pl.balanced ? dim3(sp.Hkv, static_cast<unsigned>(pl.NB) * pl.JS, 1)
+                                : dim3(sp.Hkv, static_cast<unsigned>(pl.NB) * pl.nsplit, batch);
+  if (grid.y > 65535u) return VEGAS_ERR_UNSUPPORTED;        // more chunks per sequence than a grid dimension holds
   const int rows = pl.R < 32 ? pl.R : 32;
   const size_t lds = split_lds_bytes(pl.NW, rows, COLLECT, pl.chunk, D);
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW, D));

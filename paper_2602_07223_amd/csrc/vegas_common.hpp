@@ -124,7 +124,7 @@ enum {
 #define VEGAS_TL_FLUSH(buf, waves)                                                                              \
   do {                                                                                                          \
     if ((buf) != nullptr && (threadIdx.x & 63) == 0) {                                                          \
-      const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;                                                 \
+      const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);                      \
       unsigned long long* tl_dst = (buf) + (static_cast<size_t>(lin) * (waves) + (threadIdx.x >> 6)) * kTimelineEvents; \
       for (int tl_i = 0; tl_i < kTimelineEvents; ++tl_i) tl_dst[tl_i] = tl_stamps[tl_i];                        \
     }                                                                                                           \
