@@ -684,6 +684,8 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
   if (p.out_direct != nullptr) {
     // The only chunk of its (sequence, KV head): the workgroup's sums are the whole result, so it divides by the
     // softmax denominator and writes the bf16 rows itself (Eq. 1); no partials, no merge kernel.
+    const float rcp_g = __builtin_amdgcn_rcpf(static_cast<float>(p.g));     // (row / g without an integer division)
+    uint16_t* const out_base = p.out_direct + (static_cast<int64_t>(b) * p.G * p.Hq + h * p.g) * D;
 #pragma unroll
     for (int it = 0; it < kSumTrips; ++it) {
       const int e = tid + it * NW * 64;
@@ -693,14 +695,14 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
 #pragma unroll
         for (int w = 0; w < NW; ++w) lw += sm_l[w * (NB * 32) + row];
         const int r = row0 + row;
+        const int rt = static_cast<int>((static_cast<float>(r) + 0.5f) * rcp_g), rj = r - rt * p.g;
         const float inv = lw > 0.f ? 1.0f / lw : 0.f;       // (a row with no visible key: zeros)
         u32x2 packed;
         packed[0] = static_cast<uint32_t>(float_to_bf16_bits(sums[it][0] * inv)) |
                     (static_cast<uint32_t>(float_to_bf16_bits(sums[it][1] * inv)) << 16);
         packed[1] = static_cast<uint32_t>(float_to_bf16_bits(sums[it][2] * inv)) |
                     (static_cast<uint32_t>(float_to_bf16_bits(sums[it][3] * inv)) << 16);
-        *reinterpret_cast<u32x2*>(
-            p.out_direct + ((static_cast<int64_t>(b) * p.G + r / p.g) * p.Hq + h * p.g + r % p.g) * D + d) = packed;
+        *reinterpret_cast<u32x2*>(out_base + (rt * p.Hq + rj) * D + d) = packed;
       }
     }
     VEGAS_TL(kTlExit);
