@@ -11,6 +11,7 @@
 #include <utility>
 
 #include "attn_finalize.hpp"
+#include "attn_draft.hpp"
 #include "attn_pair.hpp"
 #include "attn_split.hpp"
 #include "debug_kernels.hpp"
@@ -301,8 +302,11 @@ int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t s
   sp.lds_q_off = static_cast<int32_t>(lds - split_lds_tail_bytes(pl.NW, D));
   sp.row_blocks = pl.NB;
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
-  if constexpr (!CAUSAL && COLLECT == 0) {              // draft calls may walk a table of smaller pages
-    switch (page_size) {
+  if constexpr (!CAUSAL && COLLECT == 0) {
+    // one draft token, a group of at most 16 heads, 16-token pages: the kernel written for exactly that
+    if (page_size == kPage && pl.R <= kDraftRows && sp.G == 1 && pl.NB == 1)
+      return launch_one(attn_draft16_kernel<D>, grid, dim3(kDraftWaves * 64), draft16_lds_bytes(pl.R, D), st, sp);
+    switch (page_size) {                                // draft calls may walk a table of smaller pages
       case 1: return launch_one(attn_split_kernel<4, 2, false, 0, false, 0, false, D>, grid, dim3(256), lds, st, sp);
       case 2: return launch_one(attn_split_kernel<4, 2, false, 0, false, 1, false, D>, grid, dim3(256), lds, st, sp);
       case 4: return launch_one(attn_split_kernel<4, 2, false, 0, false, 2, false, D>, grid, dim3(256), lds, st, sp);
@@ -471,6 +475,7 @@ int for_each_lds_kernel(F f) {
     one(attn_split_kernel<4, 2, true, 1, false, 4, false, D>);
     one(attn_split_kernel<4, 2, true, 2, true, 4, false, D>);
     one(attn_split_kernel<4, 2, true, 2, false, 4, false, D>);
+    one(attn_draft16_kernel<D>);
     one(attn_pair_kernel<0, D>);
     one(attn_pair_kernel<1, D>);
     one(attn_pair_kernel<2, D>);

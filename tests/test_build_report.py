@@ -19,8 +19,8 @@ def test_no_kernel_spills_registers(usage):
 
 
 def test_streaming_kernels_fit_two_waves_per_simd(usage):
-    streaming = {k: v for k, v in usage.items() if "attn_split_kernel" in k or "attn_pair_kernel" in k}
-    assert len(streaming) >= 30                      # every instantiation the launch code can pick is in the report
+    streaming = {k: v for k, v in usage.items() if "attn_split_kernel" in k or "attn_pair_kernel" in k or "attn_draft16_kernel" in k}
+    assert len(streaming) >= 32                      # every instantiation the launch code can pick is in the report
     for name, v in streaming.items():
         assert v["vgprs"] + v.get("agprs", 0) <= 256, (name, v)
         assert v["occupancy"] >= 2, (name, v)
