@@ -21,6 +21,12 @@ Beyond the default run:
                        CPU baseline and the counter-derived traffic belong to the default workload only
   --extras             adds per-iteration percentiles, the warm-cache figure (one cache copy) and the
                        iteration replayed from captured HIP graphs to the same JSON line
+  --live               the drafting phase as it runs live: every draft step first appends the drafted token's K/V rows
+                       (vegas_append_kv) and grows the selection by them (vegas_extend_selection)
+  --all-layers         a multi-layer workload (stack32) with every layer's cache resident: a step is one pass over all
+                       layers
+  --timeline           per-wave phase times of the two KV-streaming kernels (profiling build of the library)
+  --no-all-workloads   the default run appends one compact record per other workload (`workloads`); this skips them
   --sweep page_size    draft attention latency versus the page size (1..16 tokens) of the selection table in the
                        set-up of App. D / Table 5 (batch 16, 8192 selected tokens per request, random positions)
   --sweep collect      the collection-overhead curve (Sec. 3.3, Fig. 6 analogue): the verification call
@@ -546,7 +552,8 @@ def main() -> int:
         roofline["achieved"] = verify_bytes / (v_us * 1e-6) / 1e9
         roofline["frac"] = roofline["achieved"] / HBM_PEAK_GBS
         d_us = kernel_leg(lambda i: path.draft(copies[i % len(copies)], i % G, stages=vb.STAGE_STREAM), K)
-        roofline_draft = {"bound": "hbm", "kernel": "attn_split_kernel (KV-streaming kernel of vegas_draft_attention)",
+        dkernel = "attn_draft16_kernel" if spec.num_q_heads // spec.num_kv_heads <= 16 and not token else "attn_split_kernel"
+        roofline_draft = {"bound": "hbm", "kernel": dkernel + " (KV-streaming kernel of vegas_draft_attention)",
                           "kernel_us": d_us, "achieved": draft_bytes / (d_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                           "unit": "GB/s", "frac": draft_bytes / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                           "bytes_per_launch": draft_bytes, "traffic": None}
