@@ -231,6 +231,20 @@ int vegas_extend_selection(const vegas_desc* desc, const int32_t* block_table, c
                            int32_t num_new, int32_t* sel_table, int32_t* sel_seq_lens, void* hip_stream);
 
 /*
+ * vegas_append_kv followed by vegas_extend_selection in ONE launch (a draft step of a live drafting phase, Sec. 2.3
+ * with Sec. 3.2's last sentence, then costs one small kernel before its draft call instead of two).  Arguments as
+ * for vegas_append_kv (desc->page_size is 16: it describes the cache and block_table), plus
+ *   sel_table      int32 [B, max_sel_blocks]   the selection to grow, updated in place (desc->max_sel_blocks entries
+ *   sel_seq_lens   int32 [B]                   per row), under vegas_extend_selection's rules
+ *   sel_page_size  page size of sel_table: 16 or 1
+ * A sequence whose append is refused (no room) keeps its length AND its selection; otherwise the results are those
+ * of the two calls one after the other, bit for bit.  VEGAS_ERR_UNSUPPORTED for another sel_page_size.
+ */
+int vegas_append_kv_extend(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
+                           const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache,
+                           int32_t* sel_table, int32_t* sel_seq_lens, int32_t sel_page_size, void* hip_stream);
+
+/*
  * Sparse draft attention (Sec. 2.2 last paragraph; Sec. 4: the selection is the page list).
  *   q            bf16 [B, H_q, D]           one draft token per sequence
  *   sel_table    int32 [B, max_sel_blocks]  as written by vegas_select_blocks

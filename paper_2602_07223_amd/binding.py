@@ -39,7 +39,7 @@ STAGE_STREAM = 1
 STAGE_MERGE = 2
 
 EXPORTS = ("vegas_init", "vegas_workspace_bytes", "vegas_verify_attention", "vegas_select_blocks",
-           "vegas_select_tokens", "vegas_append_kv", "vegas_extend_selection", "vegas_draft_attention",
+           "vegas_select_tokens", "vegas_append_kv", "vegas_append_kv_extend", "vegas_extend_selection", "vegas_draft_attention",
            "vegas_draft_attention_static", "vegas_static_scratch_bytes",
            "vegas_debug_verify_attention_stages", "vegas_debug_draft_attention_stages", "vegas_debug_stream_read",
            "vegas_debug_check_tables", "vegas_debug_set_timeline", "vegas_strerror")
@@ -104,6 +104,8 @@ def load_library(path: Optional[str] = None):
     lib.vegas_select_tokens.argtypes = [D, P, P, P, ctypes.c_int32, P, P, P, P, ctypes.c_size_t, P]
     lib.vegas_append_kv.restype = ctypes.c_int
     lib.vegas_append_kv.argtypes = [D, P, P, ctypes.c_int32, P, P, P, P, P]
+    lib.vegas_append_kv_extend.restype = ctypes.c_int
+    lib.vegas_append_kv_extend.argtypes = [D, P, P, ctypes.c_int32, P, P, P, P, P, P, ctypes.c_int32, P]
     lib.vegas_extend_selection.restype = ctypes.c_int
     lib.vegas_extend_selection.argtypes = [D, P, P, ctypes.c_int32, P, P, P]
     lib.vegas_draft_attention.restype = ctypes.c_int
@@ -277,6 +279,22 @@ def vegas_append_kv(desc: VegasDesc, k_new, v_new, num_new: int, block_table, se
                                         _ptr(seq_lens), _ptr(k_cache), _ptr(v_cache), _stream(stream))
     if rc != VEGAS_OK:
         raise VegasError(rc, "vegas_append_kv")
+
+
+def vegas_append_kv_extend(desc: VegasDesc, k_new, v_new, num_new: int, block_table, seq_lens, k_cache, v_cache,
+                           sel_table, sel_seq_lens, sel_page_size: int, stream=None) -> None:
+    if not (isinstance(k_new, int) and isinstance(k_cache, int)):
+        d = desc
+        rows = d.batch * int(num_new) * d.num_kv_heads * d.head_dim * 2
+        _check_extents("vegas_append_kv_extend", k_new=(k_new, rows), v_new=(v_new, rows),
+                       k_cache=(k_cache, cache_extent_bytes(d)), v_cache=(v_cache, cache_extent_bytes(d)),
+                       block_table=(block_table, d.batch * d.max_blocks * 4), seq_lens=(seq_lens, d.batch * 4),
+                       sel_table=(sel_table, d.batch * d.max_sel_blocks * 4), sel_seq_lens=(sel_seq_lens, d.batch * 4))
+    rc = load_library().vegas_append_kv_extend(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), int(num_new),
+                                               _ptr(block_table), _ptr(seq_lens), _ptr(k_cache), _ptr(v_cache),
+                                               _ptr(sel_table), _ptr(sel_seq_lens), int(sel_page_size), _stream(stream))
+    if rc != VEGAS_OK:
+        raise VegasError(rc, "vegas_append_kv_extend")
 
 
 def vegas_extend_selection(desc: VegasDesc, block_table, seq_lens, num_new: int, sel_table, sel_seq_lens,

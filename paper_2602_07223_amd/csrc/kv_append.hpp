@@ -6,6 +6,7 @@
 // block_table[b][(n_b + t) / 16], slot (n_b + t) % 16, every KV head (App. D's [page, slot, KV head, dim] layout
 // with the descriptor's strides).  The lengths live on the device, so the kernel also advances them.
 #pragma once
+#include "select_blocks.hpp"
 #include "vegas_common.hpp"
 
 namespace vegas {
@@ -19,11 +20,15 @@ struct AppendParams {
   int32_t* seq_lens;            // [B], advanced by T
   int32_t T, Hkv, D, max_blocks, max_tokens;
   int64_t page_stride, token_stride, head_stride, num_pages;
+  ExtendParams grow;            // sel_table != nullptr: the selection grows by the same tokens in the same launch
 };
 
 // One workgroup per sequence.  A thread moves 16 bytes: (token, K or V, KV head, 16-byte piece of the head's row).
 // The length is read by every thread before anybody advances it (a barrier separates the two).  A sequence without
 // room for T more tokens (its table row, or the descriptor's bound) is left alone: nothing written, length kept.
+// With a selection to grow (vegas_append_kv_extend), the sequence's first thread then does what
+// extend_selection_kernel does for the advanced length -- one launch per draft step instead of two; a sequence
+// whose append was refused keeps its selection as it is.
 __global__ __launch_bounds__(256) void append_kv_kernel(const AppendParams p) {
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
@@ -47,7 +52,10 @@ __global__ __launch_bounds__(256) void append_kv_kernel(const AppendParams p) {
     const u32x4 v = *reinterpret_cast<const u32x4*>((which ? p.v_new : p.k_new) + src);
     *reinterpret_cast<u32x4*>((which ? p.v_cache : p.k_cache) + dst) = v;
   }
-  if (tid == 0) p.seq_lens[b] = n + p.T;
+  if (tid == 0) {
+    p.seq_lens[b] = n + p.T;
+    if (p.grow.sel_table != nullptr) extend_selection_row(p.grow, b, n + p.T);
+  }
 }
 
 }  // namespace vegas

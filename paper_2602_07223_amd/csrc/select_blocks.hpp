@@ -434,15 +434,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_blocks_kernel(const Sel
   if (tid == 0) p.sel_seq_lens[b] = kPage * (k - 1) + (n - kPage * (nblk - 1));
 }
 
-// Adds the num_new newest token positions of every sequence to its selection (one thread per sequence):
-// a new table entry whenever a position starts a page of the selection's page size.
-__global__ void extend_selection_kernel(const ExtendParams p) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= p.batch) return;
+// Adds the num_new newest token positions of sequence b, whose length now is n_new, to its selection: a new table
+// entry whenever a position starts a page of the selection's page size (one thread's work).
+__device__ __forceinline__ void extend_selection_row(const ExtendParams& p, int b, int n_new) {
   const int covered = p.sel_seq_lens[b];
   if (covered <= 0) return;
   const int P = p.page_size;
-  const int n_new = p.seq_lens[b];
   int32_t* sel = p.sel_table + static_cast<int64_t>(b) * p.max_sel_blocks;
   const int32_t* table = p.block_table + static_cast<int64_t>(b) * p.max_blocks;
   int count = (covered + P - 1) / P;
@@ -456,6 +453,13 @@ __global__ void extend_selection_kernel(const ExtendParams p) {
     }
   }
   p.sel_seq_lens[b] = covered + p.num_new;
+}
+
+// One thread per sequence.
+__global__ void extend_selection_kernel(const ExtendParams p) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= p.batch) return;
+  extend_selection_row(p, b, p.seq_lens[b]);
 }
 
 }  // namespace vegas

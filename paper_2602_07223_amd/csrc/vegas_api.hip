@@ -702,8 +702,9 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores, const
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
 }
 
-int vegas_append_kv(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
-                    const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache, void* hip_stream) {
+static int append_impl(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
+                       const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache, int32_t* sel_table,
+                       int32_t* sel_seq_lens, int32_t sel_page_size, void* hip_stream) {
   int rc = check_common(desc);
   if (rc == VEGAS_OK) rc = check_paged16(desc);
   if (rc != VEGAS_OK) return rc;
@@ -726,8 +727,33 @@ int vegas_append_kv(const vegas_desc* desc, const void* k_new, const void* v_new
   ap.token_stride = desc->kv_token_stride;
   ap.head_stride = desc->kv_head_stride;
   ap.num_pages = desc->num_pages;
+  ap.grow.block_table = block_table;
+  ap.grow.seq_lens = seq_lens;
+  ap.grow.sel_table = sel_table;
+  ap.grow.sel_seq_lens = sel_seq_lens;
+  ap.grow.batch = desc->batch;
+  ap.grow.num_new = num_new;
+  ap.grow.max_blocks = desc->max_blocks;
+  ap.grow.max_sel_blocks = desc->max_sel_blocks;
+  ap.grow.page_size = sel_page_size;
   hipLaunchKernelGGL(append_kv_kernel, dim3(desc->batch), dim3(256), 0, static_cast<hipStream_t>(hip_stream), ap);
   return hipGetLastError() == hipSuccess ? VEGAS_OK : VEGAS_ERR_LAUNCH;
+}
+
+int vegas_append_kv(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
+                    const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache, void* hip_stream) {
+  return append_impl(desc, k_new, v_new, num_new, block_table, seq_lens, k_cache, v_cache, nullptr, nullptr, kPage,
+                     hip_stream);
+}
+
+int vegas_append_kv_extend(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
+                           const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache,
+                           int32_t* sel_table, int32_t* sel_seq_lens, int32_t sel_page_size, void* hip_stream) {
+  if (!sel_table || !sel_seq_lens) return VEGAS_ERR_NULL;
+  if (sel_page_size != kPage && sel_page_size != 1) return VEGAS_ERR_UNSUPPORTED;
+  if (!desc || desc->max_sel_blocks <= 0) return desc ? VEGAS_ERR_SHAPE : VEGAS_ERR_NULL;
+  return append_impl(desc, k_new, v_new, num_new, block_table, seq_lens, k_cache, v_cache, sel_table, sel_seq_lens,
+                     sel_page_size, hip_stream);
 }
 
 int vegas_extend_selection(const vegas_desc* desc, const int32_t* block_table, const int32_t* seq_lens,

@@ -177,11 +177,12 @@ class VegasPath:
                                  o["ws"], stream=self.stream() if stream is None else stream,
                                  workspace_bytes=o["wsn"], stages=stages)
 
-    def live_iteration(self, dl: DeviceLayer) -> None:
+    def live_iteration(self, dl: DeviceLayer, fused: bool = True) -> None:
         """One decoding iteration with a live drafting phase (Sec. 2.3): verify and select at the layer's lengths,
         then per draft step the new token's K/V is appended, the selection grows by it (Sec. 3.2, last sentence)
         and the draft call attends over the grown selection.  The live lengths are rewound first (one small device
-        copy), so every iteration starts from the same state; the appended slots are simply overwritten."""
+        copy), so every iteration starts from the same state; the appended slots are simply overwritten.
+        fused: append and growth in one launch (vegas_append_kv_extend) instead of two calls."""
         st = self.stream()
         a, o = self._addrs(dl), self._own()
         dl.seq_lens_live.copy_(dl.seq_lens)
@@ -190,9 +191,14 @@ class VegasPath:
         sll = dl.seq_lens_live.data_ptr()
         row = dl.k_new[0].numel() * dl.k_new.element_size()
         for s in range(self.G):
-            vb.vegas_append_kv(self.desc_append, dl.k_new.data_ptr() + s * row, dl.v_new.data_ptr() + s * row, 1,
-                               a["bt"], sll, a["k"], a["v"], stream=st)
-            vb.vegas_extend_selection(self.desc_extend, a["bt"], sll, 1, o["st"], o["ssl"], stream=st)
+            if fused:
+                vb.vegas_append_kv_extend(self.desc_append, dl.k_new.data_ptr() + s * row, dl.v_new.data_ptr() + s * row,
+                                          1, a["bt"], sll, a["k"], a["v"], o["st"], o["ssl"],
+                                          self.desc_extend.page_size, stream=st)
+            else:
+                vb.vegas_append_kv(self.desc_append, dl.k_new.data_ptr() + s * row, dl.v_new.data_ptr() + s * row, 1,
+                                   a["bt"], sll, a["k"], a["v"], stream=st)
+                vb.vegas_extend_selection(self.desc_extend, a["bt"], sll, 1, o["st"], o["ssl"], stream=st)
             self.draft(dl, s, st)
 
     def iteration(self, dl: DeviceLayer) -> None:

@@ -20,7 +20,7 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def run_live(L, budget, name, token_granular=False):
+def run_live(L, budget, name, token_granular=False, fused=True):
     G = L.spec.num_queries
     L = synth.with_growth(L, G)
     dl = harness.DeviceLayer.upload(L)
@@ -31,7 +31,7 @@ def run_live(L, budget, name, token_granular=False):
     print(f"[case] live {name}: lens={list(map(int, L.seq_lens[:8]))} budget={budget} P={P}", flush=True)
     # the GPU runs the whole iteration as one stream of calls; the stages are then replayed one by one for comparison
     k0, v0 = dl.k_cache.clone(), dl.v_cache.clone()
-    path.live_iteration(dl)
+    path.live_iteration(dl, fused=fused)      # fused: vegas_append_kv_extend, one launch per step instead of two
     torch.cuda.synchronize()
     final_out = [path.out_draft[s].clone() for s in range(G)]
     final_sel, final_ssl = path.sel_table.cpu().numpy(), path.sel_seq_lens.cpu().numpy()
@@ -95,11 +95,12 @@ LIVE = [
 ]
 
 
+@pytest.mark.parametrize("fused", [True, False], ids=["one_launch", "two_calls"])
 @pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,budget", LIVE, ids=[c[0] for c in LIVE])
-def test_live_iteration_pages(name, B, Hq, Hkv, G, lens, budget):
+def test_live_iteration_pages(name, B, Hq, Hkv, G, lens, budget, fused):
     L = synth.make_random_case(seed=600 + len(name), batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=G,
                                seq_lens=lens, logit_std=1.5, value_std=1.0, outliers=2, outlier_logit=20.0)
-    run_live(L, budget, name)
+    run_live(L, budget, name, fused=fused)
 
 
 @pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,budget", LIVE[:4], ids=[c[0] for c in LIVE[:4]])
@@ -135,3 +136,43 @@ def test_append_refuses_a_sequence_without_room():
     assert list(ref_lens) == [102, 160, 42]
     assert np.array_equal(lens.cpu().numpy(), ref_lens)
     assert np.array_equal(bits_of(dk), kc) and np.array_equal(bits_of(dv), vc)
+
+
+@pytest.mark.parametrize("P", [16, 1])
+def test_fused_append_and_growth_leave_a_refused_sequence_alone(P):
+    """vegas_append_kv_extend: a sequence without room keeps its length, its cache slots AND its selection; the
+    others get exactly what the two separate calls give (the oracle's append followed by its growth step)."""
+    L = synth.make_random_case(seed=43, batch=3, num_q_heads=32, num_kv_heads=8, num_queries=2, seq_lens=[100, 160, 47],
+                               max_blocks=10)
+    rng = np.random.default_rng(6)
+    table = L.block_table.copy()                        # position 48 of the last sequence needs a page of its own
+    table[2, 3] = sorted(set(range(L.num_pages)) - set(table[table >= 0].tolist()))[0]
+    k_new = rng.integers(0, 0x7F00, size=(3, 1, 8, 128), dtype=np.uint16)
+    v_new = rng.integers(0, 0x7F00, size=(3, 1, 8, 128), dtype=np.uint16)
+    dev = torch.device("cuda:0")
+    msb = 12 if P == 16 else 170
+    if P == 16:
+        sel, ssl, _ = O.select_blocks(rng.random((3, 10)).astype(np.float32), table, L.seq_lens, 2, 64, msb)
+    else:
+        sel, ssl, _ = O.select_tokens(rng.standard_normal((3, 160)).astype(np.float32), table, L.seq_lens, 2, 64, msb)
+    desc = vb.make_desc(batch=3, num_q_heads=32, num_kv_heads=8, num_queries=2, max_blocks=10, max_sel_blocks=msb,
+                        max_seq_len=160, num_pages=L.num_pages, softmax_scale=0.1)
+    dk, dv = harness.bf16_to_device(L.k_cache, dev), harness.bf16_to_device(L.v_cache, dev)
+    lens = torch.from_numpy(L.seq_lens.copy()).to(dev)
+    d_sel, d_ssl = torch.from_numpy(sel.copy()).to(dev), torch.from_numpy(ssl.copy()).to(dev)
+    ref_sel, ref_ssl, ref_lens = sel, ssl, L.seq_lens
+    kc, vc = L.k_cache, L.v_cache
+    for step in range(2):                               # 47 -> 48 -> 49: the second step opens a 16-token page
+        vb.vegas_append_kv_extend(desc, harness.bf16_to_device(k_new, dev), harness.bf16_to_device(v_new, dev), 1,
+                                  torch.from_numpy(table).to(dev), lens, dk, dv, d_sel, d_ssl, P)
+        torch.cuda.synchronize()
+        kc, vc, new_lens = O.append_kv(kc, vc, k_new, v_new, table, ref_lens, max_seq_len=160)
+        grown_sel, grown_ssl = O.extend_selection(ref_sel, ref_ssl, table, new_lens, 1, P)
+        # the sequence at its bound was refused: the oracle's growth step would re-add its last position, the call must not
+        grown_sel[1], grown_ssl[1] = ref_sel[1], ref_ssl[1]
+        ref_sel, ref_ssl, ref_lens = grown_sel, grown_ssl, new_lens
+        assert list(ref_lens) == [101 + step, 160, 48 + step]
+        assert np.array_equal(lens.cpu().numpy(), ref_lens)
+        assert np.array_equal(bits_of(dk), kc) and np.array_equal(bits_of(dv), vc)
+        assert np.array_equal(d_sel.cpu().numpy(), ref_sel) and np.array_equal(d_ssl.cpu().numpy(), ref_ssl)
+    assert int(ref_ssl[0]) == int(ssl[0]) + 2 and int(ref_ssl[1]) == int(ssl[1])
