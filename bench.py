@@ -504,11 +504,14 @@ def main() -> int:
 
     K, W = args.steps, args.warmup
 
-    def step(i: int) -> None:
+    def run_one(c) -> None:
         if args.live:
-            path.live_iteration(copies[i % len(copies)])
+            path.live_iteration(c)
         else:
-            path.iteration(copies[i % len(copies)])
+            path.iteration(c)
+
+    def step(i: int) -> None:
+        run_one(copies[i % len(copies)])
 
     for i in range(W):
         step(i)
@@ -608,11 +611,11 @@ def main() -> int:
         per = sorted(a.elapsed_ms(b) * 1e3 for a, b in evs)
         # (2) warm caches: every step reads the same cache copy
         for i in range(W):
-            path.iteration(copies[0])
+            run_one(copies[0])
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(K):
-            path.iteration(copies[0])
+            run_one(copies[0])
         torch.cuda.synchronize()
         warm_us = (time.perf_counter() - t0) / K * 1e6
         # (3) the iteration replayed from ONE captured HIP graph that holds an iteration for every cache copy (a serving
@@ -621,12 +624,12 @@ def main() -> int:
         side.wait_stream(torch.cuda.current_stream(dev))
         with torch.cuda.stream(side):
             for c in copies:
-                path.iteration(c)                      # settle one-time set-up outside capture
+                run_one(c)                             # settle one-time set-up outside capture
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             for c in copies:
-                path.iteration(c)
+                run_one(c)
         torch.cuda.synchronize()
         replays = max(1, K // len(copies))
         for i in range(max(1, W // len(copies))):
