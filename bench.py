@@ -220,12 +220,17 @@ def timeline_table(buf, label: str) -> dict:
     """Per-phase summary of one launch's stamps ([records][8] uint64 at 100 MHz; records never written stay zero):
     event times relative to the first wave's entry, and per-wave phase durations, in microseconds."""
     import numpy as np
-    rec = buf.cpu().numpy().view(np.uint64).reshape(-1, 8)
-    rec = rec[rec[:, 0] > 0].astype(np.float64)
+    raw = buf.cpu().numpy().view(np.uint64).reshape(-1, 8)
+    live = raw[:, 0] > 0
+    rec = raw[live].astype(np.float64)
     if rec.shape[0] == 0:
         return {"kernel": label, "waves": 0}
     t0 = rec[:, 0].min()
     rel = (rec - t0) / 100.0
+    # Workgroup ids are dealt round-robin to the 8 XCDs (record index = 4 * workgroup id + wave): when each XCD's
+    # waves are done streaming, which is what a static partition of the work has to live with.
+    xcd = ((np.nonzero(live)[0] // 4) % 8)
+    by_xcd = [float(rel[xcd == x, 5].mean()) if np.any(xcd == x) else None for x in range(8)]
 
     def summary(col):
         c = np.sort(col)
@@ -233,7 +238,8 @@ def timeline_table(buf, label: str) -> dict:
     events = {name: summary(rel[:, i]) for i, name in enumerate(TIMELINE_EVENTS)}
     phases = {f"{TIMELINE_EVENTS[i]} -> {TIMELINE_EVENTS[i + 1]}": summary(rel[:, i + 1] - rel[:, i]) for i in range(7)}
     return {"kernel": label, "waves": int(rec.shape[0]), "unit": "us",
-            "events_after_first_entry": events, "phase_durations_per_wave": phases}
+            "events_after_first_entry": events, "phase_durations_per_wave": phases,
+            "last_tile_done_mean_by_xcd": by_xcd}
 
 
 def run_timeline(args, torch, vb, harness, synth) -> int:
@@ -271,6 +277,9 @@ def run_timeline(args, torch, vb, harness, synth) -> int:
             print(f"   at   {name:40s} min {v['min']:6.2f}  p50 {v['p50']:6.2f}  p90 {v['p90']:6.2f}  max {v['max']:6.2f}", file=sys.stderr)
         for name, v in k.get("phase_durations_per_wave", {}).items():
             print(f"   took {name:80s} p50 {v['p50']:6.2f}  p90 {v['p90']:6.2f}  max {v['max']:6.2f}", file=sys.stderr)
+        if k.get("last_tile_done_mean_by_xcd"):
+            print("   last tile done, mean over the waves of XCD 0..7 (workgroup id mod 8): " +
+                  "  ".join("   -  " if v is None else f"{v:6.2f}" for v in k["last_tile_done_mean_by_xcd"]), file=sys.stderr)
     print(json.dumps(out), flush=True)
     return 0
 
