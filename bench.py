@@ -564,12 +564,14 @@ def main() -> int:
         roofline["kernel_us"] = v_us
         roofline["achieved"] = verify_bytes / (v_us * 1e-6) / 1e9
         roofline["frac"] = roofline["achieved"] / HBM_PEAK_GBS
-        d_us = kernel_leg(lambda i: path.draft(copies[i % len(copies)], i % G, stages=vb.STAGE_STREAM), K)
+        d_reps = max(K, 100)              # (a 7 us kernel: twenty launches are too few for a stable mean)
+        d_us = kernel_leg(lambda i: path.draft(copies[i % len(copies)], i % G, stages=vb.STAGE_STREAM), d_reps)
         dkernel = "attn_draft16_kernel" if spec.num_q_heads // spec.num_kv_heads <= 16 and not token else "attn_split_kernel"
         roofline_draft = {"bound": "hbm", "kernel": dkernel + " (KV-streaming kernel of vegas_draft_attention)",
                           "kernel_us": d_us, "achieved": draft_bytes / (d_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                           "unit": "GB/s", "frac": draft_bytes / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                          "bytes_per_launch": draft_bytes, "traffic": None}
+                          "bytes_per_launch": draft_bytes, "traffic": None, "launches": d_reps}
+        roofline["launches"] = K
         # The yardstick: a kernel that only reads the same K and V caches (cold, rotating over the same copies), plain
         # coalesced 16-byte non-temporal loads, best of several grid sizes.  What it reaches is what this memory system
         # gives a launch of this footprint; the verification kernel is held against it beside the published peak.

@@ -94,7 +94,10 @@ typedef struct vegas_desc {
   int32_t kv_chunk_tokens; /* tokens of one sequence handled by one workgroup (a multiple of 32); 0 = the library
                               chooses: from batch, heads and max_seq_len on the host, or, for a verification call
                               on a batch of 2..64 sequences, per sequence on the GPU from seq_lens, so that all
-                              workgroups stream about the same number of tokens however loose max_seq_len is */
+                              workgroups stream about the same number of tokens however loose max_seq_len is.
+                              A sequence's chunks are a dimension of the launch grid: a chunk length under which
+                              max_seq_len would need more than 65535 chunks (times up to four 32-row blocks where a
+                              KV head carries more than 64 rows) is VEGAS_ERR_UNSUPPORTED */
   int32_t reserved;        /* must be 0 */
   float   softmax_scale;   /* Eq. 1's 1/sqrt(d) */
   int32_t score_metric;    /* VEGAS_METRIC_*: what vegas_verify_attention writes to block_scores */
@@ -205,7 +208,7 @@ int vegas_select_tokens(const vegas_desc* desc, const float* token_scores,
  *   k_cache / v_cache                          written in place
  * A sequence for which seq_lens[b] + num_new would pass min(max_seq_len, 16 * max_blocks) takes nothing and keeps
  * its length.  Follow with vegas_extend_selection(desc, ..., num_new, ...) so that the next draft call sees the
- * new tokens.  One small kernel (one workgroup per sequence); no workspace.  desc->page_size is 16.
+ * new tokens (or take vegas_append_kv_extend, which does both in one launch).  One small kernel (one workgroup per sequence); no workspace.  desc->page_size is 16.
  */
 int vegas_append_kv(const vegas_desc* desc, const void* k_new, const void* v_new, int32_t num_new,
                     const int32_t* block_table, int32_t* seq_lens, void* k_cache, void* v_cache, void* hip_stream);
