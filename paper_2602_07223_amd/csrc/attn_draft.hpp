@@ -200,16 +200,23 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
     float pw[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) pw[i] = fast_exp2(__builtin_fmaf(st[i >> 2][i & 3], p.scale_log2e, -m_use));
-    l_run = l_run * alpha + ((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7]));
+    // The row sum adds the weights as the second contraction sees them, i.e. rounded to bf16: numerator and
+    // denominator of Eq. 1 then carry the same rounding errors, which cancel where one key dominates (the output
+    // is a convex combination of V rows again) and do no harm elsewhere.
+    bf16x8 pb;
+    float pr[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      pb[i] = static_cast<__bf16>(pw[i]);
+      pr[i] = static_cast<float>(pb[i]);
+    }
+    l_run = l_run * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7]));
     const float m_before = m_run;
     m_run = m_new;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f && m_before != -INFINITY) != 0) {   // (no key seen yet: sums still zero)
 #pragma unroll
       for (int blk = 0; blk < NBLK; ++blk) acc[blk] *= alpha;
     }
-    bf16x8 pb;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) pb[i] = static_cast<__bf16>(pw[i]);
     if (tail) {                              // slots past the end may hold anything: feed zeros
 #pragma unroll
       for (int e = 0; e < 8; ++e)

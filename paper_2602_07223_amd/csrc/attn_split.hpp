@@ -495,7 +495,17 @@ __global__ __launch_bounds__(NW * 64, WPS) void attn_split_kernel(VEGAS_SPLIT_HO
       float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) { ps0 += pr[i]; ps1 += pr[8 + i]; }
-      l_run[nb] = l_run[nb] * alpha + (ps0 + ps1);
+      if constexpr (!CAUSAL && COLLECT == 0) {
+        // Draft calls: the row sum adds the weights as the second contraction sees them (rounded to bf16), so that
+        // numerator and denominator of Eq. 1 carry the same rounding errors; they cancel where one key dominates.
+        // (Verification keeps the unrounded sums: the page scores are formed from them.)
+        float rs = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) rs += static_cast<float>(static_cast<__bf16>(pr[i]));
+        l_run[nb] = l_run[nb] * alpha + rs;
+      } else {
+        l_run[nb] = l_run[nb] * alpha + (ps0 + ps1);
+      }
       float m_run_before[NB];
       m_run_before[nb] = m_run[nb];
       m_run[nb] = m_new;

@@ -83,7 +83,8 @@ class VegasPath:
                                         **common)
         if token_granular:
             draft_common = dict(common, max_blocks=self.max_sel_blocks, num_pages=num_pages * PAGE)
-            self.desc_draft = vb.make_desc(max_seq_len=min(self.max_sel_blocks, max_seq_len), collect_rows=vb.COLLECT_NONE,
+            # (a selection that holds the whole sequence grows past max_seq_len while drafting)
+            self.desc_draft = vb.make_desc(max_seq_len=min(self.max_sel_blocks, max_seq_len + growth), collect_rows=vb.COLLECT_NONE,
                                            kv_chunk_tokens=draft_chunk, page_size=1, **draft_common)
         else:
             draft_len = min(self.max_sel_blocks * PAGE, max_blocks * PAGE)

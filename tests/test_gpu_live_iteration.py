@@ -103,7 +103,14 @@ def test_live_iteration_pages(name, B, Hq, Hkv, G, lens, budget, fused):
     run_live(L, budget, name, fused=fused)
 
 
-@pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,budget", LIVE[:4], ids=[c[0] for c in LIVE[:4]])
+LIVE_TOKENS = LIVE[:4] + [
+    # every token selected: the selection then grows past the longest sequence of the batch
+    ("all_tokens_selected", 2, 64, 8, 6, [20, 10], 200),
+    ("all_tokens_selected_one_sequence", 1, 16, 4, 5, [58], 200),
+]
+
+
+@pytest.mark.parametrize("name,B,Hq,Hkv,G,lens,budget", LIVE_TOKENS, ids=[c[0] for c in LIVE_TOKENS])
 def test_live_iteration_tokens(name, B, Hq, Hkv, G, lens, budget):
     """The paper's own granularity: token selection from averaged logits, one-token pages, growing by one entry a step."""
     L = synth.make_random_case(seed=650 + len(name), batch=B, num_q_heads=Hq, num_kv_heads=Hkv, num_queries=G,
