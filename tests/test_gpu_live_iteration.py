@@ -33,6 +33,11 @@ def run_live(L, budget, name, token_granular=False, fused=True):
     k0, v0 = dl.k_cache.clone(), dl.v_cache.clone()
     path.live_iteration(dl, fused=fused)      # fused: vegas_append_kv_extend, one launch per step instead of two
     torch.cuda.synchronize()
+    # nothing the draft calls were given lay outside what their descriptor lets them see (they would clamp silently)
+    err = torch.zeros(1, dtype=torch.int32, device=path.device)
+    vb.vegas_debug_check_tables(path.desc_draft, vb.TABLE_SELECTION, path.sel_table, path.sel_seq_lens, err)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0, f"{name}: the grown selection trips the table checker: bits {int(err.item())}"
     final_out = [path.out_draft[s].clone() for s in range(G)]
     final_sel, final_ssl = path.sel_table.cpu().numpy(), path.sel_seq_lens.cpu().numpy()
     final_k, final_lens = bits_of(dl.k_cache), dl.seq_lens_live.cpu().numpy()
