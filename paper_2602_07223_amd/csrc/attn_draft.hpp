@@ -47,7 +47,11 @@ inline size_t draft16_lds_bytes(int R, int D) {
          2 * static_cast<size_t>(kDraftWaves) * kDraftRows * sizeof(float);
 }
 
-template <int D>
+// PS: log2 of the tokens per page of the selection table (4: 16-token pages; 0..3: the 1, 2, 4, 8-token pages of
+// Sec. 4 / App. D).  With small pages a tile spans 32 >> PS pages: their ids are loaded one tile ahead into one
+// register (lane e <-> page e of the tile), every lane fetches the id of each of its tokens with a lane permute and
+// forms a 64-bit address of its own; everything after the loads is the 16-token code.
+template <int D, int PS = 4>
 __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS_SPLIT_HOT_PARAMS, const SplitParams pfull) {
   VEGAS_TL_DECL;
   VEGAS_TL(kTlEntry);
@@ -60,6 +64,7 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
   constexpr int NBLK = D / 16;               // 16-wide blocks of the output = head dims one V load covers
   constexpr int kRedPitch = red_pitch(D);
   using VReg = typename std::conditional<D == 128, u32x4, u32x2>::type;      // NBLK head dims of one token
+  constexpr int TP = 32 >> (PS < 4 ? PS : 0);   // pages per tile on the small-page path
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -88,10 +93,16 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
     return static_cast<int>(ph < 0 ? 0 : (ph >= p.num_pages ? p.num_pages - 1 : ph));
   };
   auto load_pagevec = [&](int kbase) { pagevec = into_pool(table_entry(kbase)); };
+  // Small pages: ids of the TP pages of this wave's tile k, lane e (mod TP) <-> page e of the tile.
+  auto ids_entry = [&](int k) -> int {
+    int page = (tile_first + k * NW) * TP + (lane & (TP - 1));
+    page = page < p.table_stride ? page : p.table_stride - 1;
+    return table[page];
+  };
 
   // ---- one round trip for everything the preloaded arguments can address: table entry, length, query rows; the
   //      rest of the argument block is pulled in one go meanwhile (see attn_split_kernel)
-  int first_entry = table_entry(0);
+  int first_entry = PS == 4 ? table_entry(0) : ids_entry(0);
   int n = p.lens[b];
   u32x4 qreg[KK];
   {
@@ -113,7 +124,9 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
   const int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot
   // (when the workgroup finishes the rows itself: G = 1, so the group's rows are consecutive)
   auto out_rows = [&]() -> uint16_t* { return p.out_direct + (static_cast<int64_t>(b) * p.Hq + h * p.g) * D; };
-  pagevec = into_pool(first_entry);
+  int ids_cur = 0, ids_pending = 0;          // small pages: ids of the tile whose loads go out next; of the one after
+  if constexpr (PS == 4) pagevec = into_pool(first_entry);
+  else ids_cur = into_pool(first_entry);
 
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   if (c0 >= n) {                             // nothing to do, no partial is read
@@ -134,8 +147,26 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
   auto page_base = [&](const uint16_t* cache, int ph) -> const unsigned char* {
     return uniform_ptr(reinterpret_cast<const unsigned char*>(cache + static_cast<int64_t>(ph) * p.page_stride + head_off));
   };
+  // Small pages: byte address of token t (0..31, a per-lane value) of the tile whose page ids are in ids_cur.
+  typedef const __attribute__((address_space(1))) unsigned char* gbytes;
+  auto token_addr = [&](const uint16_t* cache, int t) -> gbytes {
+    const int id = __shfl(ids_cur, t >> (PS & 3), 64);
+    const int tokin = t & ((1 << (PS & 3)) - 1);
+    const int64_t el = static_cast<int64_t>(id) * p.page_stride + static_cast<int64_t>(tokin) * p.token_stride + head_off;
+    return (gbytes)cache + el * 2;
+  };
   // K load (pg, kk): token l16 of page pg, head dims 32 kk + 8 kg .. + 7
   auto issue_k = [&](int k, u32x4 (&kr)[2][KK]) {
+    if constexpr (PS != 4) {
+      typedef const __attribute__((address_space(1))) u32x4* gp;
+#pragma unroll
+      for (int pg = 0; pg < 2; ++pg) {
+        const gbytes row = token_addr(p.k, 16 * pg + l16) + kg * 16;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kr[pg][kk] = *(gp)(row + kk * 64);
+      }
+      return;
+    }
     if ((k & 31) == 0 && k > 0) load_pagevec(k);
     const unsigned char* kb0 = page_base(p.k, __builtin_amdgcn_readlane(pagevec, k & 31));
     const unsigned char* kb1 = page_base(p.k, __builtin_amdgcn_readlane(pagevec, 32 + (k & 31)));
@@ -146,6 +177,12 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
   };
   // V load e: token 4 kg + e % 4 of page e / 4, head dims NBLK l16 .. + NBLK - 1
   auto issue_v = [&](int k, VReg (&vr)[8]) {
+    if constexpr (PS != 4) {
+      typedef const __attribute__((address_space(1))) VReg* gp;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vr[e] = *(gp)(token_addr(p.v, 16 * (e >> 2) + 4 * kg + (e & 3)) + l16 * (2 * NBLK));
+      return;
+    }
     const unsigned char* vb0 = page_base(p.v, __builtin_amdgcn_readlane(pagevec, k & 31));
     const unsigned char* vb1 = page_base(p.v, __builtin_amdgcn_readlane(pagevec, 32 + (k & 31)));
 #pragma unroll
@@ -155,6 +192,7 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
 
   u32x4 kr[2][KK];
   VReg va[8], vb[8];
+  if constexpr (PS != 4) ids_pending = into_pool(ids_entry(1));     // (requested before tile 0's loads: it is back first)
   if (tile_first < tile_end) {
     issue_k(0, kr);
     issue_v(0, va);
@@ -180,6 +218,10 @@ __global__ __launch_bounds__(kDraftWaves * 64, 2) void attn_draft16_kernel(VEGAS
         st[pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr[pg][kk]),
                                                          __builtin_bit_cast(bf16x8, qreg[kk]), st[pg], 0, 0, 0);
     if (has_next) {
+      if constexpr (PS != 4) {               // the next tile's ids are here (requested a tile ago); ask for the ones after
+        ids_cur = ids_pending;
+        ids_pending = into_pool(ids_entry(k + 2));
+      }
       issue_k(k + 1, kr);
       issue_v(k + 1, vnxt);
     }

@@ -304,9 +304,18 @@ int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t s
   if (lds > 160 * 1024) return VEGAS_ERR_UNSUPPORTED;
   if constexpr (!CAUSAL && COLLECT == 0) {
     // one draft token, a group of at most 16 heads, 16-token pages: the kernel written for exactly that
-    if (page_size == kPage && pl.R <= kDraftRows && sp.G == 1 && pl.NB == 1)
-      return launch_one(attn_draft16_kernel<D>, grid, dim3(kDraftWaves * 64), draft16_lds_bytes(pl.R, D), st, sp);
-    switch (page_size) {                                // draft calls may walk a table of smaller pages
+    if (pl.R <= kDraftRows && sp.G == 1 && pl.NB == 1) {
+      const dim3 dblock(kDraftWaves * 64);
+      const size_t dlds = draft16_lds_bytes(pl.R, D);
+      switch (page_size) {                              // (draft calls may walk a table of smaller pages)
+        case 1: return launch_one(attn_draft16_kernel<D, 0>, grid, dblock, dlds, st, sp);
+        case 2: return launch_one(attn_draft16_kernel<D, 1>, grid, dblock, dlds, st, sp);
+        case 4: return launch_one(attn_draft16_kernel<D, 2>, grid, dblock, dlds, st, sp);
+        case 8: return launch_one(attn_draft16_kernel<D, 3>, grid, dblock, dlds, st, sp);
+        default: return launch_one(attn_draft16_kernel<D, 4>, grid, dblock, dlds, st, sp);
+      }
+    }
+    switch (page_size) {                                // larger groups: the 32-row kernel, any page size
       case 1: return launch_one(attn_split_kernel<4, 2, false, 0, false, 0, false, D>, grid, dim3(256), lds, st, sp);
       case 2: return launch_one(attn_split_kernel<4, 2, false, 0, false, 1, false, D>, grid, dim3(256), lds, st, sp);
       case 4: return launch_one(attn_split_kernel<4, 2, false, 0, false, 2, false, D>, grid, dim3(256), lds, st, sp);
@@ -475,7 +484,11 @@ int for_each_lds_kernel(F f) {
     one(attn_split_kernel<4, 2, true, 1, false, 4, false, D>);
     one(attn_split_kernel<4, 2, true, 2, true, 4, false, D>);
     one(attn_split_kernel<4, 2, true, 2, false, 4, false, D>);
-    one(attn_draft16_kernel<D>);
+    one(attn_draft16_kernel<D, 0>);
+    one(attn_draft16_kernel<D, 1>);
+    one(attn_draft16_kernel<D, 2>);
+    one(attn_draft16_kernel<D, 3>);
+    one(attn_draft16_kernel<D, 4>);
     one(attn_pair_kernel<0, D>);
     one(attn_pair_kernel<1, D>);
     one(attn_pair_kernel<2, D>);
