@@ -62,8 +62,11 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   const int pr = wave >> 1, role = wave & 1;
   const int half = lane >> 5;
   const int l32 = lane & 31;
-  const int h = blockIdx.x;                  // grid (KV head, chunk, sequence): see attn_split_kernel
-  int split = blockIdx.y;
+  // Grid (chunk, KV head, sequence): workgroup ids go round-robin to the XCDs, so with chunks fastest every XCD works
+  // on all KV heads (measured 3.5 % faster for this kernel than one XCD per head; the other streaming kernels, which
+  // are shorter, keep heads fastest).
+  const int h = blockIdx.y;
+  int split = blockIdx.x;
   int b = blockIdx.z;
   int chunk_tokens = p.chunk_tokens;
   int64_t pbase = (static_cast<int64_t>(b) * p.Hkv + h) * p.nsplit + split;   // this workgroup's partial slot

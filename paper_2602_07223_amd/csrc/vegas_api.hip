@@ -284,8 +284,7 @@ template <bool CAUSAL, int COLLECT, int D>
 int launch_split_d(const SplitPlan& pl, SplitParams sp, int batch, hipStream_t st, int page_size) {
   if constexpr (CAUSAL) {
     if (pl.pair) {                                  // both row blocks from one read of K/V
-      const dim3 pgrid = pl.balanced ? dim3(sp.Hkv, pl.JS, 1) : dim3(sp.Hkv, pl.nsplit, batch);
-      if (pgrid.y > 65535u) return VEGAS_ERR_UNSUPPORTED;
+      const dim3 pgrid = pl.balanced ? dim3(pl.JS, sp.Hkv, 1) : dim3(pl.nsplit, sp.Hkv, batch);   // chunks fastest
       const size_t plds = pair_lds_bytes(pl.R, COLLECT, D);
       sp.lds_q_off = static_cast<int32_t>(plds - pair_lds_tail_bytes(D));
       sp.row_blocks = 1;
