@@ -50,8 +50,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # runs, each scaled by what the same counter reads for a plain 64 MiB copy (factors 1.9990 and 1.0); the figures are
 # the `traffic_bytes_per_launch[...]` lines of the two summaries (tests/test_profiles_match_bench.py compares them).
 VERIFY_TRAFFIC_BYTES = {
-    "ctx32k": 138574111,       # (131447 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
-    "ragged16": 2428279638,    # (2305890 KiB fetched + 65477 KiB written), profiles/ragged16_hbm_traffic_pmc.md
+    "ctx32k": 138574632,       # (131447 KiB fetched + 3880 KiB written), profiles/ctx32k_hbm_traffic_pmc.md
+    "ragged16": 2434575050,    # (2312055 KiB fetched + 65460 KiB written), profiles/ragged16_hbm_traffic_pmc.md
 }
 DEFAULT_WORKLOAD = "ctx32k"
 ROTATE_BYTES = 1.2e9           # rotate cache copies up to about this much K+V in total
