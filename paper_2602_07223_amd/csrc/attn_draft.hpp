@@ -1,5 +1,5 @@
 // Draft-attention streaming kernel for up to 16 query rows per KV head (one draft token, GQA groups of up to 16
-// heads), 16-token pages, gfx950.
+// heads), gfx950; 16-token pages, or the 1, 2, 4, 8-token pages of Sec. 4 / App. D through a template argument.
 //
 // Same arithmetic, chunking, partial-result layout and merge kernels as attn_split_kernel (Eq. 1 over the selected
 // pages of Sec. 3.2, split over the selection), but shaped for a call that is a few microseconds long and whose
