@@ -10,6 +10,11 @@
  *   2. vegas_select_blocks     top-k of those criticalities (the argmax of Eq. 2 / Eq. 3);
  *   3. vegas_draft_attention   attention of one draft token over the selected pages only, done as
  *                              paged attention whose page list is the selection (Sec. 4, App. D).
+ * Around them: vegas_select_tokens (the paper's own granularity: single tokens from averaged logits, Sec. 3.3);
+ * vegas_append_kv, vegas_extend_selection and vegas_append_kv_extend (the step between two draft calls of a live
+ * drafting phase: Sec. 2.3, Sec. 3.2 last sentence); vegas_draft_attention_static (the draft call for callers that
+ * cannot allocate device memory); vegas_init, vegas_workspace_bytes, vegas_strerror; and the vegas_debug_* entry
+ * points (parts of a call for benchmarks, a table checker, a plain-read yardstick, phase stamps of profiling builds).
  *
  * Conventions shared by every call
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library never allocates,
