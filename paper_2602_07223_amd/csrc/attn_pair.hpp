@@ -35,6 +35,8 @@ constexpr int kPairs = 2;
 
 template <int COLLECT, int D>
 __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPLIT_HOT_PARAMS, const SplitParams pfull) {
+  VEGAS_TL_DECL;                             // (profiling builds: per-wave phase stamps, see vegas_common.hpp)
+  VEGAS_TL(kTlEntry);
   SplitParams p = pfull;                     // (see attn_split_kernel: the preloaded arguments)
   VEGAS_SPLIT_HOT_ASSIGN(p);
   static_assert(D == 128 || D == 64, "head dimension");
@@ -102,6 +104,7 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   int n = p.lens[b];
   n = n < 0 ? 0 : (n > p.max_tokens ? p.max_tokens : n);
   if (c0 >= n) return;                       // whole workgroup: nothing to do, no partial is read
+  VEGAS_TL(kTlLength);
   const int c1 = min(c0 + chunk_tokens, n);
   const int nblk = (n + kPage - 1) / kPage;
   const int tile_end = (c1 + kTile - 1) / kTile;
@@ -143,10 +146,12 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   VReg vr0[8], vr1[8];
   issue(0, kr0, vr0);
   issue(1, kr1, vr1);
+  VEGAS_TL(kTlLoadsIssued);
 
   // ---- query rows -> LDS [64 rows][CH chunks of 16 B], padded rows; rows past R are zero.
   // COLLECT == 2: rows R (high part) and R + 1 (low part) carry the sum of the collected query rows.
   load_queries_to_lds<D>(qlds, p, b, h, 64, 0, p.R, COLLECT == 2, tid, NW * 64);
+  VEGAS_TL(kTlQueries);                      // (queries written; the first step's barrier publishes them)
   const int xr = p.R - row0;                 // COLLECT 2: column of the high-part sum row inside block 1
   const bool has_extra = COLLECT == 2 && role == 1;
   // last visible token of this lane's row: the causal bound, and nothing past this workgroup's chunk
@@ -302,6 +307,9 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
       float* dst = ok ? col_dst + k * (kTile * NP) : trash;
       *dst = tok_lds[col_elem] + tok_lds[kTile * NP + col_elem];
     }
+#ifdef VEGAS_TIMELINE
+    if (tl_stamps[kTlFirstTile] == 0) VEGAS_TL(kTlFirstTile);
+#endif
   };
 
   // ---- stream the chunk: T steps (even), the two register sets in turn; the last two steps issue no loads
@@ -320,8 +328,10 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
   // ---- merge the two pairs, one row block after the other (the merge buffer aliases the tiles and the parked
   //      values): row maxima meet in LDS, every wave rescales, the waves of the block park their rows as
   //      [pair][row][d], all threads add the pairs and write the block's rows of the workgroup's partial.
+  VEGAS_TL(kTlStreamed);
   if (half == 0) sm_m[pr * 64 + row0 + l32] = m_run;
   __syncthreads();                           // also: the collected values have been read out of LDS
+  VEGAS_TL(kTlMerged);
   const float mw = fmaxf(sm_m[row0 + l32], sm_m[64 + row0 + l32]);
   const float m_fin = (mw == -INFINITY) ? 0.f : mw;
   const float sc = fast_exp2(m_run - m_fin);
@@ -355,6 +365,8 @@ __global__ __launch_bounds__(kPairWaves * 64, 2) void attn_pair_kernel(VEGAS_SPL
     const float m2 = fmaxf(sm_m[tid], sm_m[64 + tid]);
     p.part_ml[pbase * p.R + tid] = make_float2(m2, sm_l[tid] + sm_l[64 + tid]);
   }
+  VEGAS_TL(kTlExit);
+  VEGAS_TL_FLUSH(p.timeline, NW);
 }
 
 // Dynamic LDS bytes of attn_pair_kernel for R rows per KV head.
